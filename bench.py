@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the ABFT-checked u8 x s8 -> s32 GEMM on one MI355X.
+
+A step is one pass of the hot path over one batch of synthetic input already resident
+in HBM: the checked GEMM call (product with the checksum column folded in, row sums,
+comparison, flags, store of C_temp, plus the requantization epilogue for the workloads
+that have one).  The encode/pack of the weight is done once outside the timed region,
+as the method prescribes (the weight is encoded once for many products), and its time
+is reported separately as pack_ms.
+
+Prints ONE JSON line.  `value` is checked-GEMM TOPS (2*M*N*K per step; the checksum
+columns are not counted as useful work).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
+
+
+def algorithmic_bytes(wl, want_c=True, want_q=False):
+    """Bytes the method itself must move per GEMM: A, B, the checksum column (4 bytes
+    per k), the outputs and the flags (+ column offsets and multipliers when requantizing)."""
+    M, N, K = wl.M, wl.N, wl.K
+    b = M * K + K * N + 4 * K + 4 * M
+    if want_c:
+        b += 4 * M * N
+    if want_q:
+        b += M * N + 4 * N + 4 * N
+    return b
+
+
+class Job:
+    """Device-resident operands and outputs of one workload."""
+
+    def __init__(self, b, torch, cfg, n_rot=1):
+        from paper_2103_00130_amd import workloads as w
+        self.b, self.torch = b, torch
+        self.ops = w.make_operands(cfg)
+        self.wl = wl = self.ops.wl
+        self.A = torch.from_numpy(self.ops.A).cuda()
+        B = torch.from_numpy(self.ops.B).cuda()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.Bp = [b.abft_pack_b_checksum(B)]
+        torch.cuda.synchronize()
+        self.pack_ms = (time.perf_counter() - t0) * 1e3
+        t0 = time.perf_counter()
+        for _ in range(n_rot - 1):      # distinct copies so that caches cannot hold the weight
+            self.Bp.append(b.abft_pack_b_checksum(B))
+        torch.cuda.synchronize()
+        if n_rot > 1:
+            self.pack_ms = (time.perf_counter() - t0) * 1e3 / (n_rot - 1)
+        self.C = torch.empty((wl.M, wl.N), dtype=torch.int32, device="cuda")
+        self.flags = torch.empty(wl.M, dtype=torch.int32, device="cuda")
+        self.cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+        self.ws = b.Workspace(wl.M, self.Bp[0])
+        self.rq = self.Cq = None
+        if self.ops.mult is not None:
+            self.mult = torch.from_numpy(self.ops.mult).cuda()
+            self.rq = b.make_requant(wl.zA, wl.zC, self.mult)
+            self.Cq = torch.empty((wl.M, wl.N), dtype=torch.uint8, device="cuda")
+        self.i = 0
+
+    def step(self, check=True, inj=None, n_inj=0, variant=0):
+        b = self.b
+        Bp = self.Bp[self.i % len(self.Bp)]
+        self.i += 1
+        b.abft_gemm_u8s8s32_checked(self.A, Bp, self.C, self.flags, self.cnt, rq=self.rq, Cq=self.Cq, inj=inj,
+                                    n_inj=n_inj, flags=(b.ABFT_CHECK if check else b.ABFT_NOCHECK) | variant,
+                                    workspace=self.ws.tensor)
+
+    def time_steps(self, steps, warmup, check=True, variant=0):
+        """Average milliseconds per step: HIP events on the launching stream around `steps` launches."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step(check, variant=variant)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            self.step(check, variant=variant)
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        return e0.elapsed_time(e1) / steps, wall_ms
+
+
+def detection_sample(job, n=200):
+    """Seeded single-bit flips in C accumulators; returns (detected, corrupted, false_pos_rows)."""
+    import numpy as np
+    from paper_2103_00130_amd import workloads as w
+    torch, b, wl = job.torch, job.b, job.wl
+    r, c, bit = w.draw_flips(wl.index, "C", n)
+    detected = wrong_rows = 0
+    for t in range(n):
+        inj = b.make_injections([(int(r[t]), int(c[t]), 1 << int(bit[t]))])
+        job.step(True, inj=inj, n_inj=1)
+        f = job.flags
+        hit = int(f[int(r[t])].item())
+        total = int(job.cnt.item())
+        detected += hit
+        wrong_rows += total - hit
+    return detected, n, wrong_rows
+
+
+def cpu_baseline(job, target_s=12.0):
+    """The CPU oracle as it stands, timed on a bounded row sample of the same workload."""
+    import numpy as np
+    from oracle import abft_oracle as oracle
+    wl, ops = job.wl, job.ops
+    probe_rows = min(wl.M, 64)
+    t0 = time.perf_counter()
+    oracle.gemm_u8s8s32(ops.A[:probe_rows], ops.B)
+    dt = time.perf_counter() - t0
+    rows = int(min(wl.M, max(probe_rows, probe_rows * target_s / max(dt, 1e-6))))
+    A = np.ascontiguousarray(ops.A[:rows])
+    t0 = time.perf_counter()
+    S = oracle.b_checksum(ops.B)
+    C = oracle.gemm_u8s8s32(A, ops.B)
+    chk = oracle.row_checksum(A, S)
+    rs = oracle.row_sums(C)
+    oracle.compare(rs, chk)
+    dt = time.perf_counter() - t0
+    return {"value": 2.0 * rows * wl.N * wl.K / dt / 1e12, "unit": "TOPS", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": f"first {rows} of {wl.M} rows of A against the full B "
+            f"(checksum, product, row sums, comparison), {dt:.1f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=4, help="index into the five workloads (default: dense 4096^3)")
+    ap.add_argument("--others", action="store_true", help="also time the other workloads (reported under 'others')")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-detection", action="store_true")
+    ap.add_argument("--variant", type=lambda s: int(s, 0), default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2103_00130_amd import binding as b     # fails loudly if the HIP library is missing
+    from paper_2103_00130_amd import workloads as w
+    torch.cuda.set_device(0)
+
+    def measure(cfg, steps, warmup, variant=0):
+        wl = w.WORKLOADS[cfg]
+        hbm_bound = wl.M <= 64
+        # HBM-bound shapes: rotate through enough packed copies of the weight to exceed the caches
+        n_rot = max(1, (768 << 20) // (wl.K * wl.N)) if hbm_bound else 1
+        n_rot = min(n_rot, 128)
+        job = Job(b, torch, cfg, n_rot=n_rot)
+        ms_c, wall_c = job.time_steps(steps, warmup, True, variant)
+        ms_u, _ = job.time_steps(steps, warmup, False, variant)
+        ms_c2, _ = job.time_steps(steps, warmup, True, variant)
+        ms_u2, _ = job.time_steps(steps, warmup, False, variant)
+        ms_c, ms_u = min(ms_c, ms_c2), min(ms_u, ms_u2)
+        ops_per_step = 2.0 * wl.M * wl.N * wl.K
+        res = {
+            "workload": wl.name, "M": wl.M, "N": wl.N, "K": wl.K, "requant": wl.requant,
+            "ms_per_step": ms_c, "tops_checked": ops_per_step / ms_c / 1e9, "tops_unchecked": ops_per_step / ms_u / 1e9,
+            "abft_overhead_pct": 100.0 * (ms_c - ms_u) / ms_u, "pack_ms": job.pack_ms, "weight_copies_rotated": n_rot,
+            "host_wall_ms_per_step": wall_c,
+        }
+        if hbm_bound:
+            by = algorithmic_bytes(wl, True, job.rq is not None)
+            res["roofline"] = {"bound": "hbm", "achieved": by / ms_c / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                               "frac": by / ms_c / 1e6 / PEAK_HBM_GBS, "traffic": None}
+        else:
+            res["roofline"] = {"bound": "mfma", "achieved": ops_per_step / ms_c / 1e9 / 1e3, "peak": PEAK_INT8_TOPS / 1e3,
+                               "unit": "POP/s", "frac": ops_per_step / ms_c / 1e9 / PEAK_INT8_TOPS, "traffic": None}
+        return job, res
+
+    job, main_res = measure(args.workload, args.steps, args.warmup, args.variant)
+    wl = job.wl
+    out = {
+        "metric": "checked u8s8s32 GEMM TOPS, ABFT overhead % vs unchecked, bit-flip detection %",
+        "value": main_res["tops_checked"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": wl.name, "M": wl.M, "N": wl.N, "K": wl.K, "requant": wl.requant,
+                   "baseline_config_index": wl.index},
+        "abft_overhead_pct": main_res["abft_overhead_pct"], "tops_unchecked": main_res["tops_unchecked"],
+        "pack_ms": main_res["pack_ms"], "roofline": main_res["roofline"],
+    }
+    if not args.no_detection:
+        det, n, wrong = detection_sample(job, 200)
+        out["detection_pct"] = 100.0 * det / n
+        out["detection_sample"] = f"{n} seeded single-bit flips in C accumulators, one per launch; " \
+                                  f"{wrong} rows flagged other than the injected one"
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(job)
+    if args.others:
+        out["others"] = []
+        for cfg in range(len(w.WORKLOADS)):
+            if cfg == args.workload:
+                continue
+            _, r = measure(cfg, args.steps, args.warmup)
+            out["others"].append(r)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

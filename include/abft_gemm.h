@@ -1,0 +1,172 @@
+/*
+ * libabftgemm: ABFT-checked u8 x s8 -> s32 GEMM for AMD MI355X (gfx950).
+ *
+ * The operation is Algorithm 1 of arXiv 2103.00130 ("ABFT for low-precision
+ * GEMM", Section IV) on the quantized product of Section III (Eq. 1): the
+ * weight matrix B is encoded once with its checksum column S_B = B e
+ * (Section IV-A-1: only B is encoded), the checksum is packed together with B
+ * (Section IV-A-3) so that C_temp = A * [B | S_B] comes out of one pass, and
+ * every row of the 32-bit intermediate is verified with the row identity of
+ * Eq. 2b before requantization (Section IV-B).  One deliberate difference from
+ * the printed algorithm: the checksum column is kept exact (int32, carried
+ * through the int8 matrix cores as four signed base-256 digits) and the
+ * comparison is an equality of wrap-around int32 values (mod 2^32) rather
+ * than mod 127.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer owned by the caller unless a comment
+ *     says "host".  Matrices are row-major with a leading dimension in
+ *     elements.  `stream` is a hipStream_t passed as void* (NULL = default
+ *     stream).  Calls enqueue work on `stream` and return; they never
+ *     synchronise.  Only abft_pack_b_checksum / abft_packed_b_destroy
+ *     allocate or free device memory.
+ *   - Return value: ABFT_OK, or a negative code for a usage or runtime error;
+ *     abft_last_error() then gives a message (thread-local, host).  Nothing is
+ *     enqueued when a call returns ABFT_EINVAL or ABFT_EUNSUPPORTED.
+ *   - A DETECTED SOFT ERROR IS NOT AN ERROR RETURN.  It is data: row_flags and
+ *     err_count, the "number of corrupted rows" output of Algorithm 1.
+ *   - B is symmetric-quantized (zero point 0): the row-offset term
+ *     alpha_A beta_B (A_I e_k) e_n^T of Eq. 1 is not part of this library.
+ */
+#ifndef ABFT_GEMM_H
+#define ABFT_GEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ABFT_OK 0
+#define ABFT_EINVAL (-1)        /* null pointer, bad shape, ld < dim, workspace too small */
+#define ABFT_EUNSUPPORTED (-2)  /* valid request this build does not implement */
+#define ABFT_EHIP (-3)          /* a HIP runtime call failed */
+
+/* flags of abft_gemm_u8s8s32_checked */
+#define ABFT_CHECK 0u             /* default: verify every row (Algorithm 1) */
+#define ABFT_NOCHECK 1u           /* same kernel with the checksum work compiled out */
+#define ABFT_VARIANT_MASK 0xF00u  /* 0 = choose by shape */
+#define ABFT_VARIANT_TILE256 0x100u
+#define ABFT_VARIANT_TILE128 0x200u
+#define ABFT_VARIANT_TILE64 0x300u
+#define ABFT_VARIANT_SMALLM 0x400u /* streaming kernel, M <= 64 */
+
+/* Opaque packed weight: B in matrix-core fragment order, its checksum column
+ * S_B = B e as four signed base-256 digit columns, S_B itself, and the column
+ * sums e^T B used by the zero-point correction of Eq. 1.  The library owns
+ * its device memory. */
+typedef struct abft_packed_b abft_packed_b;
+
+/* Algorithm 1, the encode and pack steps (rowSum[] loop and pack(B, rowSum[])),
+ * done once per weight matrix (Section IV-A-1: the cost is amortised).
+ *   B    int8, K x N row-major with ldb >= N when b_is_transposed == 0;
+ *        N x K row-major with ldb >= K (a torch Linear weight) when 1.
+ *   out  host pointer receiving the handle.
+ * Allocates with hipMalloc; the packing kernels are enqueued on `stream`, and
+ * B must stay valid until they have run. */
+int abft_pack_b_checksum(const int8_t* B, int64_t ldb, int K, int N, int b_is_transposed,
+                         void* stream, abft_packed_b** out);
+
+/* K and N of a packed weight (host out-pointers, either may be NULL). */
+int abft_packed_b_dims(const abft_packed_b* Bp, int* K, int* N);
+
+/* Copy S_B = B e (int32 [K]; Section IV, definition of the encoded column). */
+int abft_packed_b_get_checksum(const abft_packed_b* Bp, int32_t* S_B, void* stream);
+
+/* Copy e^T B (int32 [N]; rank-1 term of Eq. 1). */
+int abft_packed_b_get_col_offsets(const abft_packed_b* Bp, int32_t* colsum, void* stream);
+
+/* Fault-injection hooks (Section VI-B: "flipping a random bit" of a randomly
+ * selected element, in B after its checksum has been calculated).
+ * flip_bit inverts bit `bit` (0..7) of logical B[k][j] inside the packed
+ * layout and leaves the checksum stale; flip_checksum_bit inverts bit `bit`
+ * (0..31) of the stored checksum entry S_B[k] as the kernels see it (the paper
+ * assumes this column error-free, Section IV-C).  Calling either twice with
+ * the same arguments restores the weight. */
+int abft_packed_b_flip_bit(abft_packed_b* Bp, int k, int j, int bit, void* stream);
+int abft_packed_b_flip_checksum_bit(abft_packed_b* Bp, int k, int bit, void* stream);
+
+/* Host call.  Frees the handle; the caller has synchronised every stream that
+ * used it. */
+void abft_packed_b_destroy(abft_packed_b* Bp);
+
+/* Requantization parameters (Section III-B; Eq. 1 with beta_B = 0):
+ *   t = C_temp[i][j] - zA * colsum_B[j] (+ bias[j]);  y = clamp(rne(float(t) * mult) + zC, 0, 255)
+ * in binary32 with round-to-nearest-even.  HOST struct; `mult` (1 value, or N
+ * when per_channel) and `bias` (N, or NULL) are device pointers. */
+typedef struct {
+    int32_t zA;
+    int32_t zC;
+    const float* mult;
+    int32_t per_channel;
+    const int32_t* bias;
+} abft_requant_t;
+
+/* One simulated fault in the 32-bit intermediate (Section VI-B-1, "random bit
+ * flip injection to the 32-bit intermediate result matrix"): C_temp[row][col]
+ * ^= xor_mask after the product and before the row sums, the store and the
+ * requantization. */
+typedef struct {
+    int32_t row;
+    int32_t col;
+    uint32_t xor_mask;
+} abft_inject_t;
+
+/* Scratch the checked GEMM needs for a problem with M rows against Bp:
+ * per-row partial (row sum - checksum) accumulators and an arrival counter.
+ * The memory must be zero before its first use (abft_workspace_init) and every
+ * call leaves it zero again, so one workspace serves any number of calls that
+ * are ordered on one stream.  Calls that may overlap need one workspace each. */
+size_t abft_gemm_workspace_bytes(int M, const abft_packed_b* Bp);
+int abft_workspace_init(void* workspace, size_t bytes, void* stream);
+
+/* Algorithm 1 from the product line to the return: C_temp = A * [B | S_B] in
+ * one pass over A, tSum per row, comparison (Eq. 2b, equality mod 2^32),
+ * errCount; optionally the requantization that follows it (Section IV-B: the
+ * check reads the 32-bit values, requantization excludes the checksum column).
+ *   A          uint8 M x K row-major, lda >= K.  Fast path when A and lda are
+ *              multiples of 16 bytes; any alignment is accepted.
+ *   C          int32 M x N, ldc >= N; may be NULL when rq != NULL (then only
+ *              the uint8 output is written).
+ *   row_flags  int32 [M], overwritten with 0/1 per row (ignored with ABFT_NOCHECK).
+ *   err_count  int32 [1], overwritten with the number of flagged rows; may be NULL.
+ *   rq, Cq     host struct or NULL; uint8 M x N output with ldcq >= N.
+ *   inj        device array of n_inj simulated faults, or NULL / 0.
+ *   flags      ABFT_CHECK or ABFT_NOCHECK, optionally | ABFT_VARIANT_*.
+ *   workspace  abft_gemm_workspace_bytes(M, Bp) bytes, zeroed once; may be
+ *              NULL with ABFT_NOCHECK.
+ * Errors: ABFT_EINVAL for null/shape/ld/workspace problems or an injection
+ * outside the matrix (checked on the host only when inj is NULL-free of host
+ * knowledge: the kernel ignores out-of-range entries); ABFT_EUNSUPPORTED for a
+ * variant that cannot run the shape; ABFT_EHIP for a failed launch. */
+int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp,
+                              int32_t* C, int64_t ldc, int32_t* row_flags, int32_t* err_count,
+                              const abft_requant_t* rq, uint8_t* Cq, int64_t ldcq,
+                              const abft_inject_t* inj, int n_inj, uint32_t flags,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* Stand-alone requantization of a stored int32 C_temp (Section III-B), using the
+ * column sums held in Bp.  Same arithmetic as the fused epilogue. */
+int abft_requantize_u8(const int32_t* C, int64_t ldc, int M, int N, const abft_packed_b* Bp,
+                       const abft_requant_t* rq, uint8_t* Cq, int64_t ldcq, void* stream);
+
+/* Re-verification of a C_temp that has been sitting in memory (the paper's
+ * "flip in the 32-bit intermediate" fault model applied after the GEMM):
+ * row_chk[i] = (A S_B)[i] as produced by a checked GEMM with want_row_chk, or
+ * supplied by the caller; flags rows whose sum differs.  */
+int abft_verify_rows(const int32_t* C, int64_t ldc, int M, int N, const int32_t* row_chk,
+                     int32_t* row_flags, int32_t* err_count, void* stream);
+
+/* chk = A S_B (int32 [M]) on its own, from A and the packed checksum digits:
+ * the reference side of Eq. 2b for abft_verify_rows. */
+int abft_row_checksum(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp,
+                      int32_t* row_chk, void* stream);
+
+/* Message for the last non-OK return on this host thread. */
+const char* abft_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ABFT_GEMM_H */

@@ -1,0 +1,220 @@
+"""ctypes binding of libabftgemm.so: same names as include/abft_gemm.h.
+
+Argument marshalling only.  torch tensors supply device memory and the current
+stream; every step of the method runs in the HIP kernels behind the C ABI.
+Importing this module fails loudly when the library has not been built
+(`python -m paper_2103_00130_amd.build`): there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libabftgemm.so")
+
+ABFT_OK, ABFT_EINVAL, ABFT_EUNSUPPORTED, ABFT_EHIP = 0, -1, -2, -3
+ABFT_CHECK, ABFT_NOCHECK = 0, 1
+ABFT_VARIANT_TILE256, ABFT_VARIANT_TILE128, ABFT_VARIANT_TILE64, ABFT_VARIANT_SMALLM = 0x100, 0x200, 0x300, 0x400
+
+EXPORTS = (
+    "abft_pack_b_checksum", "abft_packed_b_dims", "abft_packed_b_get_checksum", "abft_packed_b_get_col_offsets",
+    "abft_packed_b_flip_bit", "abft_packed_b_flip_checksum_bit", "abft_packed_b_destroy",
+    "abft_gemm_workspace_bytes", "abft_workspace_init", "abft_gemm_u8s8s32_checked", "abft_requantize_u8",
+    "abft_verify_rows", "abft_row_checksum", "abft_last_error",
+)
+
+
+class abft_requant_t(ctypes.Structure):
+    _fields_ = [("zA", ctypes.c_int32), ("zC", ctypes.c_int32), ("mult", ctypes.c_void_p),
+                ("per_channel", ctypes.c_int32), ("bias", ctypes.c_void_p)]
+
+
+class abft_inject_t(ctypes.Structure):
+    _fields_ = [("row", ctypes.c_int32), ("col", ctypes.c_int32), ("xor_mask", ctypes.c_uint32)]
+
+
+class AbftError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libabftgemm error {code}: {msg}")
+        self.code = code
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2103_00130_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, u32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, ctypes.c_size_t
+    L.abft_last_error.restype = ctypes.c_char_p
+    L.abft_pack_b_checksum.argtypes = [vp, i64, i32, i32, i32, vp, ctypes.POINTER(vp)]
+    L.abft_packed_b_dims.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.abft_packed_b_get_checksum.argtypes = [vp, vp, vp]
+    L.abft_packed_b_get_col_offsets.argtypes = [vp, vp, vp]
+    L.abft_packed_b_flip_bit.argtypes = [vp, i32, i32, i32, vp]
+    L.abft_packed_b_flip_checksum_bit.argtypes = [vp, i32, i32, vp]
+    L.abft_packed_b_destroy.argtypes = [vp]
+    L.abft_packed_b_destroy.restype = None
+    L.abft_gemm_workspace_bytes.argtypes = [i32, vp]
+    L.abft_gemm_workspace_bytes.restype = sz
+    L.abft_workspace_init.argtypes = [vp, sz, vp]
+    L.abft_gemm_u8s8s32_checked.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64,
+                                            vp, i32, u32, vp, sz, vp]
+    L.abft_requantize_u8.argtypes = [vp, i64, i32, i32, vp, ctypes.POINTER(abft_requant_t), vp, i64, vp]
+    L.abft_verify_rows.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
+    L.abft_row_checksum.argtypes = [vp, i64, i32, vp, vp, vp]
+    return L
+
+
+lib = _load()
+
+
+def _check(rc: int):
+    if rc != ABFT_OK:
+        raise AbftError(rc, lib.abft_last_error().decode())
+
+
+def _stream(stream=None) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def _ptr(t, dtype, name):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _ld(t, name):
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{name} must be 2-D with unit column stride")
+    return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+class PackedB:
+    """Owner of an abft_packed_b handle."""
+
+    def __init__(self, handle: int, K: int, N: int):
+        self.handle, self.K, self.N = handle, K, N
+
+    def destroy(self):
+        if self.handle:
+            torch.cuda.synchronize()
+            lib.abft_packed_b_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def abft_pack_b_checksum(B: torch.Tensor, b_is_transposed: bool = False, stream=None) -> PackedB:
+    """B: int8 device tensor, K x N (or N x K when b_is_transposed)."""
+    ptr = _ptr(B, torch.int8, "B")
+    ldb = _ld(B, "B")
+    K, N = (B.shape[1], B.shape[0]) if b_is_transposed else (B.shape[0], B.shape[1])
+    out = ctypes.c_void_p()
+    _check(lib.abft_pack_b_checksum(ptr, ldb, K, N, int(b_is_transposed), _stream(stream), ctypes.byref(out)))
+    return PackedB(out.value, K, N)
+
+
+def abft_packed_b_dims(Bp: PackedB):
+    k, n = ctypes.c_int(), ctypes.c_int()
+    _check(lib.abft_packed_b_dims(Bp.handle, ctypes.byref(k), ctypes.byref(n)))
+    return k.value, n.value
+
+
+def abft_packed_b_get_checksum(Bp: PackedB, S_B: torch.Tensor, stream=None):
+    assert S_B.numel() >= Bp.K
+    _check(lib.abft_packed_b_get_checksum(Bp.handle, _ptr(S_B, torch.int32, "S_B"), _stream(stream)))
+
+
+def abft_packed_b_get_col_offsets(Bp: PackedB, colsum: torch.Tensor, stream=None):
+    assert colsum.numel() >= Bp.N
+    _check(lib.abft_packed_b_get_col_offsets(Bp.handle, _ptr(colsum, torch.int32, "colsum"), _stream(stream)))
+
+
+def abft_packed_b_flip_bit(Bp: PackedB, k: int, j: int, bit: int, stream=None):
+    _check(lib.abft_packed_b_flip_bit(Bp.handle, int(k), int(j), int(bit), _stream(stream)))
+
+
+def abft_packed_b_flip_checksum_bit(Bp: PackedB, k: int, bit: int, stream=None):
+    _check(lib.abft_packed_b_flip_checksum_bit(Bp.handle, int(k), int(bit), _stream(stream)))
+
+
+def abft_gemm_workspace_bytes(M: int, Bp: PackedB) -> int:
+    return int(lib.abft_gemm_workspace_bytes(int(M), Bp.handle))
+
+
+def abft_workspace_init(workspace: torch.Tensor, stream=None):
+    _check(lib.abft_workspace_init(workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def make_requant(zA: int, zC: int, mult: torch.Tensor, bias: torch.Tensor | None = None) -> abft_requant_t:
+    """Host struct holding device pointers; keep `mult`/`bias` alive while it is in use."""
+    return abft_requant_t(int(zA), int(zC), _ptr(mult, torch.float32, "mult"), int(mult.numel() > 1),
+                          _ptr(bias, torch.int32, "bias"))
+
+
+def make_injections(entries, device="cuda") -> torch.Tensor:
+    """[(row, col, xor_mask), ...] -> device tensor laid out as abft_inject_t[n]."""
+    import numpy as np
+    arr = np.zeros((len(entries), 3), dtype=np.uint32)
+    for t, (r, c, m) in enumerate(entries):
+        arr[t] = (r, c, m)
+    return torch.from_numpy(arr.view(np.int32)).to(device)
+
+
+def abft_gemm_u8s8s32_checked(A, Bp: PackedB, C, row_flags, err_count, rq=None, Cq=None, inj=None, n_inj=0,
+                              flags=ABFT_CHECK, workspace=None, stream=None):
+    M = A.shape[0]
+    if A.shape[1] != Bp.K:
+        raise ValueError(f"A is {tuple(A.shape)}, packed B has K={Bp.K}")
+    for t, nm in ((C, "C"), (Cq, "Cq")):
+        if t is not None and tuple(t.shape) != (M, Bp.N):
+            raise ValueError(f"{nm} must be {M}x{Bp.N}")
+    if row_flags is not None and row_flags.numel() < M:
+        raise ValueError("row_flags shorter than M")
+    if inj is not None and inj.numel() < 3 * n_inj:
+        raise ValueError("injection tensor shorter than n_inj entries")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.abft_gemm_u8s8s32_checked(
+        _ptr(A, torch.uint8, "A"), _ld(A, "A"), M, Bp.handle,
+        _ptr(C, torch.int32, "C"), 0 if C is None else _ld(C, "C"),
+        _ptr(row_flags, torch.int32, "row_flags"), _ptr(err_count, torch.int32, "err_count"),
+        None if rq is None else ctypes.byref(rq), _ptr(Cq, torch.uint8, "Cq"), 0 if Cq is None else _ld(Cq, "Cq"),
+        _ptr(inj, torch.int32, "inj"), int(n_inj), int(flags),
+        None if workspace is None else workspace.data_ptr(), ws_bytes, _stream(stream)))
+
+
+def abft_requantize_u8(C, Bp: PackedB, rq: abft_requant_t, Cq, stream=None):
+    M, N = C.shape
+    _check(lib.abft_requantize_u8(_ptr(C, torch.int32, "C"), _ld(C, "C"), M, N, Bp.handle, ctypes.byref(rq),
+                                  _ptr(Cq, torch.uint8, "Cq"), _ld(Cq, "Cq"), _stream(stream)))
+
+
+def abft_verify_rows(C, row_chk, row_flags, err_count=None, stream=None):
+    M, N = C.shape
+    _check(lib.abft_verify_rows(_ptr(C, torch.int32, "C"), _ld(C, "C"), M, N, _ptr(row_chk, torch.int32, "row_chk"),
+                                _ptr(row_flags, torch.int32, "row_flags"), _ptr(err_count, torch.int32, "err_count"),
+                                _stream(stream)))
+
+
+def abft_row_checksum(A, Bp: PackedB, row_chk, stream=None):
+    _check(lib.abft_row_checksum(_ptr(A, torch.uint8, "A"), _ld(A, "A"), A.shape[0], Bp.handle,
+                                 _ptr(row_chk, torch.int32, "row_chk"), _stream(stream)))
+
+
+class Workspace:
+    """A zero-initialised workspace tensor sized for (M, Bp)."""
+
+    def __init__(self, M: int, Bp: PackedB, device="cuda"):
+        self.tensor = torch.empty(abft_gemm_workspace_bytes(M, Bp) // 4, dtype=torch.int32, device=device)
+        abft_workspace_init(self.tensor)

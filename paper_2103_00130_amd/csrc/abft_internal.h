@@ -1,0 +1,103 @@
+// Internal declarations shared by the HIP translation units of libabftgemm.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace abft {
+
+// ---- packed weight layout -----------------------------------------------------------
+// B is cut into "units" of 64 k-values x 32 columns = 2 KiB, stored as
+// [k-group kg 0..3][column c 0..31][16 consecutive k bytes].  A 32x32x32 int8 MFMA
+// takes k-groups {2h, 2h+1} of a unit as its B operand with lane l reading the
+// 16 bytes at h*1024 + l*16; a 16x16x64 MFMA takes columns 16s..16s+15 of all four
+// k-groups with lane l reading (l/16)*512 + (16s + l%16)*16.  Units are ordered
+// [n-tile of 256 columns][k-block of 64][unit 0..7] so that a workgroup streaming
+// along K for one n-tile reads consecutive memory.  Rows k >= K and columns
+// j >= N are zero, which leaves both the product and the checksum unchanged.
+constexpr int kUnitK = 64;        // k-values per unit
+constexpr int kUnitN = 32;        // columns per unit
+constexpr int kUnitBytes = kUnitK * kUnitN;
+constexpr int kTileN = 256;       // columns per packed n-tile
+constexpr int kUnitsPerTile = kTileN / kUnitN;
+constexpr int kLimbs = 4;         // signed base-256 digits of an int32 checksum entry
+
+__host__ __device__ inline int64_t packed_unit_offset(int ntile, int kb, int unit, int KB) {
+    return (((int64_t)ntile * KB + kb) * kUnitsPerTile + unit) * kUnitBytes;
+}
+// byte offset of logical B[k][j]
+__host__ __device__ inline int64_t packed_elem_offset(int k, int j, int KB) {
+    const int ntile = j / kTileN, unit = (j % kTileN) / kUnitN, c = j % kUnitN;
+    const int kb = k / kUnitK, kg = (k % kUnitK) / 16, b = k % 16;
+    return packed_unit_offset(ntile, kb, unit, KB) + (kg * kUnitN + c) * 16 + b;
+}
+// Checksum digits: [k-block][k-group][digit 0..3][16 k bytes]; digit d of S_B[k]
+// multiplies 256^d.  Same k order as the units, so a 16x16x64 MFMA reads digit
+// column d with lane l = kg*16 + d.
+__host__ __device__ inline int64_t limb_offset(int k, int digit) {
+    const int kb = k / kUnitK, kg = (k % kUnitK) / 16, b = k % 16;
+    return (((int64_t)kb * 4 + kg) * kLimbs + digit) * 16 + b;
+}
+
+}  // namespace abft
+
+struct abft_packed_b {
+    int K, N;
+    int KB;            // k-blocks of 64
+    int NT;            // n-tiles of 256
+    int device;
+    int8_t* packed;    // NT*KB*8 units
+    int8_t* limbs;     // KB*64*4 bytes
+    int32_t* S_B;      // [KB*64], zero past K
+    int32_t* colsum;   // [NT*256], zero past N
+    int32_t* total;    // [1] sum of S_B (wrap-around)
+};
+
+namespace abft {
+
+struct RequantDev {
+    int32_t zA, zC;
+    const float* mult;
+    int32_t per_channel;
+    const int32_t* bias;
+};
+
+struct GemmParams {
+    const uint8_t* A;
+    int64_t lda;
+    int M, N, K, KB;
+    int a_vec_ok;              // A and lda are multiples of 16 bytes
+    const int8_t* packed;
+    const int8_t* limbs;
+    const int32_t* colsum;
+    const int32_t* total;
+    int32_t* C;
+    int64_t ldc;
+    int32_t* row_flags;
+    int32_t* err_count;
+    uint8_t* Cq;
+    int64_t ldcq;
+    RequantDev rq;
+    const void* inj;           // abft_inject_t[n_inj]
+    int n_inj;
+    int32_t* ws;               // workspace: [0] ticket, [16..16+M) row differences
+};
+
+constexpr int kWsHeaderInts = 16;
+
+enum Variant { kTile256 = 1, kTile128 = 2, kTile64 = 3, kSmallM = 4 };
+
+// launchers (each returns the hipError_t of its launch)
+hipError_t launch_pack(const int8_t* B, int64_t ldb, int transposed, abft_packed_b* h, hipStream_t s);
+hipError_t launch_flip_bit(abft_packed_b* h, int k, int j, int bit, hipStream_t s);
+hipError_t launch_flip_checksum_bit(abft_packed_b* h, int k, int bit, hipStream_t s);
+hipError_t launch_fill_zero(int32_t* p, size_t n_ints, hipStream_t s);
+hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s);
+hipError_t launch_gemm_smallm(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s);
+hipError_t launch_requantize(const int32_t* C, int64_t ldc, int M, int N, const int32_t* colsum,
+                             const RequantDev& rq, uint8_t* Cq, int64_t ldcq, hipStream_t s);
+hipError_t launch_verify_rows(const int32_t* C, int64_t ldc, int M, int N, const int32_t* row_chk,
+                              int32_t* row_flags, int32_t* err_count, hipStream_t s);
+hipError_t launch_row_checksum(const uint8_t* A, int64_t lda, int M, int K, const int32_t* S_B,
+                               int32_t* row_chk, hipStream_t s);
+
+}  // namespace abft

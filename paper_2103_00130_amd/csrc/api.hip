@@ -1,0 +1,238 @@
+// C ABI of libabftgemm (see include/abft_gemm.h): argument checks, variant choice and
+// kernel launches.  No arithmetic of the method happens on the host.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "../../include/abft_gemm.h"
+#include "abft_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+    return fail(ABFT_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(expr)                                      \
+    do {                                                   \
+        hipError_t e_ = (expr);                            \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr);  \
+    } while (0)
+
+void free_handle(abft_packed_b* h) {
+    if (!h) return;
+    (void)hipFree(h->packed);
+    (void)hipFree(h->limbs);
+    (void)hipFree(h->S_B);
+    (void)hipFree(h->colsum);
+    (void)hipFree(h->total);
+    delete h;
+}
+
+size_t ws_ints(int M) { return (size_t)abft::kWsHeaderInts + (((size_t)M + 63) / 64) * 64; }
+
+}  // namespace
+
+extern "C" {
+
+const char* abft_last_error(void) { return g_err; }
+
+int abft_pack_b_checksum(const int8_t* B, int64_t ldb, int K, int N, int b_is_transposed, void* stream,
+                         abft_packed_b** out) {
+    if (!B || !out) return fail(ABFT_EINVAL, "abft_pack_b_checksum: null pointer");
+    if (K < 1 || N < 1) return fail(ABFT_EINVAL, "abft_pack_b_checksum: K=%d N=%d must be >= 1", K, N);
+    if (ldb < (b_is_transposed ? K : N))
+        return fail(ABFT_EINVAL, "abft_pack_b_checksum: ldb=%lld smaller than the row length", (long long)ldb);
+    if (N > (1 << 23)) return fail(ABFT_EUNSUPPORTED, "abft_pack_b_checksum: N=%d above 2^23", N);
+    abft_packed_b* h = new (std::nothrow) abft_packed_b();
+    if (!h) return fail(ABFT_EHIP, "abft_pack_b_checksum: out of host memory");
+    std::memset(h, 0, sizeof *h);
+    h->K = K;
+    h->N = N;
+    h->KB = (K + abft::kUnitK - 1) / abft::kUnitK;
+    h->NT = (N + abft::kTileN - 1) / abft::kTileN;
+    hipError_t e = hipGetDevice(&h->device);
+    const size_t packed_bytes = (size_t)h->NT * h->KB * abft::kUnitsPerTile * abft::kUnitBytes;
+    if (e == hipSuccess) e = hipMalloc(&h->packed, packed_bytes);
+    if (e == hipSuccess) e = hipMalloc(&h->limbs, (size_t)h->KB * abft::kUnitK * abft::kLimbs);
+    if (e == hipSuccess) e = hipMalloc(&h->S_B, (size_t)h->KB * abft::kUnitK * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc(&h->colsum, (size_t)h->NT * abft::kTileN * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc(&h->total, 64);
+    if (e == hipSuccess) e = abft::launch_pack(B, ldb, b_is_transposed ? 1 : 0, h, (hipStream_t)stream);
+    if (e != hipSuccess) {
+        free_handle(h);
+        return hip_fail(e, "abft_pack_b_checksum");
+    }
+    *out = h;
+    return ABFT_OK;
+}
+
+int abft_packed_b_dims(const abft_packed_b* Bp, int* K, int* N) {
+    if (!Bp) return fail(ABFT_EINVAL, "abft_packed_b_dims: null handle");
+    if (K) *K = Bp->K;
+    if (N) *N = Bp->N;
+    return ABFT_OK;
+}
+
+int abft_packed_b_get_checksum(const abft_packed_b* Bp, int32_t* S_B, void* stream) {
+    if (!Bp || !S_B) return fail(ABFT_EINVAL, "abft_packed_b_get_checksum: null pointer");
+    HIP_TRY(hipMemcpyAsync(S_B, Bp->S_B, (size_t)Bp->K * sizeof(int32_t), hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+int abft_packed_b_get_col_offsets(const abft_packed_b* Bp, int32_t* colsum, void* stream) {
+    if (!Bp || !colsum) return fail(ABFT_EINVAL, "abft_packed_b_get_col_offsets: null pointer");
+    HIP_TRY(hipMemcpyAsync(colsum, Bp->colsum, (size_t)Bp->N * sizeof(int32_t), hipMemcpyDeviceToDevice,
+                           (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+int abft_packed_b_flip_bit(abft_packed_b* Bp, int k, int j, int bit, void* stream) {
+    if (!Bp) return fail(ABFT_EINVAL, "abft_packed_b_flip_bit: null handle");
+    if (k < 0 || k >= Bp->K || j < 0 || j >= Bp->N || bit < 0 || bit > 7)
+        return fail(ABFT_EINVAL, "abft_packed_b_flip_bit: (k=%d, j=%d, bit=%d) outside %dx%d int8", k, j, bit, Bp->K, Bp->N);
+    HIP_TRY(abft::launch_flip_bit(Bp, k, j, bit, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+int abft_packed_b_flip_checksum_bit(abft_packed_b* Bp, int k, int bit, void* stream) {
+    if (!Bp) return fail(ABFT_EINVAL, "abft_packed_b_flip_checksum_bit: null handle");
+    if (k < 0 || k >= Bp->K || bit < 0 || bit > 31)
+        return fail(ABFT_EINVAL, "abft_packed_b_flip_checksum_bit: (k=%d, bit=%d) outside [0,%d) x [0,32)", k, bit, Bp->K);
+    HIP_TRY(abft::launch_flip_checksum_bit(Bp, k, bit, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+void abft_packed_b_destroy(abft_packed_b* Bp) { free_handle(Bp); }
+
+size_t abft_gemm_workspace_bytes(int M, const abft_packed_b* Bp) {
+    (void)Bp;
+    if (M < 1) return 0;
+    return ws_ints(M) * sizeof(int32_t);
+}
+
+int abft_workspace_init(void* workspace, size_t bytes, void* stream) {
+    if (!workspace && bytes) return fail(ABFT_EINVAL, "abft_workspace_init: null workspace");
+    if (bytes % 4) return fail(ABFT_EINVAL, "abft_workspace_init: size must be a multiple of 4");
+    HIP_TRY(abft::launch_fill_zero((int32_t*)workspace, bytes / 4, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp, int32_t* C,
+                              int64_t ldc, int32_t* row_flags, int32_t* err_count, const abft_requant_t* rq,
+                              uint8_t* Cq, int64_t ldcq, const abft_inject_t* inj, int n_inj, uint32_t flags,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+    const char* fn = "abft_gemm_u8s8s32_checked";
+    if (!A || !Bp) return fail(ABFT_EINVAL, "%s: null A or packed B", fn);
+    if (M < 1) return fail(ABFT_EINVAL, "%s: M=%d must be >= 1", fn, M);
+    if (lda < Bp->K) return fail(ABFT_EINVAL, "%s: lda=%lld < K=%d", fn, (long long)lda, Bp->K);
+    const bool check = !(flags & ABFT_NOCHECK);
+    const bool want_c = C != nullptr, want_q = rq != nullptr;
+    if (!want_c && !want_q) return fail(ABFT_EINVAL, "%s: C is NULL and no requantization was asked for", fn);
+    if (want_c && ldc < Bp->N) return fail(ABFT_EINVAL, "%s: ldc=%lld < N=%d", fn, (long long)ldc, Bp->N);
+    if (want_q) {
+        if (!Cq) return fail(ABFT_EINVAL, "%s: requantization asked for but Cq is NULL", fn);
+        if (ldcq < Bp->N) return fail(ABFT_EINVAL, "%s: ldcq=%lld < N=%d", fn, (long long)ldcq, Bp->N);
+        if (!rq->mult) return fail(ABFT_EINVAL, "%s: requantization multiplier is NULL", fn);
+    }
+    if (n_inj < 0 || (n_inj > 0 && !inj)) return fail(ABFT_EINVAL, "%s: bad injection list", fn);
+    if (check) {
+        if (!row_flags) return fail(ABFT_EINVAL, "%s: row_flags is NULL", fn);
+        if (!workspace || workspace_bytes < abft_gemm_workspace_bytes(M, Bp))
+            return fail(ABFT_EINVAL, "%s: workspace of %zu bytes, %zu needed", fn, workspace_bytes,
+                        abft_gemm_workspace_bytes(M, Bp));
+    }
+
+    abft::GemmParams p;
+    std::memset(&p, 0, sizeof p);
+    p.A = A;
+    p.lda = lda;
+    p.M = M;
+    p.N = Bp->N;
+    p.K = Bp->K;
+    p.KB = Bp->KB;
+    p.a_vec_ok = (((uintptr_t)A | (uintptr_t)lda) & 15) == 0;
+    p.packed = Bp->packed;
+    p.limbs = Bp->limbs;
+    p.colsum = Bp->colsum;
+    p.total = Bp->total;
+    p.C = C;
+    p.ldc = ldc;
+    p.row_flags = row_flags;
+    p.err_count = err_count;
+    p.Cq = Cq;
+    p.ldcq = ldcq;
+    if (want_q) {
+        p.rq.zA = rq->zA;
+        p.rq.zC = rq->zC;
+        p.rq.mult = rq->mult;
+        p.rq.per_channel = rq->per_channel;
+        p.rq.bias = rq->bias;
+    }
+    p.inj = inj;
+    p.n_inj = n_inj;
+    p.ws = (int32_t*)workspace;
+
+    int variant = (int)((flags & ABFT_VARIANT_MASK) >> 8);
+    if (variant == 0) {
+        // largest tile that still gives every compute unit a workgroup
+        auto tiles = [&](int b) { return (int64_t)((M + b - 1) / b) * ((Bp->N + b - 1) / b); };
+        if (tiles(256) >= 192) variant = abft::kTile256;
+        else if (tiles(128) >= 192) variant = abft::kTile128;
+        else variant = abft::kTile64;
+    }
+    hipError_t e;
+    if (variant == abft::kSmallM) {
+        if (M > 64) return fail(ABFT_EUNSUPPORTED, "%s: the streaming variant takes M <= 64, got %d", fn, M);
+        e = abft::launch_gemm_smallm(check, want_c, want_q, p, (hipStream_t)stream);
+    } else if (variant >= abft::kTile256 && variant <= abft::kTile64) {
+        e = abft::launch_gemm_tile(variant, check, want_c, want_q, p, (hipStream_t)stream);
+    } else {
+        return fail(ABFT_EINVAL, "%s: unknown variant %d", fn, variant);
+    }
+    if (e == hipErrorNotSupported) return fail(ABFT_EUNSUPPORTED, "%s: variant %d is not available", fn, variant);
+    if (e != hipSuccess) return hip_fail(e, fn);
+    return ABFT_OK;
+}
+
+int abft_requantize_u8(const int32_t* C, int64_t ldc, int M, int N, const abft_packed_b* Bp,
+                       const abft_requant_t* rq, uint8_t* Cq, int64_t ldcq, void* stream) {
+    const char* fn = "abft_requantize_u8";
+    if (!C || !Bp || !rq || !Cq || !rq->mult) return fail(ABFT_EINVAL, "%s: null pointer", fn);
+    if (M < 1 || N < 1 || N != Bp->N) return fail(ABFT_EINVAL, "%s: M=%d N=%d (packed N=%d)", fn, M, N, Bp->N);
+    if (ldc < N || ldcq < N) return fail(ABFT_EINVAL, "%s: leading dimension below N", fn);
+    abft::RequantDev r{rq->zA, rq->zC, rq->mult, rq->per_channel, rq->bias};
+    HIP_TRY(abft::launch_requantize(C, ldc, M, N, Bp->colsum, r, Cq, ldcq, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+int abft_verify_rows(const int32_t* C, int64_t ldc, int M, int N, const int32_t* row_chk, int32_t* row_flags,
+                     int32_t* err_count, void* stream) {
+    const char* fn = "abft_verify_rows";
+    if (!C || !row_chk || !row_flags) return fail(ABFT_EINVAL, "%s: null pointer", fn);
+    if (M < 1 || N < 1 || ldc < N) return fail(ABFT_EINVAL, "%s: M=%d N=%d ldc=%lld", fn, M, N, (long long)ldc);
+    HIP_TRY(abft::launch_verify_rows(C, ldc, M, N, row_chk, row_flags, err_count, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+int abft_row_checksum(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp, int32_t* row_chk,
+                      void* stream) {
+    const char* fn = "abft_row_checksum";
+    if (!A || !Bp || !row_chk) return fail(ABFT_EINVAL, "%s: null pointer", fn);
+    if (M < 1 || lda < Bp->K) return fail(ABFT_EINVAL, "%s: M=%d lda=%lld K=%d", fn, M, (long long)lda, Bp->K);
+    HIP_TRY(abft::launch_row_checksum(A, lda, M, Bp->K, Bp->S_B, row_chk, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,87 @@
+// Bandwidth-bound companions of the checked GEMM: stand-alone requantization
+// (Section III-B of arXiv 2103.00130), re-verification of a stored C_temp against the
+// checksum column (Eq. 2b; the paper's "bit flip in the 32-bit intermediate" fault
+// model applied to a matrix at rest), and the checksum column A*S_B on its own.
+#include "abft_internal.h"
+
+namespace abft {
+namespace {
+
+// 4 consecutive columns per thread: one 16-byte load of C, one 4-byte store of Cq when
+// the row is aligned for it, element-wise otherwise.
+__global__ void requantize_kernel(const int32_t* __restrict__ C, int64_t ldc, int M, int N,
+                                  const int32_t* __restrict__ colsum, RequantDev rq, uint8_t* __restrict__ Cq,
+                                  int64_t ldcq) {
+    const int row = blockIdx.y;
+    const int j0 = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (row >= M || j0 >= N) return;
+    const int n = min(4, N - j0);
+    for (int e = 0; e < n; ++e) {
+        const int col = j0 + e;
+        uint32_t t = (uint32_t)C[(int64_t)row * ldc + col] - (uint32_t)rq.zA * (uint32_t)colsum[col];
+        if (rq.bias) t += (uint32_t)rq.bias[col];
+        const float m = rq.mult[rq.per_channel ? col : 0];
+        const float p = __fmul_rn((float)(int32_t)t, m);
+        float y = __builtin_rintf(p) + (float)rq.zC;
+        y = fminf(fmaxf(y, 0.0f), 255.0f);
+        Cq[(int64_t)row * ldcq + col] = (uint8_t)y;
+    }
+}
+
+// one workgroup (256 lanes) per row: tSum, comparison with row_chk, flag, count.
+__global__ void verify_rows_kernel(const int32_t* __restrict__ C, int64_t ldc, int M, int N,
+                                   const int32_t* __restrict__ row_chk, int32_t* __restrict__ row_flags,
+                                   int32_t* __restrict__ err_count) {
+    __shared__ uint32_t part[4];
+    const int row = blockIdx.x;
+    uint32_t s = 0;
+    for (int j = threadIdx.x; j < N; j += blockDim.x) s += (uint32_t)C[(int64_t)row * ldc + j];
+    for (int off = 32; off > 0; off >>= 1) s += (uint32_t)__shfl_xor((int)s, off);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t t = part[0] + part[1] + part[2] + part[3];
+        const int f = ((int32_t)t != row_chk[row]) ? 1 : 0;
+        row_flags[row] = f;
+        if (err_count && f) atomicAdd(err_count, 1);
+    }
+}
+
+// chk[i] = sum_k A[i][k] * S_B[k], wrap-around int32; one wavefront per row.
+__global__ void row_checksum_kernel(const uint8_t* __restrict__ A, int64_t lda, int M, int K,
+                                    const int32_t* __restrict__ S_B, int32_t* __restrict__ row_chk) {
+    const int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
+    const int lane = threadIdx.x & 63;
+    if (row >= M) return;
+    uint32_t s = 0;
+    for (int k = lane; k < K; k += 64) s += (uint32_t)A[(int64_t)row * lda + k] * (uint32_t)S_B[k];
+    for (int off = 32; off > 0; off >>= 1) s += (uint32_t)__shfl_xor((int)s, off);
+    if (lane == 0) row_chk[row] = (int32_t)s;
+}
+
+}  // namespace
+
+hipError_t launch_requantize(const int32_t* C, int64_t ldc, int M, int N, const int32_t* colsum,
+                             const RequantDev& rq, uint8_t* Cq, int64_t ldcq, hipStream_t s) {
+    const dim3 block(64), grid((unsigned)((N + 255) / 256), (unsigned)M);
+    requantize_kernel<<<grid, block, 0, s>>>(C, ldc, M, N, colsum, rq, Cq, ldcq);
+    return hipGetLastError();
+}
+
+hipError_t launch_verify_rows(const int32_t* C, int64_t ldc, int M, int N, const int32_t* row_chk,
+                              int32_t* row_flags, int32_t* err_count, hipStream_t s) {
+    if (err_count) {
+        hipError_t e = launch_fill_zero(err_count, 1, s);
+        if (e != hipSuccess) return e;
+    }
+    verify_rows_kernel<<<dim3((unsigned)M), dim3(256), 0, s>>>(C, ldc, M, N, row_chk, row_flags, err_count);
+    return hipGetLastError();
+}
+
+hipError_t launch_row_checksum(const uint8_t* A, int64_t lda, int M, int K, const int32_t* S_B,
+                               int32_t* row_chk, hipStream_t s) {
+    row_checksum_kernel<<<dim3((unsigned)((M + 3) / 4)), dim3(256), 0, s>>>(A, lda, M, K, S_B, row_chk);
+    return hipGetLastError();
+}
+
+}  // namespace abft

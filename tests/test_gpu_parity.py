@@ -1,0 +1,280 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Integer results (C_temp, S_B, column sums, flags, errCount) must match bit for bit.
+The requantized uint8 output must equal the oracle's float32 evaluation exactly and
+stay within one code of its float64 evaluation; the differing fraction is printed.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2103_00130_amd import workloads as wlmod
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def binding():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2103_00130_amd import binding as b   # raises if the HIP library is missing
+    return b
+
+
+@pytest.fixture(scope="module")
+def gpu_util():
+    import gpu_util
+    return gpu_util
+
+
+def operands(M, N, K, seed, relu_like=False, full_range_b=True):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    A = wlmod.draw_a(rng, M, K, relu_like)
+    B = rng.integers(-128, 128, size=(K, N), dtype=np.int8) if full_range_b else wlmod.draw_b(rng, K, N)
+    return A, B
+
+
+SHAPES = [(1, 1, 1), (3, 5, 7), (16, 48, 64), (64, 256, 512), (70, 300, 130), (129, 257, 65), (257, 513, 129),
+          (300, 520, 200)]
+TILE_VARIANTS = ["tile64", "tile128", "tile256", "auto"]
+
+
+@pytest.mark.parametrize("transposed", [False, True])
+@pytest.mark.parametrize("K,N", [(1, 1), (7, 5), (64, 256), (130, 300), (129, 513), (512, 256)])
+def test_pack_checksum_and_colsum(binding, gpu_util, oracle, K, N, transposed):
+    say(f"pack K={K} N={N} transposed={transposed}")
+    _, B = operands(1, N, K, 100 + K + N)
+    run = gpu_util.GpuRun(binding, B, transposed=transposed)
+    assert np.array_equal(run.checksum(), oracle.b_checksum(B))
+    assert np.array_equal(run.colsum(), oracle.b_colsum(B))
+    assert binding.abft_packed_b_dims(run.Bp) == (K, N)
+
+
+@pytest.mark.parametrize("variant", TILE_VARIANTS)
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_checked_gemm_matches_oracle(binding, gpu_util, oracle, M, N, K, variant):
+    say(f"gemm {M}x{N}x{K} variant={variant}")
+    A, B = operands(M, N, K, 7 * M + 3 * N + K, relu_like=(M % 2 == 1))
+    ref = oracle.checked_gemm(A, B)
+    run = gpu_util.GpuRun(binding, B)
+    out = run.gemm(A, variant=variant)
+    assert np.array_equal(out["C"], ref.C)
+    assert np.array_equal(out["flags"], ref.flags) and out["err_count"] == 0
+    assert not out["ws"].any(), "workspace must be left zero"
+    # same call without the check: same C, flags and count untouched
+    out2 = run.gemm(A, variant=variant, check=False)
+    assert np.array_equal(out2["C"], ref.C)
+    assert (out2["flags"] == -1).all() and out2["err_count"] == -1
+
+
+@pytest.mark.parametrize("variant", ["tile64", "tile256"])
+def test_unaligned_and_strided_operands(binding, gpu_util, oracle, variant):
+    import torch
+    M, N, K = 37, 70, 83
+    say(f"strided operands {M}x{N}x{K} variant={variant}")
+    A, B = operands(M, N, K, 99)
+    ref = oracle.checked_gemm(A, B)
+    run = gpu_util.GpuRun(binding, B)
+    # lda = K + 5 and a base pointer that is 1 byte off 16-byte alignment
+    buf = torch.zeros(M * (K + 5) + 1, dtype=torch.uint8, device="cuda")
+    A_dev = buf[1:1 + M * (K + 5)].view(M, K + 5)[:, :K]
+    A_dev.copy_(gpu_util.dev(A))
+    Cbuf = torch.full((M, N + 3), 55, dtype=torch.int32, device="cuda")
+    C = Cbuf[:, :N]
+    flags = torch.empty(M, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+    ws = binding.Workspace(M, run.Bp)
+    binding.abft_gemm_u8s8s32_checked(A_dev, run.Bp, C, flags, cnt, flags=gpu_util.VARIANTS[variant],
+                                      workspace=ws.tensor)
+    torch.cuda.synchronize()
+    assert np.array_equal(C.cpu().numpy(), ref.C)
+    assert (Cbuf[:, N:].cpu().numpy() == 55).all(), "columns past N must not be written"
+    assert not flags.cpu().numpy().any() and int(cnt.item()) == 0
+
+
+@pytest.mark.parametrize("variant", TILE_VARIANTS)
+def test_c_flips_flag_exactly_their_rows(binding, gpu_util, oracle, variant):
+    M, N, K = 150, 290, 140
+    say(f"C flips {M}x{N}x{K} variant={variant}")
+    A, B = operands(M, N, K, 5)
+    run = gpu_util.GpuRun(binding, B)
+    ws = binding.Workspace(M, run.Bp)
+    rng = np.random.default_rng(3)
+    for bit in list(range(32)) + [None]:
+        if bit is None:   # several faults in one launch, two of them in the same row
+            inj = [(3, 7, 1 << 31), (3, 200, 1 << 4), (149, 289, 1), (64, 128, 0x00F0F000)]
+        else:
+            inj = [(int(rng.integers(M)), int(rng.integers(N)), 1 << bit)]
+        ref = oracle.checked_gemm(A, B, flips_c=inj)
+        out = run.gemm(A, variant=variant, injections=inj, ws=ws)
+        assert np.array_equal(out["C"], ref.C), f"bit {bit}"
+        assert np.array_equal(out["flags"], ref.flags), f"bit {bit}"
+        assert out["err_count"] == ref.err_count
+        assert not out["ws"].any()
+    # two flips in one row that cancel in the row sum (+2^5 and -2^5) are silent in both
+    clean = oracle.gemm_u8s8s32(A, B)
+    cols = [c for c in range(N) if not (clean[10, c] >> 5) & 1][:1] + [c for c in range(N) if (clean[10, c] >> 5) & 1][:1]
+    inj = [(10, cols[0], 1 << 5), (10, cols[1], 1 << 5)]
+    ref = oracle.checked_gemm(A, B, flips_c=inj)
+    out = run.gemm(A, variant=variant, injections=inj, ws=ws)
+    assert ref.err_count == 0 and out["err_count"] == 0 and np.array_equal(out["C"], ref.C)
+
+
+@pytest.mark.parametrize("variant", ["tile64", "tile256"])
+def test_b_and_a_flips(binding, gpu_util, oracle, variant):
+    import torch
+    M, N, K = 96, 300, 200
+    say(f"A/B flips {M}x{N}x{K} variant={variant}")
+    A, B = operands(M, N, K, 17, relu_like=True)
+    run = gpu_util.GpuRun(binding, B)
+    ws = binding.Workspace(M, run.Bp)
+    rng = np.random.default_rng(8)
+    for _ in range(12):
+        k, j, bit = int(rng.integers(K)), int(rng.integers(N)), int(rng.integers(8))
+        ref = oracle.checked_gemm(A, B, flips_b=[(k, j, bit)])
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        out = run.gemm(A, variant=variant, ws=ws)
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        assert np.array_equal(out["C"], ref.C) and np.array_equal(out["flags"], ref.flags)
+        assert out["err_count"] == ref.err_count == int((A[:, k] != 0).sum())
+    out = run.gemm(A, variant=variant, ws=ws)          # restored weight is clean again
+    assert out["err_count"] == 0
+    A_dev = gpu_util.dev(A)
+    for _ in range(12):
+        i, k, bit = int(rng.integers(M)), int(rng.integers(K)), int(rng.integers(8))
+        ref = oracle.checked_gemm(A, B, flips_a=[(i, k, bit)])
+        A_dev[i, k] ^= (1 << bit)
+        out = run.gemm(A_dev, variant=variant, ws=ws)
+        A_dev[i, k] ^= (1 << bit)
+        assert np.array_equal(out["C"], ref.C)
+        assert out["err_count"] == ref.err_count == 0
+    torch.cuda.synchronize()
+
+
+def test_checksum_entry_flip_flags_rows_it_touches(binding, gpu_util, oracle):
+    # the paper assumes the encoded column error-free (Section IV-C); if S_B[k] is hit anyway,
+    # row p differs by A[p][k] * (+-2^b) mod 2^32
+    M, N, K = 80, 130, 70
+    say("checksum entry flips")
+    A, B = operands(M, N, K, 23, relu_like=True)
+    run = gpu_util.GpuRun(binding, B)
+    S = oracle.b_checksum(B)
+    C = oracle.gemm_u8s8s32(A, B)
+    rs = oracle.row_sums(C)
+    for (k, bit) in [(0, 0), (5, 7), (69, 13), (33, 25), (12, 31)]:
+        S2 = S.copy()
+        S2.view(np.uint32)[k] ^= np.uint32(1 << bit)
+        want, n = oracle.compare(rs, oracle.row_checksum(A, S2))
+        binding.abft_packed_b_flip_checksum_bit(run.Bp, k, bit)
+        out = run.gemm(A)
+        assert np.array_equal(run.checksum(), S2)
+        binding.abft_packed_b_flip_checksum_bit(run.Bp, k, bit)
+        assert np.array_equal(out["flags"], want) and out["err_count"] == n
+        assert np.array_equal(out["C"], C)
+    assert np.array_equal(run.checksum(), S)
+    assert run.gemm(A)["err_count"] == 0
+
+
+@pytest.mark.parametrize("variant", ["tile64", "tile128", "tile256"])
+@pytest.mark.parametrize("kind", ["tensor", "channel", "channel_bias"])
+def test_requant_epilogue(binding, gpu_util, oracle, kind, variant):
+    import torch
+    M, N, K = 140, 270, 600
+    say(f"requant {kind} variant={variant}")
+    rng = np.random.default_rng(31)
+    for zA, relu in ((128, False), (0, True), (17, False)):
+        A, B = operands(M, N, K, 41 + zA, relu_like=relu, full_range_b=False)
+        mult = wlmod.draw_mult(rng, N, "tensor" if kind == "tensor" else "channel")
+        bias = rng.integers(-5000, 5000, size=N).astype(np.int32) if kind == "channel_bias" else None
+        ref = oracle.checked_gemm(A, B)
+        q32 = oracle.requantize(ref.C, ref.colsum, zA, 128, mult, bias, precision="f32")
+        q64 = oracle.requantize(ref.C, ref.colsum, zA, 128, mult, bias, precision="f64")
+        run = gpu_util.GpuRun(binding, B)
+        both = run.gemm(A, variant=variant, requant=(zA, 128, mult, bias))
+        only_q = run.gemm(A, variant=variant, requant=(zA, 128, mult, bias), want_c=False)
+        assert np.array_equal(both["C"], ref.C) and both["err_count"] == 0 and only_q["err_count"] == 0
+        for got in (both["Cq"], only_q["Cq"]):
+            assert np.array_equal(got, q32)
+            d = np.abs(got.astype(np.int32) - q64.astype(np.int32))
+            assert d.max() <= 1
+        say(f"  zA={zA}: fraction of codes differing from the float64 evaluation = {(both['Cq'] != q64).mean():.2e}")
+        # stand-alone requantization of the stored C_temp
+        mult_d = gpu_util.dev(np.atleast_1d(mult))
+        bias_d = None if bias is None else gpu_util.dev(bias)
+        rq = binding.make_requant(zA, 128, mult_d, bias_d)
+        Cq = torch.zeros((M, N), dtype=torch.uint8, device="cuda")
+        binding.abft_requantize_u8(gpu_util.dev(ref.C), run.Bp, rq, Cq)
+        assert np.array_equal(Cq.cpu().numpy(), q32)
+    # a fault in C_temp is flagged by the check and still requantized as it stands
+    inj = [(9, 11, 1 << 30)]
+    refi = oracle.checked_gemm(A, B, flips_c=inj)
+    out = run.gemm(A, variant=variant, requant=(zA, 128, mult, bias), injections=inj)
+    assert np.array_equal(out["flags"], refi.flags) and out["err_count"] == 1
+    assert np.array_equal(out["Cq"], oracle.requantize(refi.C, refi.colsum, zA, 128, mult, bias, precision="f32"))
+
+
+def test_verify_rows_and_row_checksum(binding, gpu_util, oracle):
+    import torch
+    M, N, K = 77, 301, 150
+    say("verify_rows / row_checksum")
+    A, B = operands(M, N, K, 61)
+    ref = oracle.checked_gemm(A, B)
+    run = gpu_util.GpuRun(binding, B)
+    chk = torch.empty(M, dtype=torch.int32, device="cuda")
+    binding.abft_row_checksum(gpu_util.dev(A), run.Bp, chk)
+    assert np.array_equal(chk.cpu().numpy(), ref.chk)
+    C_dev = gpu_util.dev(ref.C)
+    flags = torch.empty(M, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+    binding.abft_verify_rows(C_dev, chk, flags, cnt)
+    assert not flags.cpu().numpy().any() and int(cnt.item()) == 0
+    C_dev[5, 300] ^= (1 << 20)          # a stored intermediate picks up a flip after the GEMM
+    C_dev[70, 0] ^= 1
+    binding.abft_verify_rows(C_dev, chk, flags, cnt)
+    want = np.zeros(M, np.int32)
+    want[[5, 70]] = 1
+    assert np.array_equal(flags.cpu().numpy(), want) and int(cnt.item()) == 2
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4])
+def test_paper_shaped_workloads_full_size(binding, gpu_util, oracle, cfg):
+    """The five workloads at full size, in the launch configuration the benchmark times."""
+    ops = wlmod.make_operands(cfg)
+    wl = ops.wl
+    say(f"workload {cfg}: {wl.name}")
+    ref = oracle.checked_gemm(ops.A, ops.B)
+    run = gpu_util.GpuRun(binding, ops.B)
+    assert np.array_equal(run.checksum(), ref.S_B)
+    assert np.array_equal(run.colsum(), ref.colsum)
+    rq = None if ops.mult is None else (wl.zA, wl.zC, ops.mult, None)
+    out = run.gemm(ops.A, requant=rq)
+    assert np.array_equal(out["C"], ref.C)
+    assert not out["flags"].any() and out["err_count"] == 0
+    if rq is not None:
+        q32 = oracle.requantize(ref.C, ref.colsum, wl.zA, wl.zC, ops.mult, precision="f32")
+        q64 = oracle.requantize(ref.C, ref.colsum, wl.zA, wl.zC, ops.mult, precision="f64")
+        assert np.array_equal(out["Cq"], q32)
+        assert np.abs(out["Cq"].astype(np.int32) - q64.astype(np.int32)).max() <= 1
+        say(f"  requantized codes differing from the float64 evaluation: {(out['Cq'] != q64).mean():.3e}")
+    # one flip in C: exactly that row
+    inj = [(wl.M - 1, wl.N - 1, 1 << 31)]
+    out = run.gemm(ops.A, injections=inj)
+    want = np.zeros(wl.M, np.int32)
+    want[wl.M - 1] = 1
+    assert np.array_equal(out["flags"], want) and out["err_count"] == 1
+    assert out["C"][wl.M - 1, wl.N - 1] == np.int32(np.uint32(ref.C[wl.M - 1, wl.N - 1]) ^ np.uint32(1 << 31))
+
+
+def test_deterministic_across_runs(binding, gpu_util):
+    ops = wlmod.make_operands(3)
+    say("determinism")
+    run = gpu_util.GpuRun(binding, ops.B)
+    a = run.gemm(ops.A)
+    b = run.gemm(ops.A)
+    assert np.array_equal(a["C"], b["C"]) and np.array_equal(a["flags"], b["flags"])
