@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libabftgemm.so")
-SOURCES = ["api.hip", "pack.hip", "gemm_tile.hip", "gemm_smallm.hip", "rowops.hip"]
+SOURCES = ["api.hip", "pack.hip", "gemm_tile.hip", "gemm_tile_t256.hip", "gemm_tile_t256w24.hip", "gemm_tile_t256w42.hip",
+           "gemm_tile_t128.hip", "gemm_tile_t64.hip", "gemm_smallm.hip", "rowops.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

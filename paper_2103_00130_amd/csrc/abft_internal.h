@@ -84,7 +84,7 @@ struct GemmParams {
 
 constexpr int kWsHeaderInts = 16;
 
-enum Variant { kTile256 = 1, kTile128 = 2, kTile64 = 3, kSmallM = 4 };
+enum Variant { kTile256 = 1, kTile128 = 2, kTile64 = 3, kSmallM = 4, kTile256w24 = 5, kTile256w42 = 6, kVariantEnd = 7 };
 
 // launchers (each returns the hipError_t of its launch)
 hipError_t launch_pack(const int8_t* B, int64_t ldb, int transposed, abft_packed_b* h, hipStream_t s);

@@ -196,7 +196,7 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
     if (variant == abft::kSmallM) {
         if (M > 64) return fail(ABFT_EUNSUPPORTED, "%s: the streaming variant takes M <= 64, got %d", fn, M);
         e = abft::launch_gemm_smallm(check, want_c, want_q, p, (hipStream_t)stream);
-    } else if (variant >= abft::kTile256 && variant <= abft::kTile64) {
+    } else if (variant >= abft::kTile256 && variant < abft::kVariantEnd) {
         e = abft::launch_gemm_tile(variant, check, want_c, want_q, p, (hipStream_t)stream);
     } else {
         return fail(ABFT_EINVAL, "%s: unknown variant %d", fn, variant);
