@@ -2,17 +2,19 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libabftgemm.so")
-SOURCES = ["api.hip", "pack.hip", "gemm_tile.hip", "gemm_tile_t256.hip", "gemm_tile_t256w24.hip", "gemm_tile_t256w42.hip",
-           "gemm_tile_t128.hip", "gemm_tile_t64.hip", "gemm_smallm.hip", "rowops.hip"]
+SOURCES = ["api.hip", "pack.hip", "gemm_tile.hip", "gemm_tile_a256.hip", "gemm_tile_a256w24.hip", "gemm_tile_a256w42.hip",
+           "gemm_tile_a128.hip", "gemm_tile_a64.hip", "gemm_tile_g128.hip", "gemm_tile_g64.hip", "gemm_smallm.hip",
+           "rowops.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
     # packed-FP32 instruction selection is switched off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-ffp-contract=off",

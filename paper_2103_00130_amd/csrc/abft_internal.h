@@ -42,7 +42,7 @@ __host__ __device__ inline int64_t limb_offset(int k, int digit) {
 
 struct abft_packed_b {
     int K, N;
-    int KB;            // k-blocks of 64
+    int KB;            // k-blocks of 64, rounded up to an even count (zero padded)
     int NT;            // n-tiles of 256
     int device;
     int8_t* packed;    // NT*KB*8 units
@@ -64,7 +64,8 @@ struct RequantDev {
 struct GemmParams {
     const uint8_t* A;
     int64_t lda;
-    int M, N, K, KB;
+    int M, N, K, KB;           // KB: k-blocks of 64 in the packed weight (even)
+    int KB2;                   // stages of 128 k-values = KB / 2
     int a_vec_ok;              // A and lda are multiples of 16 bytes
     const int8_t* packed;
     const int8_t* limbs;
@@ -79,10 +80,13 @@ struct GemmParams {
     RequantDev rq;
     const void* inj;           // abft_inject_t[n_inj]
     int n_inj;
-    int32_t* ws;               // workspace: [0] ticket, [16..16+M) row differences
+    int32_t* ws;               // workspace: [0] arrival counter, [16..) per-row differences (tiled: [M]; streaming: [32][64])
 };
 
 constexpr int kWsHeaderInts = 16;
+// the streaming kernel spreads its per-row sums over kSmallMSlots slots of kSmallMRows rows
+constexpr int kSmallMSlots = 32;
+constexpr int kSmallMRows = 64;
 
 enum Variant { kTile256 = 1, kTile128 = 2, kTile64 = 3, kSmallM = 4, kTile256w24 = 5, kTile256w42 = 6, kVariantEnd = 7 };
 

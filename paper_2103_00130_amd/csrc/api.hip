@@ -40,7 +40,11 @@ void free_handle(abft_packed_b* h) {
     delete h;
 }
 
-size_t ws_ints(int M) { return (size_t)abft::kWsHeaderInts + (((size_t)M + 63) / 64) * 64; }
+size_t ws_ints(int M) {
+    const size_t rows = (((size_t)M + 63) / 64) * 64;
+    const size_t streaming = (size_t)abft::kSmallMSlots * abft::kSmallMRows;
+    return (size_t)abft::kWsHeaderInts + (rows > streaming ? rows : streaming);
+}
 
 }  // namespace
 
@@ -60,7 +64,7 @@ int abft_pack_b_checksum(const int8_t* B, int64_t ldb, int K, int N, int b_is_tr
     std::memset(h, 0, sizeof *h);
     h->K = K;
     h->N = N;
-    h->KB = (K + abft::kUnitK - 1) / abft::kUnitK;
+    h->KB = ((K + 2 * abft::kUnitK - 1) / (2 * abft::kUnitK)) * 2;
     h->NT = (N + abft::kTileN - 1) / abft::kTileN;
     hipError_t e = hipGetDevice(&h->device);
     const size_t packed_bytes = (size_t)h->NT * h->KB * abft::kUnitsPerTile * abft::kUnitBytes;
@@ -162,6 +166,7 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
     p.N = Bp->N;
     p.K = Bp->K;
     p.KB = Bp->KB;
+    p.KB2 = Bp->KB / 2;
     p.a_vec_ok = (((uintptr_t)A | (uintptr_t)lda) & 15) == 0;
     p.packed = Bp->packed;
     p.limbs = Bp->limbs;
@@ -185,17 +190,21 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
     p.ws = (int32_t*)workspace;
 
     int variant = (int)((flags & ABFT_VARIANT_MASK) >> 8);
-    if (variant == 0) {
-        // largest tile that still gives every compute unit a workgroup
+    const bool chosen = variant != 0;
+    auto pick_tile = [&]() {
+        // largest tile that still gives (nearly) every compute unit a workgroup
         auto tiles = [&](int b) { return (int64_t)((M + b - 1) / b) * ((Bp->N + b - 1) / b); };
-        if (tiles(256) >= 192) variant = abft::kTile256;
-        else if (tiles(128) >= 192) variant = abft::kTile128;
-        else variant = abft::kTile64;
-    }
+        if (tiles(256) >= 192) return (int)abft::kTile256;
+        if (tiles(128) >= 192) return (int)abft::kTile128;
+        return (int)abft::kTile64;
+    };
+    if (!chosen) variant = M <= 64 ? (int)abft::kSmallM : pick_tile();
     hipError_t e;
     if (variant == abft::kSmallM) {
         if (M > 64) return fail(ABFT_EUNSUPPORTED, "%s: the streaming variant takes M <= 64, got %d", fn, M);
         e = abft::launch_gemm_smallm(check, want_c, want_q, p, (hipStream_t)stream);
+        if (e == hipErrorNotSupported && !chosen)  // unaligned A: the general tiled path takes it
+            e = abft::launch_gemm_tile(pick_tile(), check, want_c, want_q, p, (hipStream_t)stream);
     } else if (variant >= abft::kTile256 && variant < abft::kVariantEnd) {
         e = abft::launch_gemm_tile(variant, check, want_c, want_q, p, (hipStream_t)stream);
     } else {

@@ -1,6 +1,286 @@
-// Streaming checked GEMM for M <= 64 (placeholder until the kernel lands).
+// Streaming checked u8 x s8 -> s32 GEMM for M <= 64 (tall-skinny, batch-of-requests shapes).
+//
+// Algorithm 1 of arXiv 2103.00130 (product with the encoded B, row sums, comparison) for the
+// shapes where the weight matrix is read once and barely reused: the kernel is bound by
+// streaming the packed B from HBM, so the design goal is bytes in flight, not MFMA rate.
+//
+//  * One workgroup owns 16 columns for the whole K range; its four wavefronts take the
+//    k-blocks kb = wave, wave+4, ... and issue their loads in batches, two batches in flight,
+//    so that the grid as a whole keeps the entire weight matrix in flight.  No LDS staging:
+//    a 16x16x64 int8 MFMA B operand is read straight from the packed layout (four 256-byte
+//    runs per instruction), the A operand straight from A (it is small and lives in L2).
+//  * u8 -> s8 by XOR 0x80 on the A operand, +128 * (column sum of the streamed B bytes) added
+//    back; the checksum column S_B rides as four base-256 digit columns on a second MFMA; the
+//    column blocks split its K range between them.
+//  * The four partial accumulators meet in LDS; wavefront 0 adds them, forms the row sums with
+//    DPP row reductions, and adds (row sum - checksum) per row into one of 32 workspace slots
+//    (returned integer atomics, at most a handful of workgroups per address).  The last
+//    workgroup to arrive sums the slots, writes flags and count, and zeroes the workspace.
+#include "../../include/abft_gemm.h"
 #include "abft_internal.h"
 
 namespace abft {
-hipError_t launch_gemm_smallm(bool, bool, bool, const GemmParams&, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+constexpr int kOutC = 1, kOutQ = 2;
+
+__device__ inline uint8_t requant_one(int32_t v, int32_t cs, int col, const RequantDev& rq) {
+    uint32_t t = (uint32_t)v - (uint32_t)rq.zA * (uint32_t)cs;
+    if (rq.bias) t += (uint32_t)rq.bias[col];
+    const float m = rq.mult[rq.per_channel ? col : 0];
+    const float p = __fmul_rn((float)(int32_t)t, m);
+    float y = __builtin_rintf(p) + (float)rq.zC;
+    y = fminf(fmaxf(y, 0.0f), 255.0f);
+    return (uint8_t)y;
+}
+
+// sum over the 16 lanes of a DPP row; every lane of the row ends up with the total
+__device__ inline uint32_t row_sum16(uint32_t s) {
+    s += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+    s += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+    s += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s, 0x141, 0xF, 0xF, true);  // row_half_mirror
+    s += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s, 0x140, 0xF, 0xF, true);  // row_mirror
+    return s;
+}
+
+// RB = 16-row blocks of A (M <= 16*RB)
+template <int RB, bool kCheck, int kOut>
+__global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, const int n_blocks) {
+    constexpr int BATCH = RB == 1 ? 8 : 4;  // k-blocks per wave per batch of loads
+    constexpr bool kWantC = (kOut & kOutC) != 0, kWantQ = (kOut & kOutQ) != 0;
+    __shared__ v4i s_acc[3][RB][64];
+    __shared__ v4i s_chk[3][RB][64];
+    __shared__ uint32_t s_bsum[3][64];
+    __shared__ int s_ctl[2];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int cb = blockIdx.x, col0 = cb * 16;
+    const int KB = p.KB;
+    const int lcol = lane & 15, lkg = lane >> 4;
+
+    // B operand of k-block kb: unit of col0, columns 16*half .. +15, k-group lkg
+    const int8_t* const b_src = p.packed + packed_unit_offset(col0 / kTileN, 0, (col0 % kTileN) / kUnitN, KB) +
+                                (lkg * kUnitN + (col0 % kUnitN) + lcol) * 16;
+    constexpr int64_t B_KB_STRIDE = (int64_t)kUnitsPerTile * kUnitBytes;
+    // A operand of row block rb: row rb*16 + lcol (clamped), k-group lkg
+    const uint8_t* a_row[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) a_row[rb] = p.A + (int64_t)min(rb * 16 + lcol, p.M - 1) * p.lda;
+    // this column block's share of the checksum product's K range
+    const int lo = (int)(((int64_t)cb * KB) / n_blocks), hi = (int)(((int64_t)(cb + 1) * KB) / n_blocks);
+
+    v4i acc[RB], cacc[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) acc[rb] = cacc[rb] = v4i{0, 0, 0, 0};
+    uint32_t bsum = 0;
+
+    v4i fb[2][BATCH], fa[2][BATCH][RB], fl[2][BATCH];
+    auto issue = [&](int kb0, int s) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int kb = kb0 + 4 * u;
+            const int kbc = min(kb, KB - 1);
+            // a k-block past the end is fetched from the last one and zeroed below
+            fb[s][u] = *reinterpret_cast<const v4i*>(b_src + (int64_t)kbc * B_KB_STRIDE);
+            const int k = min(kbc * 64 + lkg * 16, p.K - 16);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) fa[s][u][rb] = *reinterpret_cast<const v4i*>(a_row[rb] + k);
+            if (kCheck) {
+                fl[s][u] = v4i{0, 0, 0, 0};
+                if (kb >= lo && kb < hi && lcol < kLimbs)
+                    fl[s][u] = *reinterpret_cast<const v4i*>(p.limbs + ((((int64_t)kb * 4 + lkg) * kLimbs + lcol) << 4));
+            }
+        }
+    };
+    auto consume = [&](int kb0, int s) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int kb = kb0 + 4 * u;
+            v4i b = fb[s][u];
+            if (kb >= KB) b = v4i{0, 0, 0, 0};
+            // bytes of B as biased uint8, summed four at a time; the bias comes off at the end
+            bsum = __builtin_amdgcn_sad_u8((uint32_t)b.x ^ 0x80808080u, 0u, bsum);
+            bsum = __builtin_amdgcn_sad_u8((uint32_t)b.y ^ 0x80808080u, 0u, bsum);
+            bsum = __builtin_amdgcn_sad_u8((uint32_t)b.z ^ 0x80808080u, 0u, bsum);
+            bsum = __builtin_amdgcn_sad_u8((uint32_t)b.w ^ 0x80808080u, 0u, bsum);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                const v4i a = fa[s][u][rb] ^ (int)0x80808080;
+                acc[rb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[rb], 0, 0, 0);
+                if (kCheck) cacc[rb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, fl[s][u], cacc[rb], 0, 0, 0);
+            }
+        }
+    };
+
+    // k-blocks of this wave: wave, wave+4, ...; the same number of batches for every wave
+    const int per_wave = (KB + 3) / 4;
+    const int n_batches = (per_wave + BATCH - 1) / BATCH;
+    issue(wave, 0);
+    for (int bt = 0; bt < n_batches; bt += 2) {
+        if (bt + 1 < n_batches) issue(wave + 4 * BATCH * (bt + 1), 1);
+        consume(wave + 4 * BATCH * bt, 0);
+        if (bt + 1 < n_batches) {
+            if (bt + 2 < n_batches) issue(wave + 4 * BATCH * (bt + 2), 0);
+            consume(wave + 4 * BATCH * (bt + 1), 1);
+        }
+    }
+
+    // ---- the four partial results meet in wavefront 0 --------------------------------
+    if (wave > 0) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            s_acc[wave - 1][rb][lane] = acc[rb];
+            if (kCheck) s_chk[wave - 1][rb][lane] = cacc[rb];
+        }
+        s_bsum[wave - 1][lane] = bsum;
+    }
+    __syncthreads();
+    int32_t atom_old = 0;
+    if (wave == 0) {
+#pragma unroll
+        for (int w = 0; w < 3; ++w) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                acc[rb] += s_acc[w][rb][lane];
+                if (kCheck) cacc[rb] += s_chk[w][rb][lane];
+            }
+            bsum += s_bsum[w][lane];
+        }
+        // column sum of the streamed B for column lcol: the four k-groups sit in lanes lcol + 16*g
+        bsum += (uint32_t)__shfl_xor((int)bsum, 16);
+        bsum += (uint32_t)__shfl_xor((int)bsum, 32);
+        // every lane summed 16 biased bytes per k-block slot; 4 waves x n_batches x BATCH slots x 4 k-groups
+        const uint32_t bias = 128u * 16u * 4u * 4u * (uint32_t)(n_batches * BATCH);
+        const int32_t cs128 = 128 * (int32_t)(bsum - bias);
+
+        // accumulator layout of the 16x16 MFMA: lane l, element e is row 4*(l/16) + e, column l%16
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[rb][e] += cs128;
+
+        if (p.n_inj > 0) {
+            // simulated faults in the 32-bit intermediate (test hook): XOR before the row sums
+            const abft_inject_t* inj = reinterpret_cast<const abft_inject_t*>(p.inj);
+            for (int n = 0; n < p.n_inj; ++n) {
+                const int r = inj[n].row, c = inj[n].col - col0;
+                if (r < 0 || r >= p.M || r >= 16 * RB || c < 0 || c >= 16 || inj[n].col >= p.N) continue;
+                const bool mine = (lcol == c) && (lkg == ((r & 15) >> 2));
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (mine && rb == (r >> 4) && e == (r & 3)) acc[rb][e] ^= (int)inj[n].xor_mask;
+            }
+        }
+
+        if (kCheck) {
+            const int slot = cb & (kSmallMSlots - 1);
+            const uint32_t total128 = cb == 0 ? 128u * (uint32_t)(*p.total) : 0u;  // sum_k 128*S_B[k], once per row
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t rs = row_sum16((uint32_t)acc[rb][e]);
+                    uint32_t ck = lcol < kLimbs ? ((uint32_t)cacc[rb][e] << (8 * lcol)) : 0u;
+                    ck += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)ck, 0xB1, 0xF, 0xF, true);
+                    ck += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)ck, 0x4E, 0xF, 0xF, true);
+                    const int row = rb * 16 + 4 * lkg + e;
+                    const uint32_t d = rs - ck - total128;
+                    // fetch-add WITH return: the add has been performed at device scope once
+                    // the old value is back, which is what the arrival counter relies on
+                    if (lcol == 0 && row < p.M && d != 0)
+                        atom_old |= __hip_atomic_fetch_add(p.ws + kWsHeaderInts + slot * kSmallMRows + row, (int)d,
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+        }
+
+        // stores: per (rb, e) one instruction covers 4 rows x 16 columns
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int row = rb * 16 + 4 * lkg + e, col = col0 + lcol;
+                if (row < p.M && col < p.N) {
+                    if (kWantC) p.C[(int64_t)row * p.ldc + col] = acc[rb][e];
+                    if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_one(acc[rb][e], p.colsum[col], col, p.rq);
+                }
+            }
+    }
+
+    if (kCheck) {
+        // arrival count; the last workgroup sums the slots (see the tiled kernel for why no
+        // cache maintenance is needed)
+        if (wave == 0) s_bsum[0][lane] = (uint32_t)atom_old;  // waits for the returned adds
+        __syncthreads();
+        if (tid == 0) {
+            const int t = __hip_atomic_fetch_add(p.ws, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_ctl[0] = (t == (int)gridDim.x - 1);
+            s_ctl[1] = 0;
+        }
+        __syncthreads();
+        if (s_ctl[0]) {
+            // thread (row, part): 4 threads per row, each sums 8 of the 32 slots
+            const int row = tid >> 2, part = tid & 3;
+            uint32_t d = 0;
+            if (row < p.M) {
+                int v[kSmallMSlots / 4];
+#pragma unroll
+                for (int u = 0; u < kSmallMSlots / 4; ++u)
+                    v[u] = __hip_atomic_load(p.ws + kWsHeaderInts + (part * (kSmallMSlots / 4) + u) * kSmallMRows + row,
+                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int u = 0; u < kSmallMSlots / 4; ++u) {
+                    d += (uint32_t)v[u];
+                    if (v[u] != 0)
+                        __hip_atomic_store(p.ws + kWsHeaderInts + (part * (kSmallMSlots / 4) + u) * kSmallMRows + row, 0,
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            d += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)d, 0xB1, 0xF, 0xF, true);
+            d += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)d, 0x4E, 0xF, 0xF, true);
+            if (part == 0 && row < p.M) {
+                p.row_flags[row] = d != 0;
+                if (d != 0) atomicAdd(&s_ctl[1], 1);
+            }
+            __syncthreads();
+            if (tid == 0) {
+                if (p.err_count) *p.err_count = s_ctl[1];
+                __hip_atomic_store(p.ws, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+template <int RB>
+hipError_t launch_rb(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
+    const int n_blocks = (p.N + 15) / 16;
+    const dim3 grid((unsigned)n_blocks), block(256);
+#define ABFT_LAUNCH(CK, OUT)                                                    \
+    do {                                                                        \
+        gemm_smallm_kernel<RB, CK, OUT><<<grid, block, 0, s>>>(p, n_blocks);    \
+        return hipGetLastError();                                               \
+    } while (0)
+#define ABFT_OUT(CK)                                          \
+    do {                                                      \
+        if (want_c && want_q) ABFT_LAUNCH(CK, kOutC | kOutQ); \
+        if (want_c) ABFT_LAUNCH(CK, kOutC);                   \
+        ABFT_LAUNCH(CK, kOutQ);                               \
+    } while (0)
+    if (check) ABFT_OUT(true);
+    ABFT_OUT(false);
+#undef ABFT_OUT
+#undef ABFT_LAUNCH
+}
+
+}  // namespace
+
+hipError_t launch_gemm_smallm(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
+    if (p.M > 64 || !p.a_vec_ok || p.K % 16 != 0) return hipErrorNotSupported;
+    if (p.M <= 16) return launch_rb<1>(check, want_c, want_q, p, s);
+    if (p.M <= 32) return launch_rb<2>(check, want_c, want_q, p, s);
+    return launch_rb<4>(check, want_c, want_q, p, s);
+}
+
 }  // namespace abft

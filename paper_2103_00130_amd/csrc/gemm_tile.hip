@@ -2,19 +2,29 @@
 #include "abft_internal.h"
 
 namespace abft {
-hipError_t launch_gemm_tile_t256(bool, bool, bool, const GemmParams&, hipStream_t);
-hipError_t launch_gemm_tile_t256w24(bool, bool, bool, const GemmParams&, hipStream_t);
-hipError_t launch_gemm_tile_t256w42(bool, bool, bool, const GemmParams&, hipStream_t);
-hipError_t launch_gemm_tile_t128(bool, bool, bool, const GemmParams&, hipStream_t);
-hipError_t launch_gemm_tile_t64(bool, bool, bool, const GemmParams&, hipStream_t);
+#define ABFT_DECL(name) hipError_t launch_gemm_tile_##name(bool, bool, bool, const GemmParams&, hipStream_t)
+ABFT_DECL(a256);
+ABFT_DECL(a256w24);
+ABFT_DECL(a256w42);
+ABFT_DECL(a128);
+ABFT_DECL(a64);
+ABFT_DECL(g128);
+ABFT_DECL(g64);
+#undef ABFT_DECL
 
 hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
+    // direct-to-LDS kernels need whole, aligned 16-byte chunks of A
+    const bool fast_a = p.a_vec_ok && (p.K % 16 == 0);
+    if (!fast_a) {
+        if (variant == kTile64) return launch_gemm_tile_g64(check, want_c, want_q, p, s);
+        return launch_gemm_tile_g128(check, want_c, want_q, p, s);
+    }
     switch (variant) {
-        case kTile256: return launch_gemm_tile_t256(check, want_c, want_q, p, s);
-        case kTile128: return launch_gemm_tile_t128(check, want_c, want_q, p, s);
-        case kTile64: return launch_gemm_tile_t64(check, want_c, want_q, p, s);
-        case kTile256w24: return launch_gemm_tile_t256w24(check, want_c, want_q, p, s);
-        case kTile256w42: return launch_gemm_tile_t256w42(check, want_c, want_q, p, s);
+        case kTile256: return launch_gemm_tile_a256(check, want_c, want_q, p, s);
+        case kTile128: return launch_gemm_tile_a128(check, want_c, want_q, p, s);
+        case kTile64: return launch_gemm_tile_a64(check, want_c, want_q, p, s);
+        case kTile256w24: return launch_gemm_tile_a256w24(check, want_c, want_q, p, s);
+        case kTile256w42: return launch_gemm_tile_a256w42(check, want_c, want_q, p, s);
         default: return hipErrorInvalidValue;
     }
 }

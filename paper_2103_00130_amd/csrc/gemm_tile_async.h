@@ -1,0 +1,540 @@
+// Checked u8 x s8 -> s32 GEMM for gfx950: LDS-tiled int8-MFMA kernel whose tiles are
+// filled by direct global->LDS loads (the fast path: A and lda multiples of 16 bytes,
+// K a multiple of 16).
+//
+// Algorithm 1 of arXiv 2103.00130 from the product line on: C_temp = A * [B | S_B] in ONE
+// pass over A (Section IV-A-3, the checksum rides the level-3 product), then tSum per row,
+// the comparison of Eq. 2b and errCount, then (optionally) the requantization of
+// Section III-B, which never sees the checksum column (Section IV-B).
+//
+// Mapping to the hardware
+//  * Stage = 128 k-values.  A rows are fetched as whole 128-byte lines (8 lanes x 16 B per
+//    row) straight into LDS; each lane picks the 16-byte chunk  slot ^ ((row >> 1) & 7)  of
+//    its row, so the 128-byte-pitch LDS image is XOR-swizzled and the MFMA fragment reads
+//    (32 rows x 16 B) spread over all banks.  Packed B is already in fragment order and is
+//    copied 1 KiB per wavefront instruction.  Two stages are resident (2 x (BM+BN) x 128 B);
+//    the loads of stage s+1 are issued at the top of stage s and awaited at its last
+//    quarter, where the single barrier of the stage sits.
+//  * A is uint8, the matrix cores are signed x signed: fragments of A are XOR-ed with 0x80
+//    (a - 128) after the LDS read and 128 * (column sum of the streamed B bytes) is added
+//    back in the epilogue: exact modulo 2^32 for whatever B is in memory.
+//  * The int32 checksum column S_B enters the same MFMA pipeline as four signed base-256
+//    digit columns (a fifth B operand with 4 live columns); the tile columns of the grid
+//    split its K range (tile column c takes a contiguous share of the stages).  Row sums
+//    minus checksum go per row into the workspace with one returned integer atomic; the
+//    last workgroup to arrive writes flags and count and zeroes the workspace.
+#pragma once
+#include <type_traits>
+
+#include "../../include/abft_gemm.h"
+#include "abft_internal.h"
+
+namespace abft {
+namespace atile {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+#define ABFT_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define ABFT_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+constexpr int kOutC = 1, kOutQ = 2;
+constexpr int BK = 128;  // k-values per stage
+
+__device__ inline uint8_t requant_one(int32_t v, int32_t cs, int col, const RequantDev& rq) {
+    uint32_t t = (uint32_t)v - (uint32_t)rq.zA * (uint32_t)cs;
+    if (rq.bias) t += (uint32_t)rq.bias[col];
+    const float m = rq.mult[rq.per_channel ? col : 0];
+    const float p = __fmul_rn((float)(int32_t)t, m);
+    float y = __builtin_rintf(p) + (float)rq.zC;
+    y = fminf(fmaxf(y, 0.0f), 255.0f);
+    return (uint8_t)y;
+}
+
+// sum over the 32 lanes that share lane>>5: DPP adds inside rows of 16 lanes, then one
+// v_permlane16_swap (rows 0<->1 and 2<->3 change places) for the last step; all VALU
+__device__ inline uint32_t sum32(uint32_t s) {
+    s += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+    s += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+    s += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s, 0x141, 0xF, 0xF, true);  // row_half_mirror
+    s += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s, 0x140, 0xF, 0xF, true);  // row_mirror
+    const auto sw = __builtin_amdgcn_permlane16_swap(s, s, false, false);
+    return sw[0] + sw[1];
+}
+
+template <int BM, int BN, int WGM, int WGN, bool kCheck, int kOut>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const GemmParams p, const int tiles_m,
+                                                                        const int tiles_n) {
+    constexpr int NW = WGM * WGN, NT = NW * 64;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
+    constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 blocks per wave
+    constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK;
+    constexpr int A_LD = (BM / 8) / NW;            // async A loads per wave per stage (8 rows each)
+    constexpr int B_LD = (BN / 8) / NW;            // async B loads per wave per stage (1 KiB each)
+    constexpr int CB = (WTM / 16) / WGN;           // 16-row checksum blocks per wave
+    constexpr bool kWantC = (kOut & kOutC) != 0, kWantQ = (kOut & kOutQ) != 0;
+    static_assert(A_LD >= 1 && B_LD >= 1 && CB >= 1 && (WTM / 16) % WGN == 0, "tile too small for the workgroup");
+    static_assert(BN >= 64 && NT <= 4 * BN, "epilogue scratch layout");
+
+    // LDS: [2][A_STAGE] then [2][B_STAGE]
+    extern __shared__ __align__(1024) uint8_t smem[];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) uint8_t*)smem);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    // Workgroups go round-robin over the 8 XCDs; give every XCD a compact block of tiles
+    // (consecutive ids inside an XCD walk down a strip of 4 tile rows) so that its L2 sees
+    // few distinct A and B panels.
+    int tile_m, tile_n;
+    {
+        const int n_tiles = tiles_m * tiles_n;
+        int t = blockIdx.x;
+        if (n_tiles % 8 == 0) t = (blockIdx.x & 7) * (n_tiles >> 3) + (blockIdx.x >> 3);
+        const int strip_h = tiles_m >= 4 ? 4 : tiles_m;
+        const int per_strip = strip_h * tiles_n;
+        const int strip = t / per_strip, r = t - strip * per_strip;
+        const int h = min(strip_h, tiles_m - strip * strip_h);  // last strip may be shorter
+        tile_n = r / h;
+        tile_m = strip * strip_h + r - tile_n * h;
+    }
+    const int row0 = tile_m * BM, col0 = tile_n * BN;
+    const int NS = p.KB2;  // stages of 128 k-values
+
+    // ---- direct global->LDS loads ---------------------------------------------------
+    // One instruction moves 16 bytes per lane to LDS address m0 + lane*16.  They are issued
+    // through inline asm so that the compiler keeps treating the LDS reads of the resident
+    // stage as independent of them; completion is awaited explicitly (vmcnt) before the
+    // barrier that publishes a stage.
+    auto async16 = [](const void* g, uint32_t lds_addr) __attribute__((always_inline)) {
+        // one wait state between the write of m0 and the instruction that reads it
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "m0", "memory");
+    };
+    // A: instruction i of this wave covers rows (wave*A_LD + i)*8 .. +8 of the tile; lane l
+    // takes row l>>3 of those and the 16-byte chunk (l&7) ^ ((row>>1)&7) of the stage.
+    const uint8_t* a_row[A_LD];
+    int a_c16[A_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        const int r = (wave * A_LD + i) * 8 + (lane >> 3);
+        a_row[i] = p.A + (int64_t)min(row0 + r, p.M - 1) * p.lda;
+        a_c16[i] = ((lane & 7) ^ ((r >> 1) & 7)) * 16;
+    }
+    constexpr int TILES_PER_NT = kTileN / BN;
+    const int8_t* const b_src = p.packed +
+        packed_unit_offset(tile_n / TILES_PER_NT, 0, (tile_n % TILES_PER_NT) * (BN / 32), p.KB2 * 2) + lane * 16;
+    constexpr int64_t B_KB_STRIDE = (int64_t)kUnitsPerTile * kUnitBytes;
+    constexpr int B_CHUNKS_PER_KB = BN / 16;  // 1 KiB chunks of this tile per k-block of 64
+    const uint32_t lds_wave_a = __builtin_amdgcn_readfirstlane(lds_base + wave * A_LD * 1024);
+
+    // load n of a stage: n < A_LD is an A load (8 rows x 128 B), the rest are B loads (1 KiB of
+    // packed B).  A chunk of A at or past K is re-read from the last whole chunk (it meets zero
+    // rows of B).
+    constexpr int N_LD = A_LD + B_LD;
+    auto issue_load = [&](int s, int buf, int n) __attribute__((always_inline)) {
+        if (n < A_LD) {
+            const int k = min(s * BK + a_c16[n], p.K - 16);
+            async16(a_row[n] + k, lds_wave_a + buf * A_STAGE + n * 1024);
+        } else {
+            const int bc = __builtin_amdgcn_readfirstlane(wave * B_LD + (n - A_LD));
+            const int kbl = bc / B_CHUNKS_PER_KB, cc = bc % B_CHUNKS_PER_KB;
+            async16(b_src + (int64_t)(2 * s + kbl) * B_KB_STRIDE + cc * 1024,
+                    lds_base + 2 * A_STAGE + buf * B_STAGE + kbl * (BN * 64) + cc * 1024);
+        }
+    };
+
+    // ---- fragment reads -----------------------------------------------------------
+    // A fragment (block i, k-step j): lane l holds row wm*WTM + i*32 + (l&31), chunk 2j + (l>>5)
+    const int a_swz = (lane >> 1) & 7;
+    int a_off[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a_off[j] = (wm * WTM + (lane & 31)) * BK + (((2 * j + (lane >> 5)) ^ a_swz) << 4);
+    const int b_off = 2 * A_STAGE + wn * TN * 2048 + lane * 16;
+
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+    v4i cacc[CB];
+#pragma unroll
+    for (int i = 0; i < CB; ++i) cacc[i] = v4i{0, 0, 0, 0};
+    // column sums of the B bytes streamed (every wave keeps them for its own columns)
+    uint32_t bsum[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bsum[j] = 0;
+
+    v4i fa[2][TM], fb[2][TN];
+    auto read_frags = [&](int buf, int j, int f) __attribute__((always_inline)) {
+        const uint8_t* sA = smem + buf * A_STAGE;
+        const uint8_t* sB = smem + buf * B_STAGE;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa[f][i] = *reinterpret_cast<const v4i*>(sA + a_off[j] + i * 32 * BK);
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+            fb[f][t] = *reinterpret_cast<const v4i*>(sB + (j >> 1) * (BN * 64) + b_off + t * 2048 + (j & 1) * 1024);
+    };
+    // Checksum digits as the B operand of a 16x16x64 MFMA (one per k-block of the stage):
+    // lane l holds digit column l&15 (zero beyond 3) and k-group l>>4.  The matching A operand
+    // is row (l&15) of a 16-row block, chunk 4*kbl + (l>>4) of the stage.
+    v4i limb[2];
+    limb[0] = limb[1] = v4i{0, 0, 0, 0};
+    auto load_limbs = [&](int s) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kbl = 0; kbl < 2; ++kbl) {
+            limb[kbl] = v4i{0, 0, 0, 0};
+            if ((lane & 15) < kLimbs)
+                limb[kbl] = *reinterpret_cast<const v4i*>(
+                    p.limbs + ((((int64_t)(2 * s + kbl) * 4 + (lane >> 4)) * kLimbs + (lane & 15)) << 4));
+        }
+    };
+    int ck_off[2];
+#pragma unroll
+    for (int kbl = 0; kbl < 2; ++kbl)
+        ck_off[kbl] = (wm * WTM + wn * CB * 16 + (lane & 15)) * BK + (((4 * kbl + (lane >> 4)) ^ a_swz) << 4);
+    // One k-step of 32: TM x TN MFMAs on fragment set f.  After each row of MFMAs one slice of
+    // the pending direct-to-LDS loads [ld_lo, ld_hi) of stage ld_s is issued, so that vector
+    // memory instructions are spread between MFMAs instead of arriving in a burst.  When
+    // SUM_B, the B bytes of this k-step are added into the column sums: XOR 0x80 turns int8
+    // into a biased uint8 whose four bytes v_sad_u8 sums against zero (the bias, 128 per byte,
+    // is taken off in the epilogue).
+    auto mma = [&](int f, auto sum_b_c, int ld_s, int ld_buf, int ld_lo, int ld_hi) __attribute__((always_inline)) {
+        constexpr bool SUM_B = decltype(sum_b_c)::value;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            // a - 128 as int8: done here, on data that is already in registers, so that no
+            // VALU instruction ever waits on an LDS read inside the MFMA stream
+            const v4i a = fa[f][i] ^ (int)0x80808080;
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+                acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, fb[f][t], acc[i][t], 0, 0, 0);
+#pragma unroll
+            for (int n = ld_lo + (ld_hi - ld_lo) * i / TM; n < ld_lo + (ld_hi - ld_lo) * (i + 1) / TM; ++n)
+                issue_load(ld_s, ld_buf, n);
+        }
+        if (SUM_B) {
+#pragma unroll
+            for (int t = 0; t < TN; ++t) {
+                bsum[t] = __builtin_amdgcn_sad_u8((uint32_t)fb[f][t].x ^ 0x80808080u, 0u, bsum[t]);
+                bsum[t] = __builtin_amdgcn_sad_u8((uint32_t)fb[f][t].y ^ 0x80808080u, 0u, bsum[t]);
+                bsum[t] = __builtin_amdgcn_sad_u8((uint32_t)fb[f][t].z ^ 0x80808080u, 0u, bsum[t]);
+                bsum[t] = __builtin_amdgcn_sad_u8((uint32_t)fb[f][t].w ^ 0x80808080u, 0u, bsum[t]);
+            }
+        }
+    };
+    auto wait_lds = []() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0xC07F); };
+    auto wait_vmem = []() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };
+    // interleave hint: the LDS reads of the next fragments go one by one between MFMAs
+    auto hint_mfma_lds = []() __attribute__((always_inline)) {
+#ifndef ABFT_NO_HINTS
+#pragma unroll
+        for (int g = 0; g < TM + TN; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+#endif
+    };
+
+    constexpr int LD_HALF = N_LD / 2;
+    static_assert(N_LD % 2 == 0, "loads of a stage are issued in two halves");
+#pragma unroll
+    for (int n = 0; n < N_LD; ++n) issue_load(0, 0, n);
+    wait_vmem();
+    __syncthreads();
+    // first half of stage 1 (the second half goes out during the first k-step of stage 0)
+#pragma unroll
+    for (int n = 0; n < LD_HALF; ++n) issue_load(min(1, NS - 1), 1, n);
+    read_frags(0, 0, 0);
+    wait_lds();
+    __builtin_amdgcn_sched_barrier(0);
+
+    int cur = 0;
+    // A run of stages [s_begin, s_end) with or without the checksum-digit MFMAs (separate loops
+    // keep every loop body one straight block).  PH says on which k-steps this wave adds the B
+    // bytes it holds into the column sums: the waves that share a column range (same wn) take
+    // alternate k-steps (0: even, 1: odd), a lone wave takes all (2).
+    // Load schedule: the loads of stage s+1 go out in two halves, the first during the last
+    // k-step of stage s-1 (into the buffer that has just been released), the second during the
+    // first k-step of stage s; they are awaited at the end of the third k-step of stage s.  A
+    // stage index past the end re-reads the last stage into a dead buffer.
+    auto run = [&](int s_begin, int s_end, auto chk_c, auto ph_c) __attribute__((always_inline)) {
+        constexpr bool CHK = decltype(chk_c)::value;
+        constexpr int PH = decltype(ph_c)::value;
+        using even_c = std::integral_constant<bool, PH != 1>;
+        using odd_c = std::integral_constant<bool, PH != 0>;
+        for (int s = s_begin; s < s_end; ++s) {
+            const int s1 = min(s + 1, NS - 1), s2 = min(s + 2, NS - 1);
+            // the digit operands of this stage are needed three quarters of a stage from now
+            if (CHK) load_limbs(s);
+            read_frags(cur, 1, 1);
+            mma(0, even_c{}, s1, cur ^ 1, LD_HALF, N_LD);
+            hint_mfma_lds();
+            wait_lds();
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(cur, 2, 0);
+            mma(1, odd_c{}, 0, 0, 0, 0);
+            hint_mfma_lds();
+            wait_lds();
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(cur, 3, 1);
+            mma(0, even_c{}, 0, 0, 0, 0);
+            hint_mfma_lds();
+            __builtin_amdgcn_sched_barrier(0);
+            if (CHK) {
+                // checksum-digit columns for this wave's share of the rows (16-row blocks
+                // wn*CB ..) over both k-blocks of the stage; the A operands are re-read from
+                // the resident stage
+                const uint8_t* sA = smem + cur * A_STAGE;
+#pragma unroll
+                for (int kbl = 0; kbl < 2; ++kbl)
+#pragma unroll
+                    for (int c = 0; c < CB; ++c) {
+                        const v4i a = *reinterpret_cast<const v4i*>(sA + ck_off[kbl] + c * 16 * BK) ^ (int)0x80808080;
+                        cacc[c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, limb[kbl], cacc[c], 0, 0, 0);
+                    }
+            }
+            // publish the next stage: this wave's loads have landed, and after the barrier
+            // nobody reads the old stage any more
+            wait_vmem();
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(cur ^ 1, 0, 0);
+            mma(1, odd_c{}, s2, cur, 0, LD_HALF);
+            hint_mfma_lds();
+            wait_lds();
+            __builtin_amdgcn_sched_barrier(0);
+            cur ^= 1;
+        }
+    };
+    auto run_all = [&](auto ph_c) __attribute__((always_inline)) {
+        if (kCheck) {
+            // this tile column's contiguous share of the checksum product's K range
+            const int lo = (int)(((int64_t)tile_n * NS) / tiles_n), hi = (int)(((int64_t)(tile_n + 1) * NS) / tiles_n);
+            run(0, lo, std::false_type{}, ph_c);
+            run(lo, hi, std::true_type{}, ph_c);
+            run(hi, NS, std::false_type{}, ph_c);
+        } else {
+            run(0, NS, std::false_type{}, ph_c);
+        }
+    };
+    if (WGM == 1) run_all(std::integral_constant<int, 2>{});
+    else if ((wm & 1) == 0) run_all(std::integral_constant<int, 0>{});
+    else run_all(std::integral_constant<int, 1>{});
+    __syncthreads();
+
+    // ---------------------------------- epilogue ----------------------------------
+    // accumulator layout of the 32x32 MFMA: lane l, element e of block (i, t) is
+    // row 8*(e/4) + 4*(l/32) + e%4, column l%32 of that block.
+    const int lcol = lane & 31, lhalf = lane >> 5;
+    // LDS scratch (stage buffers are dead): [BN] column sums, [WGN][BM] row-sum parts,
+    // [BM] checksum parts, 4 control words
+    int32_t* const s_bs = reinterpret_cast<int32_t*>(smem);
+    int32_t* const s_rs = s_bs + 4 * BN;
+    int32_t* const s_ck = s_rs + WGN * BM;
+    int* const s_ctl = s_ck + BM;
+    static_assert((4 * BN + WGN * BM + BM + 4) * 4 <= A_STAGE, "epilogue scratch exceeds a stage buffer");
+    // column sums of the streamed B: lane halves hold the two k-groups, waves wm = 0 and 1 (or a
+    // lone wave) hold alternate k-steps; every byte carried a bias of 128
+    constexpr int SUM_WAVES = WGM == 1 ? 1 : 2;
+#pragma unroll
+    for (int t = 0; t < TN; ++t) {
+        bsum[t] += (uint32_t)__shfl_xor((int)bsum[t], 32);
+        if (wm < SUM_WAVES && lhalf == 0) s_bs[wm * BN + wn * WTN + t * 32 + lcol] = (int32_t)bsum[t];
+    }
+    __syncthreads();
+    int32_t cs[TN];
+#pragma unroll
+    for (int t = 0; t < TN; ++t) {
+        uint32_t v = (uint32_t)s_bs[wn * WTN + t * 32 + lcol];
+        if (SUM_WAVES == 2) v += (uint32_t)s_bs[BN + wn * WTN + t * 32 + lcol];
+        cs[t] = 128 * (int32_t)(v - 128u * (uint32_t)(NS * BK));
+    }
+    // C_temp values: undo the a - 128 shift
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][t][e] += cs[t];
+
+    if (p.n_inj > 0) {
+        // simulated faults in the 32-bit intermediate (test hook): XOR before the row sums
+        const abft_inject_t* inj = reinterpret_cast<const abft_inject_t*>(p.inj);
+        for (int n = 0; n < p.n_inj; ++n) {
+            const int r = inj[n].row - (row0 + wm * WTM), c = inj[n].col - (col0 + wn * WTN);
+            const uint32_t mask = inj[n].xor_mask;
+            if (r < 0 || r >= WTM || c < 0 || c >= WTN) continue;
+            if (inj[n].row >= p.M || inj[n].col >= p.N) continue;
+            const int bi = r >> 5, rr = r & 31, bj = c >> 5;
+            const int e_hit = (rr >> 3) * 4 + (rr & 3), half_hit = (rr >> 2) & 1;
+            const bool mine = (lcol == (c & 31)) && (lhalf == half_hit);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int t = 0; t < TN; ++t)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        if (mine && i == bi && t == bj && e == e_hit) acc[i][t][e] ^= (int)mask;
+        }
+    }
+
+    int32_t atom_old = 0;
+    if (kCheck) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                uint32_t v = 0;
+#pragma unroll
+                for (int t = 0; t < TN; ++t) v += (uint32_t)acc[i][t][e];
+                v = sum32(v);
+                if (lcol == 0) s_rs[wn * BM + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * lhalf + (e & 3)] = (int32_t)v;
+            }
+        // 16x16 accumulator: lane l, element e is row 4*(l/16) + e, column l%16; columns 0..3
+        // hold the four digit products
+#pragma unroll
+        for (int c = 0; c < CB; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int d = lane & 15;
+                uint32_t v = d < kLimbs ? ((uint32_t)cacc[c][e] << (8 * d)) : 0u;
+                v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);
+                v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);
+                if (d == 0) s_ck[wm * WTM + (wn * CB + c) * 16 + 4 * (lane >> 4) + e] = (int32_t)v;
+            }
+        __syncthreads();
+        for (int r = tid; r < BM; r += NT) {
+            if (row0 + r < p.M) {
+                uint32_t d = 0;
+#pragma unroll
+                for (int w = 0; w < WGN; ++w) d += (uint32_t)s_rs[w * BM + r];
+                d -= (uint32_t)s_ck[r];
+                if (tile_n == 0) d -= 128u * (uint32_t)(*p.total);  // sum_k 128*S_B[k], once per row
+                // fetch-add WITH return: once the old value is back the add has been
+                // performed at device scope, which is what the arrival counter relies on
+                if (d != 0)
+                    atom_old |= __hip_atomic_fetch_add(p.ws + kWsHeaderInts + row0 + r, (int)d, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+
+    // ---- stores.  One running row pointer per lane; it is laundered through an empty asm
+    // so that the 64 row addresses are produced one after the other instead of all being
+    // kept in registers.
+    {
+        const int r_lane = wm * WTM + 4 * lhalf;   // first row of this lane inside the tile
+        const int c_lane = wn * WTN + lcol;
+        const bool full = (row0 + BM <= p.M) && (col0 + BN <= p.N);
+        int32_t zcs[TN];
+#pragma unroll
+        for (int t = 0; t < TN; ++t) zcs[t] = kWantQ ? p.colsum[col0 + c_lane + t * 32] : 0;
+        int32_t* cptr = kWantC ? p.C + (int64_t)(row0 + r_lane) * p.ldc + col0 + c_lane : nullptr;
+        uint8_t* qptr = kWantQ ? p.Cq + (int64_t)(row0 + r_lane) * p.ldcq + col0 + c_lane : nullptr;
+        const int rows_left = p.M - row0 - r_lane;  // rows of this lane's column that exist
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+#pragma unroll
+                for (int ee = 0; ee < 4; ++ee) {
+                    const int e = g * 4 + ee;
+                    const int roff = i * 32 + 8 * g + ee;
+                    if (full || roff < rows_left) {
+#pragma unroll
+                        for (int t = 0; t < TN; ++t) {
+                            if (full || col0 + c_lane + t * 32 < p.N) {
+                                if (kWantC) cptr[t * 32] = acc[i][t][e];
+                                if (kWantQ) qptr[t * 32] = requant_one(acc[i][t][e], zcs[t], col0 + c_lane + t * 32, p.rq);
+                            }
+                        }
+                    }
+                    if (kWantC) cptr += p.ldc;
+                    if (kWantQ) qptr += p.ldcq;
+                    asm volatile("" : "+v"(cptr), "+v"(qptr));
+                }
+                // rows 8g+4 .. 8g+7 belong to the other half-wave
+                if (kWantC) cptr += 4 * p.ldc;
+                if (kWantQ) qptr += 4 * p.ldcq;
+            }
+    }
+
+    if (kCheck) {
+        // The last workgroup to arrive turns the accumulated differences into flags and
+        // puts the workspace back to zero.  No cache maintenance is involved: all data that
+        // crosses workgroups moves through device-scope atomics, and every thread has its
+        // fetch-add result back (the store of atom_old below waits for it) before the
+        // barrier that precedes the arrival count.
+        s_bs[tid] = atom_old;
+        __syncthreads();
+        if (tid == 0) {
+            const int t = __hip_atomic_fetch_add(p.ws, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_ctl[0] = (t == (int)gridDim.x - 1);
+            s_ctl[1] = 0;
+        }
+        __syncthreads();
+        if (s_ctl[0]) {
+            int cnt = 0;
+            constexpr int U = 16;
+            for (int r0 = 0; r0 < p.M; r0 += NT * U) {
+                // sixteen independent device-scope loads in flight per thread, then the stores
+                int d[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int r = r0 + u * NT + tid;
+                    d[u] = r < p.M ? __hip_atomic_load(p.ws + kWsHeaderInts + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int r = r0 + u * NT + tid;
+                    if (r < p.M) {
+                        if (d[u] != 0)
+                            __hip_atomic_store(p.ws + kWsHeaderInts + r, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        p.row_flags[r] = d[u] != 0;
+                        cnt += d[u] != 0;
+                    }
+                }
+            }
+            if (cnt) atomicAdd(&s_ctl[1], cnt);
+            __syncthreads();
+            if (tid == 0) {
+                if (p.err_count) *p.err_count = s_ctl[1];
+                __hip_atomic_store(p.ws, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN>
+hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(WGM * WGN * 64);
+    const size_t lds = 2 * (size_t)(BM + BN) * BK;
+#define ABFT_LAUNCH(CK, OUT)                                                                              \
+    do {                                                                                                  \
+        auto kern = gemm_tile_async_kernel<BM, BN, WGM, WGN, CK, OUT>;                                    \
+        static bool attr_set = false;                                                                     \
+        if (!attr_set) {                                                                                  \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                       \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);     \
+            if (e != hipSuccess) return e;                                                                \
+            attr_set = true;                                                                              \
+        }                                                                                                 \
+        kern<<<grid, block, lds, s>>>(p, tiles_m, tiles_n);                                               \
+        return hipGetLastError();                                                                         \
+    } while (0)
+#define ABFT_OUT(CK)                                          \
+    do {                                                      \
+        if (want_c && want_q) ABFT_LAUNCH(CK, kOutC | kOutQ); \
+        if (want_c) ABFT_LAUNCH(CK, kOutC);                   \
+        ABFT_LAUNCH(CK, kOutQ);                               \
+    } while (0)
+    if (check) ABFT_OUT(true);
+    ABFT_OUT(false);
+#undef ABFT_OUT
+#undef ABFT_LAUNCH
+}
+
+}  // namespace atile
+}  // namespace abft

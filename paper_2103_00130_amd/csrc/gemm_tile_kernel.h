@@ -56,10 +56,10 @@ __device__ inline uint8_t requant_one(int32_t v, int32_t cs, int col, const Requ
     return (uint8_t)y;
 }
 
-// kFastA: A and lda are multiples of 16 bytes and K is a multiple of 16, so every
-// 16-byte chunk is loaded whole; rows past M and chunks past K are clamped to valid
-// addresses (their products meet zero rows of B or are never stored).
-template <int BM, int BN, int WGM, int WGN, bool kCheck, int kOut, bool kFastA>
+// This is the general path: A may have any alignment, leading dimension and K; its
+// chunks are assembled byte by byte.  Aligned problems take the kernel of
+// gemm_tile_async.h instead.
+template <int BM, int BN, int WGM, int WGN, bool kCheck, int kOut>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_kernel(const GemmParams p, const int tiles_n) {
     constexpr int NT = WGM * WGN * 64;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
@@ -108,27 +108,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_kernel(const GemmPara
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) bsum[i] = 0;
 
-    // per-thread source pointers of the A chunks (fast path)
-    const uint8_t* a_src[A_CH];
-    if (kFastA) {
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) {
-            const int q = tid + NT * i;
-            const int grow = min(row0 + (q >> 2), p.M - 1);
-            a_src[i] = p.A + (int64_t)grow * p.lda + (q & 3) * 16;
-        }
-    }
-
     auto g_load = [&](int kb, int s) {
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
             const int q = tid + NT * i;
-            if (kFastA) {
-                // a chunk that starts at or past K is re-read from the last whole chunk
-                const int k0 = kb * 64 + (q & 3) * 16;
-                const int back = k0 + 16 > p.K ? k0 + 16 - p.K : 0;
-                ra[s][i] = *reinterpret_cast<const v4i*>(a_src[i] + kb * 64 - back);
-            } else {
+            {
                 const int r = q >> 2, kg = q & 3;
                 const int grow = row0 + r, k0 = kb * 64 + kg * 16;
                 v4i v = v4i{0, 0, 0, 0};
@@ -450,10 +434,9 @@ hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p,
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(WGM * WGN * 64);
     const size_t lds = 2 * (BM + BN) * 64;
-    const bool fast_a = p.a_vec_ok && (p.K % 16 == 0);
-#define ABFT_LAUNCH(CK, OUT, FA)                                                                          \
+#define ABFT_LAUNCH(CK, OUT)                                                                              \
     do {                                                                                                  \
-        auto kern = gemm_tile_kernel<BM, BN, WGM, WGN, CK, OUT, FA>;                                      \
+        auto kern = gemm_tile_kernel<BM, BN, WGM, WGN, CK, OUT>;                                          \
         static bool attr_set = false;                                                                     \
         if (!attr_set) {                                                                                  \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                       \
@@ -464,18 +447,14 @@ hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p,
         kern<<<grid, block, lds, s>>>(p, tiles_n);                                                        \
         return hipGetLastError();                                                                         \
     } while (0)
-#define ABFT_OUT(CK, FA)                                          \
-    do {                                                          \
-        if (want_c && want_q) ABFT_LAUNCH(CK, kOutC | kOutQ, FA); \
-        if (want_c) ABFT_LAUNCH(CK, kOutC, FA);                   \
-        ABFT_LAUNCH(CK, kOutQ, FA);                               \
+#define ABFT_OUT(CK)                                          \
+    do {                                                      \
+        if (want_c && want_q) ABFT_LAUNCH(CK, kOutC | kOutQ); \
+        if (want_c) ABFT_LAUNCH(CK, kOutC);                   \
+        ABFT_LAUNCH(CK, kOutQ);                               \
     } while (0)
-    if (check) {
-        if (fast_a) ABFT_OUT(true, true);
-        ABFT_OUT(true, false);
-    }
-    if (fast_a) ABFT_OUT(false, true);
-    ABFT_OUT(false, false);
+    if (check) ABFT_OUT(true);
+    ABFT_OUT(false);
 #undef ABFT_OUT
 #undef ABFT_LAUNCH
 }

@@ -278,3 +278,68 @@ def test_deterministic_across_runs(binding, gpu_util):
     a = run.gemm(ops.A)
     b = run.gemm(ops.A)
     assert np.array_equal(a["C"], b["C"]) and np.array_equal(a["flags"], b["flags"])
+
+
+SMALLM_SHAPES = [(1, 16, 16), (1, 800, 3200), (5, 33, 80), (16, 48, 64), (16, 4096, 2048), (17, 100, 144),
+                 (32, 512, 1024), (33, 70, 272), (64, 256, 512), (64, 1000, 1040)]
+
+
+@pytest.mark.parametrize("M,N,K", SMALLM_SHAPES)
+def test_streaming_kernel_matches_oracle(binding, gpu_util, oracle, M, N, K):
+    say(f"streaming gemm {M}x{N}x{K}")
+    A, B = operands(M, N, K, 11 * M + 5 * N + K, relu_like=(M % 2 == 1))
+    rng = np.random.default_rng(M + N + K)
+    run = gpu_util.GpuRun(binding, B)
+    ws = binding.Workspace(M, run.Bp)
+    ref = oracle.checked_gemm(A, B)
+    for variant in ("smallm", "auto"):
+        out = run.gemm(A, variant=variant, ws=ws)
+        assert np.array_equal(out["C"], ref.C)
+        assert np.array_equal(out["flags"], ref.flags) and out["err_count"] == 0
+        assert not out["ws"].any(), "workspace must be left zero"
+    out = run.gemm(A, variant="smallm", check=False)
+    assert np.array_equal(out["C"], ref.C) and (out["flags"] == -1).all()
+    # faults in C: single, and several at once
+    for n_f in (1, 1, 3):
+        inj = [(int(rng.integers(M)), int(rng.integers(N)), 1 << int(rng.integers(32))) for _ in range(n_f)]
+        refi = oracle.checked_gemm(A, B, flips_c=inj)
+        out = run.gemm(A, variant="smallm", injections=inj, ws=ws)
+        assert np.array_equal(out["C"], refi.C) and np.array_equal(out["flags"], refi.flags)
+        assert out["err_count"] == refi.err_count and not out["ws"].any()
+    # a fault in B after packing, and one in A
+    k, j, bit = int(rng.integers(K)), int(rng.integers(N)), int(rng.integers(8))
+    refb = oracle.checked_gemm(A, B, flips_b=[(k, j, bit)])
+    binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+    out = run.gemm(A, variant="smallm", ws=ws)
+    binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+    assert np.array_equal(out["C"], refb.C) and np.array_equal(out["flags"], refb.flags)
+    i, k, bit = int(rng.integers(M)), int(rng.integers(K)), int(rng.integers(8))
+    refa = oracle.checked_gemm(A, B, flips_a=[(i, k, bit)])
+    A2 = A.copy()
+    A2[i, k] ^= np.uint8(1 << bit)
+    out = run.gemm(A2, variant="smallm", ws=ws)
+    assert np.array_equal(out["C"], refa.C) and out["err_count"] == 0
+    # fused requantization
+    mult = wlmod.draw_mult(rng, N, "channel")
+    bias = rng.integers(-3000, 3000, size=N).astype(np.int32)
+    q32 = oracle.requantize(ref.C, ref.colsum, 128, 128, mult, bias, precision="f32")
+    for want_c in (True, False):
+        out = run.gemm(A, variant="smallm", requant=(128, 128, mult, bias), want_c=want_c, ws=ws)
+        assert np.array_equal(out["Cq"], q32) and out["err_count"] == 0
+        if want_c:
+            assert np.array_equal(out["C"], ref.C)
+
+
+def test_streaming_variant_refuses_what_it_cannot_run(binding, gpu_util):
+    import torch
+    A, B = operands(70, 64, 64, 3)
+    run = gpu_util.GpuRun(binding, B)
+    with pytest.raises(binding.AbftError) as ei:
+        run.gemm(A, variant="smallm")
+    assert ei.value.code == binding.ABFT_EUNSUPPORTED
+    A, B = operands(8, 64, 72, 4)       # K not a multiple of 16: forced streaming variant is refused,
+    run = gpu_util.GpuRun(binding, B)   # the default choice falls back to the general tiled kernel
+    with pytest.raises(binding.AbftError):
+        run.gemm(A, variant="smallm")
+    assert run.gemm(A)["err_count"] == 0
+    torch.cuda.synchronize()
