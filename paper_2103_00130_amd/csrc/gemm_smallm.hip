@@ -52,6 +52,7 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
     __shared__ v4i s_acc[3][RB][64];
     __shared__ v4i s_chk[3][RB][64];
     __shared__ uint32_t s_bsum[3][64];
+    __shared__ uint32_t s_d[64];
     __shared__ int s_ctl[2];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -187,13 +188,17 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
                     ck += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)ck, 0xB1, 0xF, 0xF, true);
                     ck += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)ck, 0x4E, 0xF, 0xF, true);
                     const int row = rb * 16 + 4 * lkg + e;
-                    const uint32_t d = rs - ck - total128;
-                    // fetch-add WITH return: the add has been performed at device scope once
-                    // the old value is back, which is what the arrival counter relies on
-                    if (lcol == 0 && row < p.M && d != 0)
-                        atom_old |= __hip_atomic_fetch_add(p.ws + kWsHeaderInts + slot * kSmallMRows + row, (int)d,
-                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (lcol == 0) s_d[row] = rs - ck - total128;
                 }
+            // one row per lane, so that all returned atomics of the workgroup are in flight together.
+            // fetch-add WITH return: the add has been performed at device scope once the old
+            // value is back, which is what the arrival counter relies on
+            if (lane < 16 * RB && lane < p.M) {
+                const uint32_t d = s_d[lane];
+                if (d != 0)
+                    atom_old = __hip_atomic_fetch_add(p.ws + kWsHeaderInts + slot * kSmallMRows + lane, (int)d,
+                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
 
         // stores: per (rb, e) one instruction covers 4 rows x 16 columns

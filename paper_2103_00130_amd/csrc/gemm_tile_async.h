@@ -119,11 +119,27 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         a_c16[i] = ((lane & 7) ^ ((r >> 1) & 7)) * 16;
     }
     constexpr int TILES_PER_NT = kTileN / BN;
-    const int8_t* const b_src = p.packed +
-        packed_unit_offset(tile_n / TILES_PER_NT, 0, (tile_n % TILES_PER_NT) * (BN / 32), p.KB2 * 2) + lane * 16;
     constexpr int64_t B_KB_STRIDE = (int64_t)kUnitsPerTile * kUnitBytes;
     constexpr int B_CHUNKS_PER_KB = BN / 16;  // 1 KiB chunks of this tile per k-block of 64
-    const uint32_t lds_wave_a = __builtin_amdgcn_readfirstlane(lds_base + wave * A_LD * 1024);
+    // B: instruction i of this wave copies chunk wave*B_LD + i of the stage (1 KiB of packed B).
+    // Per-lane source pointers for stage 0 and per-wave LDS targets are fixed up front; a
+    // stage only adds its stride.
+    const int8_t* b_ptr[B_LD];
+    uint32_t b_lds[B_LD], a_lds[A_LD];
+    {
+        const int8_t* const b_tile = p.packed +
+            packed_unit_offset(tile_n / TILES_PER_NT, 0, (tile_n % TILES_PER_NT) * (BN / 32), p.KB2 * 2) + lane * 16;
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i) {
+            const int bc = wave * B_LD + i;
+            const int kbl = bc / B_CHUNKS_PER_KB, cc = bc % B_CHUNKS_PER_KB;
+            b_ptr[i] = b_tile + (int64_t)kbl * B_KB_STRIDE + cc * 1024;
+            b_lds[i] = __builtin_amdgcn_readfirstlane(lds_base + 2 * A_STAGE + kbl * (BN * 64) + cc * 1024);
+        }
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i)
+            a_lds[i] = __builtin_amdgcn_readfirstlane(lds_base + (wave * A_LD + i) * 1024);
+    }
 
     // load n of a stage: n < A_LD is an A load (8 rows x 128 B), the rest are B loads (1 KiB of
     // packed B).  A chunk of A at or past K is re-read from the last whole chunk (it meets zero
@@ -132,12 +148,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     auto issue_load = [&](int s, int buf, int n) __attribute__((always_inline)) {
         if (n < A_LD) {
             const int k = min(s * BK + a_c16[n], p.K - 16);
-            async16(a_row[n] + k, lds_wave_a + buf * A_STAGE + n * 1024);
+            async16(a_row[n] + k, a_lds[n] + buf * A_STAGE);
         } else {
-            const int bc = __builtin_amdgcn_readfirstlane(wave * B_LD + (n - A_LD));
-            const int kbl = bc / B_CHUNKS_PER_KB, cc = bc % B_CHUNKS_PER_KB;
-            async16(b_src + (int64_t)(2 * s + kbl) * B_KB_STRIDE + cc * 1024,
-                    lds_base + 2 * A_STAGE + buf * B_STAGE + kbl * (BN * 64) + cc * 1024);
+            async16(b_ptr[n - A_LD] + (int64_t)s * (2 * B_KB_STRIDE), b_lds[n - A_LD] + buf * B_STAGE);
         }
     };
 
@@ -227,13 +240,20 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     auto wait_vmem = []() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };
     // interleave hint: the LDS reads of the next fragments go one by one between MFMAs
     auto hint_mfma_lds = []() __attribute__((always_inline)) {
-#ifndef ABFT_NO_HINTS
 #pragma unroll
         for (int g = 0; g < TM + TN; ++g) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-#endif
+    };
+
+    // One k-step: the LDS reads of the next fragment set are issued first and interleaved with
+    // the MFMAs of the current one.
+    auto phase = [&](int f, int rbuf, int jn, auto sum_b_c, int ld_s, int ld_buf, int ld_lo, int ld_hi)
+                     __attribute__((always_inline)) {
+        read_frags(rbuf, jn, f ^ 1);
+        mma(f, sum_b_c, ld_s, ld_buf, ld_lo, ld_hi);
+        hint_mfma_lds();
     };
 
     constexpr int LD_HALF = N_LD / 2;
@@ -267,19 +287,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
             const int s1 = min(s + 1, NS - 1), s2 = min(s + 2, NS - 1);
             // the digit operands of this stage are needed three quarters of a stage from now
             if (CHK) load_limbs(s);
-            read_frags(cur, 1, 1);
-            mma(0, even_c{}, s1, cur ^ 1, LD_HALF, N_LD);
-            hint_mfma_lds();
+            phase(0, cur, 1, even_c{}, s1, cur ^ 1, LD_HALF, N_LD);
             wait_lds();
             __builtin_amdgcn_sched_barrier(0);
-            read_frags(cur, 2, 0);
-            mma(1, odd_c{}, 0, 0, 0, 0);
-            hint_mfma_lds();
+            phase(1, cur, 2, odd_c{}, 0, 0, 0, 0);
             wait_lds();
             __builtin_amdgcn_sched_barrier(0);
-            read_frags(cur, 3, 1);
-            mma(0, even_c{}, 0, 0, 0, 0);
-            hint_mfma_lds();
+            phase(0, cur, 3, even_c{}, 0, 0, 0, 0);
+            wait_lds();
             __builtin_amdgcn_sched_barrier(0);
             if (CHK) {
                 // checksum-digit columns for this wave's share of the rows (16-row blocks
@@ -299,9 +314,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
             wait_vmem();
             __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
-            read_frags(cur ^ 1, 0, 0);
-            mma(1, odd_c{}, s2, cur, 0, LD_HALF);
-            hint_mfma_lds();
+            phase(1, cur ^ 1, 0, odd_c{}, s2, cur, 0, LD_HALF);
             wait_lds();
             __builtin_amdgcn_sched_barrier(0);
             cur ^= 1;
@@ -321,6 +334,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     if (WGM == 1) run_all(std::integral_constant<int, 2>{});
     else if ((wm & 1) == 0) run_all(std::integral_constant<int, 0>{});
     else run_all(std::integral_constant<int, 1>{});
+    // the last stage re-issued loads into a dead buffer: they must have landed before LDS is
+    // reused as scratch below
+    wait_vmem();
     __syncthreads();
 
     // ---------------------------------- epilogue ----------------------------------
