@@ -151,6 +151,70 @@ def cpu_baseline(job, target_s=12.0):
             f"(checksum, product, row sums, comparison), {dt:.1f} s wall"}
 
 
+CALIB_COPY_BYTES = 256 << 20
+GEMM_KERNEL_TAGS = ("gemm_tile_async_kernel", "gemm_tile_kernel", "gemm_smallm_kernel")
+
+
+def pmc_child(args):
+    """Body of the profiled child process: one calibration copy of known size, then a few
+    checked launches of the workload (no graph, no timing)."""
+    import torch
+    from paper_2103_00130_amd import binding as b
+    torch.cuda.set_device(0)
+    src = torch.zeros(CALIB_COPY_BYTES // 4, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    job = Job(b, torch, args.workload)
+    torch.cuda.synchronize()
+    b.abft_calib_copy(src, dst)
+    for _ in range(4):
+        job.step(True, variant=args.variant)
+    torch.cuda.synchronize()
+
+
+def measure_traffic(args):
+    """HBM bytes per checked launch from two counter passes of rocprofv3 (FETCH_SIZE, then
+    WRITE_SIZE), each over a child process running pmc_child, each scaled by what the same
+    counter reads for the calibration copy.  Runs before this process touches the GPU.
+    Returns (dict or None, note)."""
+    import csv
+    import glob
+    import shutil
+    import subprocess
+    import tempfile
+    if shutil.which("rocprofv3") is None:
+        return None, "rocprofv3 not found"
+    out = {}
+    for counter, key in (("FETCH_SIZE", "read"), ("WRITE_SIZE", "write")):
+        tmp = tempfile.mkdtemp(prefix="abft_pmc_")
+        env = dict(os.environ, TMPDIR=tmp)
+        cmd = ["timeout", "-s", "KILL", "170", "rocprofv3", "--pmc", counter, "-d", tmp, "-o", "pmc",
+               "--output-format", "csv", "--", sys.executable, os.path.join(ROOT, "bench.py"), "--pmc-child",
+               "--workload", str(args.workload), "--variant", str(args.variant)]
+        try:
+            r = subprocess.run(cmd, cwd=tmp, env=env, capture_output=True, text=True)
+            files = glob.glob(os.path.join(tmp, "**", "*counter_collection.csv"), recursive=True)
+            if r.returncode != 0 or not files:
+                return None, f"{counter} pass failed (exit {r.returncode})"
+            per_dispatch = {}
+            for row in csv.DictReader(open(files[0])):
+                if row["Counter_Name"] != counter:
+                    continue
+                k = (row["Dispatch_Id"], row["Kernel_Name"])
+                per_dispatch[k] = per_dispatch.get(k, 0.0) + float(row["Counter_Value"])
+            cal = [v for (d, n), v in per_dispatch.items() if "calib_copy_kernel" in n]
+            gemm = [v for (d, n), v in sorted(per_dispatch.items(), key=lambda kv: int(kv[0][0]))
+                    if any(t in n for t in GEMM_KERNEL_TAGS)]
+            if len(cal) != 1 or cal[0] <= 0 or len(gemm) < 2:
+                return None, f"{counter} pass: unexpected dispatch list"
+            gemm = gemm[1:]           # the first launch also pays for cold instruction and data caches
+            scale = CALIB_COPY_BYTES / cal[0]
+            out[key] = sum(gemm) / len(gemm) * scale
+            out[key + "_counter_units_per_byte"] = 1.0 / scale
+        finally:
+            shutil.rmtree(tmp, ignore_errors=True)
+    return out, "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per checked launch, scaled by a 256 MiB copy kernel"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -161,10 +225,16 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detection", action="store_true")
     ap.add_argument("--variant", type=lambda s: int(s, 0), default=0)
+    ap.add_argument("--no-traffic", action="store_true", help="skip the two rocprofv3 counter passes")
+    ap.add_argument("--pmc-child", action="store_true", help=argparse.SUPPRESS)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
+    if args.pmc_child:
+        pmc_child(args)
+        return
+    traffic, traffic_note = (None, "skipped") if args.no_traffic else measure_traffic(args)
 
     import torch
     from paper_2103_00130_amd import binding as b     # fails loudly if the HIP library is missing
@@ -212,6 +282,13 @@ def main():
         "pack_ms": main_res["pack_ms"], "roofline": main_res["roofline"],
         "launch": "the timed steps are captured in one HIP graph and replayed (events bracket the replay)",
     }
+    if traffic is not None:
+        out["roofline"]["traffic"] = traffic["read"] + traffic["write"]
+        out["roofline"]["traffic_read"] = traffic["read"]
+        out["roofline"]["traffic_write"] = traffic["write"]
+        out["roofline"]["traffic_unit"] = "bytes per launch"
+        out["roofline"]["algorithmic_bytes"] = algorithmic_bytes(wl, True, job.rq is not None)
+    out["roofline"]["traffic_note"] = traffic_note
     if not args.no_detection:
         det, n, wrong = detection_sample(job, 200)
         out["detection_pct"] = 100.0 * det / n

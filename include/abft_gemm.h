@@ -165,6 +165,13 @@ int abft_verify_rows(const int32_t* C, int64_t ldc, int M, int N, const int32_t*
 int abft_row_checksum(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp,
                       int32_t* row_chk, void* stream);
 
+/* Measurement aid, not part of the method: a plain device-to-device copy of
+ * `bytes` (a positive multiple of 16; both pointers 16-byte aligned, buffers
+ * must not overlap).  It reads and writes exactly `bytes` once, which makes it
+ * the known-size reference that a profiler's HBM traffic counters are scaled
+ * by when the GEMM kernels' traffic is reported. */
+int abft_calib_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 /* Message for the last non-OK return on this host thread. */
 const char* abft_last_error(void);
 

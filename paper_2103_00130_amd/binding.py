@@ -23,7 +23,7 @@ EXPORTS = (
     "abft_pack_b_checksum", "abft_packed_b_dims", "abft_packed_b_get_checksum", "abft_packed_b_get_col_offsets",
     "abft_packed_b_flip_bit", "abft_packed_b_flip_checksum_bit", "abft_packed_b_destroy",
     "abft_gemm_workspace_bytes", "abft_workspace_init", "abft_gemm_u8s8s32_checked", "abft_requantize_u8",
-    "abft_verify_rows", "abft_row_checksum", "abft_last_error",
+    "abft_verify_rows", "abft_row_checksum", "abft_calib_copy", "abft_last_error",
 )
 
 
@@ -64,6 +64,7 @@ def _load() -> ctypes.CDLL:
     L.abft_requantize_u8.argtypes = [vp, i64, i32, i32, vp, ctypes.POINTER(abft_requant_t), vp, i64, vp]
     L.abft_verify_rows.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
     L.abft_row_checksum.argtypes = [vp, i64, i32, vp, vp, vp]
+    L.abft_calib_copy.argtypes = [vp, vp, sz, vp]
     return L
 
 
@@ -210,6 +211,14 @@ def abft_verify_rows(C, row_chk, row_flags, err_count=None, stream=None):
 def abft_row_checksum(A, Bp: PackedB, row_chk, stream=None):
     _check(lib.abft_row_checksum(_ptr(A, torch.uint8, "A"), _ld(A, "A"), A.shape[0], Bp.handle,
                                  _ptr(row_chk, torch.int32, "row_chk"), _stream(stream)))
+
+
+def abft_calib_copy(src, dst, stream=None):
+    if src.numel() * src.element_size() != dst.numel() * dst.element_size():
+        raise ValueError("abft_calib_copy: src and dst differ in size")
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("abft_calib_copy: contiguous device tensors expected")
+    _check(lib.abft_calib_copy(src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size(), _stream(stream)))
 
 
 class Workspace:

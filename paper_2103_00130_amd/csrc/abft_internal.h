@@ -101,6 +101,7 @@ hipError_t launch_requantize(const int32_t* C, int64_t ldc, int M, int N, const 
                              const RequantDev& rq, uint8_t* Cq, int64_t ldcq, hipStream_t s);
 hipError_t launch_verify_rows(const int32_t* C, int64_t ldc, int M, int N, const int32_t* row_chk,
                               int32_t* row_flags, int32_t* err_count, hipStream_t s);
+hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 hipError_t launch_row_checksum(const uint8_t* A, int64_t lda, int M, int K, const int32_t* S_B,
                                int32_t* row_chk, hipStream_t s);
 

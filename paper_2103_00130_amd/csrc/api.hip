@@ -244,4 +244,13 @@ int abft_row_checksum(const uint8_t* A, int64_t lda, int M, const abft_packed_b*
     return ABFT_OK;
 }
 
+int abft_calib_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    const char* fn = "abft_calib_copy";
+    if (!src || !dst) return fail(ABFT_EINVAL, "%s: null pointer", fn);
+    if (bytes == 0 || bytes % 16 != 0 || ((uintptr_t)src | (uintptr_t)dst) % 16 != 0)
+        return fail(ABFT_EINVAL, "%s: bytes=%zu and both pointers must be multiples of 16", fn, bytes);
+    HIP_TRY(abft::launch_calib_copy(src, dst, bytes, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
 }  // extern "C"

@@ -4,6 +4,8 @@
 // model applied to a matrix at rest), and the checksum column A*S_B on its own.
 #include "abft_internal.h"
 
+#include <algorithm>
+
 namespace abft {
 namespace {
 
@@ -59,7 +61,21 @@ __global__ void row_checksum_kernel(const uint8_t* __restrict__ A, int64_t lda, 
     if (lane == 0) row_chk[row] = (int32_t)s;
 }
 
+// Plain grid-stride copy of 16-byte words: the known-size reference against which the
+// memory-traffic counters of a profiler are scaled.
+__global__ void calib_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace
+
+hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 16);
+    calib_copy_kernel<<<dim3(grid), dim3(256), 0, s>>>((const uint4*)src, (uint4*)dst, n16);
+    return hipGetLastError();
+}
 
 hipError_t launch_requantize(const int32_t* C, int64_t ldc, int M, int N, const int32_t* colsum,
                              const RequantDev& rq, uint8_t* Cq, int64_t ldcq, hipStream_t s) {

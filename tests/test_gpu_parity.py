@@ -343,3 +343,14 @@ def test_streaming_variant_refuses_what_it_cannot_run(binding, gpu_util):
         run.gemm(A, variant="smallm")
     assert run.gemm(A)["err_count"] == 0
     torch.cuda.synchronize()
+
+
+@pytest.mark.gpu
+def test_calibration_copy_is_a_copy(binding):
+    import torch
+    g = torch.Generator(device="cpu").manual_seed(7)
+    src = torch.randint(-2**31, 2**31 - 1, ((1 << 20) + 12,), dtype=torch.int32, generator=g).cuda()
+    dst = torch.zeros_like(src)
+    binding.abft_calib_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
