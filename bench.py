@@ -218,8 +218,8 @@ def measure_traffic(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", type=int, default=4, help="index into the five workloads (default: dense 4096^3)")
     ap.add_argument("--others", action="store_true", help="also time the other workloads (reported under 'others')")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -14,7 +14,8 @@ ABFT_DECL(g64);
 
 hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
     // direct-to-LDS kernels need whole, aligned 16-byte chunks of A
-    const bool fast_a = p.a_vec_ok && (p.K % 16 == 0);
+    // (and 32-bit byte offsets into A)
+    const bool fast_a = p.a_vec_ok && (p.K % 16 == 0) && ((int64_t)(p.M - 1) * p.lda + p.K <= 0x7fffffffll);
     if (!fast_a) {
         if (variant == kTile64) return launch_gemm_tile_g64(check, want_c, want_q, p, s);
         return launch_gemm_tile_g128(check, want_c, want_q, p, s);

@@ -29,6 +29,12 @@
 #include "../../include/abft_gemm.h"
 #include "abft_internal.h"
 
+#ifndef ABFT_LD_CUT0
+#define ABFT_LD_CUT0 6
+#define ABFT_LD_CUT1 12
+#define ABFT_LD_CUT2 16
+#endif
+
 namespace abft {
 namespace atile {
 
@@ -79,7 +85,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     extern __shared__ __align__(1024) uint8_t smem[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) uint8_t*)smem);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
     // Workgroups go round-robin over the 8 XCDs; give every XCD a compact block of tiles
     // (consecutive ids inside an XCD walk down a strip of 4 tile rows) so that its L2 sees
@@ -104,53 +110,64 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     // through inline asm so that the compiler keeps treating the LDS reads of the resident
     // stage as independent of them; completion is awaited explicitly (vmcnt) before the
     // barrier that publishes a stage.
-    auto async16 = [](const void* g, uint32_t lds_addr) __attribute__((always_inline)) {
+    // Addresses: a uniform base in scalar registers (advanced by the stage) plus a 32-bit
+    // per-lane offset that never changes, so that a load costs no vector address arithmetic.
+    auto dma = [](uint32_t lds_addr, uint32_t voff, const void* sbase, auto off_c) __attribute__((always_inline)) {
+        constexpr int OFF = decltype(off_c)::value;  // added to the global AND to the LDS address
         // one wait state between the write of m0 and the instruction that reads it
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "m0", "memory");
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
+                     ::"s"(lds_addr), "v"(voff), "s"(sbase), "n"(OFF) : "m0", "memory");
     };
     // A: instruction i of this wave covers rows (wave*A_LD + i)*8 .. +8 of the tile; lane l
-    // takes row l>>3 of those and the 16-byte chunk (l&7) ^ ((row>>1)&7) of the stage.
-    const uint8_t* a_row[A_LD];
-    int a_c16[A_LD];
+    // takes row l>>3 of those and the 16-byte chunk (l&7) ^ ((row>>1)&7) of the stage.  In the
+    // last stage a chunk at or past K is re-read from the last whole chunk (it meets zero rows
+    // of B), hence the second set of offsets.
+    uint32_t a_voff[A_LD], a_voff_last[A_LD], a_lds[A_LD];
+    {
+        const int c16_max = p.K - 16 - (NS - 1) * BK;
 #pragma unroll
-    for (int i = 0; i < A_LD; ++i) {
-        const int r = (wave * A_LD + i) * 8 + (lane >> 3);
-        a_row[i] = p.A + (int64_t)min(row0 + r, p.M - 1) * p.lda;
-        a_c16[i] = ((lane & 7) ^ ((r >> 1) & 7)) * 16;
+        for (int i = 0; i < A_LD; ++i) {
+            const int r = (wave * A_LD + i) * 8 + (lane >> 3);
+            const int c16 = ((lane & 7) ^ ((r >> 1) & 7)) * 16;
+            const uint32_t rowoff = (uint32_t)min(row0 + r, p.M - 1) * (uint32_t)p.lda;
+            a_voff[i] = rowoff + (uint32_t)c16;
+            a_voff_last[i] = rowoff + (uint32_t)min(c16, c16_max);
+            a_lds[i] = lds_base + (wave * A_LD + i) * 1024;
+        }
     }
     constexpr int TILES_PER_NT = kTileN / BN;
     constexpr int64_t B_KB_STRIDE = (int64_t)kUnitsPerTile * kUnitBytes;
     constexpr int B_CHUNKS_PER_KB = BN / 16;  // 1 KiB chunks of this tile per k-block of 64
-    // B: instruction i of this wave copies chunk wave*B_LD + i of the stage (1 KiB of packed B).
-    // Per-lane source pointers for stage 0 and per-wave LDS targets are fixed up front; a
-    // stage only adds its stride.
-    const int8_t* b_ptr[B_LD];
-    uint32_t b_lds[B_LD], a_lds[A_LD];
+    static_assert(B_CHUNKS_PER_KB % B_LD == 0, "the chunks of one wave lie in one k-block");
+    // B: this wave copies B_LD consecutive 1 KiB chunks of the stage; packed B and its LDS image
+    // have the same order, so one base pair serves four loads through the instruction offset.
+    const int8_t* b_wave;
+    uint32_t b_lds;
+    const uint32_t b_voff = lane * 16;
     {
-        const int8_t* const b_tile = p.packed +
-            packed_unit_offset(tile_n / TILES_PER_NT, 0, (tile_n % TILES_PER_NT) * (BN / 32), p.KB2 * 2) + lane * 16;
-#pragma unroll
-        for (int i = 0; i < B_LD; ++i) {
-            const int bc = wave * B_LD + i;
-            const int kbl = bc / B_CHUNKS_PER_KB, cc = bc % B_CHUNKS_PER_KB;
-            b_ptr[i] = b_tile + (int64_t)kbl * B_KB_STRIDE + cc * 1024;
-            b_lds[i] = __builtin_amdgcn_readfirstlane(lds_base + 2 * A_STAGE + kbl * (BN * 64) + cc * 1024);
-        }
-#pragma unroll
-        for (int i = 0; i < A_LD; ++i)
-            a_lds[i] = __builtin_amdgcn_readfirstlane(lds_base + (wave * A_LD + i) * 1024);
+        const int bc0 = wave * B_LD, kbl = bc0 / B_CHUNKS_PER_KB, cc0 = bc0 % B_CHUNKS_PER_KB;
+        b_wave = p.packed + packed_unit_offset(tile_n / TILES_PER_NT, 0, (tile_n % TILES_PER_NT) * (BN / 32), p.KB2 * 2) +
+                 (int64_t)kbl * B_KB_STRIDE + cc0 * 1024;
+        b_lds = lds_base + 2 * A_STAGE + kbl * (BN * 64) + cc0 * 1024;
     }
 
-    // load n of a stage: n < A_LD is an A load (8 rows x 128 B), the rest are B loads (1 KiB of
-    // packed B).  A chunk of A at or past K is re-read from the last whole chunk (it meets zero
-    // rows of B).
+    // load n of stage s into buffer buf: n < A_LD is an A load (8 rows x 128 B), the rest are
+    // B loads (1 KiB of packed B each).
     constexpr int N_LD = A_LD + B_LD;
     auto issue_load = [&](int s, int buf, int n) __attribute__((always_inline)) {
         if (n < A_LD) {
-            const int k = min(s * BK + a_c16[n], p.K - 16);
-            async16(a_row[n] + k, a_lds[n] + buf * A_STAGE);
+            const uint32_t voff = (s == NS - 1) ? a_voff_last[n] : a_voff[n];
+            dma(a_lds[n] + buf * A_STAGE, voff, p.A + (int64_t)s * BK, std::integral_constant<int, 0>{});
         } else {
-            async16(b_ptr[n - A_LD] + (int64_t)s * (2 * B_KB_STRIDE), b_lds[n - A_LD] + buf * B_STAGE);
+            const int j = n - A_LD, g = j >> 2;
+            const int8_t* const base = b_wave + (int64_t)s * (2 * B_KB_STRIDE) + g * 4096;
+            const uint32_t l = b_lds + buf * B_STAGE + g * 4096;
+            switch (j & 3) {
+                case 0: dma(l, b_voff, base, std::integral_constant<int, 0>{}); break;
+                case 1: dma(l, b_voff, base, std::integral_constant<int, 1024>{}); break;
+                case 2: dma(l, b_voff, base, std::integral_constant<int, 2048>{}); break;
+                default: dma(l, b_voff, base, std::integral_constant<int, 3072>{}); break;
+            }
         }
     };
 
@@ -206,57 +223,58 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
 #pragma unroll
     for (int kbl = 0; kbl < 2; ++kbl)
         ck_off[kbl] = (wm * WTM + wn * CB * 16 + (lane & 15)) * BK + (((4 * kbl + (lane >> 4)) ^ a_swz) << 4);
-    // One k-step of 32: TM x TN MFMAs on fragment set f.  After each row of MFMAs one slice of
-    // the pending direct-to-LDS loads [ld_lo, ld_hi) of stage ld_s is issued, so that vector
-    // memory instructions are spread between MFMAs instead of arriving in a burst.  When
-    // SUM_B, the B bytes of this k-step are added into the column sums: XOR 0x80 turns int8
-    // into a biased uint8 whose four bytes v_sad_u8 sums against zero (the bias, 128 per byte,
-    // is taken off in the epilogue).
-    auto mma = [&](int f, auto sum_b_c, int ld_s, int ld_buf, int ld_lo, int ld_hi) __attribute__((always_inline)) {
-        constexpr bool SUM_B = decltype(sum_b_c)::value;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            // a - 128 as int8: done here, on data that is already in registers, so that no
-            // VALU instruction ever waits on an LDS read inside the MFMA stream
-            const v4i a = fa[f][i] ^ (int)0x80808080;
-#pragma unroll
-            for (int t = 0; t < TN; ++t)
-                acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, fb[f][t], acc[i][t], 0, 0, 0);
-#pragma unroll
-            for (int n = ld_lo + (ld_hi - ld_lo) * i / TM; n < ld_lo + (ld_hi - ld_lo) * (i + 1) / TM; ++n)
-                issue_load(ld_s, ld_buf, n);
-        }
-        if (SUM_B) {
-#pragma unroll
-            for (int t = 0; t < TN; ++t) {
-                bsum[t] = __builtin_amdgcn_sad_u8((uint32_t)fb[f][t].x ^ 0x80808080u, 0u, bsum[t]);
-                bsum[t] = __builtin_amdgcn_sad_u8((uint32_t)fb[f][t].y ^ 0x80808080u, 0u, bsum[t]);
-                bsum[t] = __builtin_amdgcn_sad_u8((uint32_t)fb[f][t].z ^ 0x80808080u, 0u, bsum[t]);
-                bsum[t] = __builtin_amdgcn_sad_u8((uint32_t)fb[f][t].w ^ 0x80808080u, 0u, bsum[t]);
-            }
-        }
-    };
     auto wait_lds = []() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0xC07F); };
     auto wait_vmem = []() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };
-    // interleave hint: the LDS reads of the next fragments go one by one between MFMAs
-    auto hint_mfma_lds = []() __attribute__((always_inline)) {
+
+    // One k-step of 32: TM x TN MFMAs on fragment set f while fragment set f^1 is read for
+    // k-step jn of buffer rbuf and loads [ld_lo, ld_hi) of stage ld_s go out to buffer ld_buf.
+    // The k-step is cut into regions of two MFMAs that the instruction scheduler may not move
+    // anything across; each region carries its share of the other work, so that every LDS
+    // read, vector-memory instruction and VALU instruction issues in the shadow of an MFMA:
+    //  * the LDS reads of the next fragments go into the first half of the regions, so that
+    //    they have returned when the k-step ends;
+    //  * a - 128 as int8 (XOR 0x80 on data already in registers) for the next row of blocks is
+    //    computed one row ahead of its first MFMA;
+    //  * when SUM_B, the B bytes of this k-step are added into the column sums: XOR 0x80 turns
+    //    int8 into a biased uint8 whose four bytes v_sad_u8 sums against zero (the bias, 128
+    //    per byte, is taken off in the epilogue);
+    //  * the direct-to-LDS loads are spread evenly instead of arriving in a burst.
+    auto phase = [&](int f, int rbuf, int jn, auto sum_b_c, int ld_s, int ld_buf, int ld_lo, int ld_hi)
+                     __attribute__((always_inline)) {
+        constexpr bool SUM_B = decltype(sum_b_c)::value;
+        constexpr int Q = TM * TN, NR = Q / 2, R = TM + TN, RR = NR >= 2 ? NR / 2 : 1, D = 4 * TN;
+        static_assert(TN % 2 == 0, "regions pair the MFMAs of one row of blocks");
+        const uint8_t* const sA = smem + rbuf * A_STAGE + a_off[jn];
+        const uint8_t* const sB = smem + rbuf * B_STAGE + (jn >> 1) * (BN * 64) + b_off + (jn & 1) * 1024;
+        v4i a_cur = fa[f][0] ^ (int)0x80808080, a_nxt = a_cur;
 #pragma unroll
-        for (int g = 0; g < TM + TN; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        for (int r = 0; r < NR; ++r) {
+            const int i = (2 * r) / TN, t0 = (2 * r) % TN;
+            if (t0 == 0 && i + 1 < TM) a_nxt = fa[f][i + 1] ^ (int)0x80808080;
+            acc[i][t0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_cur, fb[f][t0], acc[i][t0], 0, 0, 0);
+            acc[i][t0 + 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_cur, fb[f][t0 + 1], acc[i][t0 + 1], 0, 0, 0);
+            if (r < RR) {
+#pragma unroll
+                for (int x = R * r / RR; x < R * (r + 1) / RR; ++x) {
+                    if (x < TM) fa[f ^ 1][x] = *reinterpret_cast<const v4i*>(sA + x * 32 * BK);
+                    else fb[f ^ 1][x - TM] = *reinterpret_cast<const v4i*>(sB + (x - TM) * 2048);
+                }
+            }
+            if (SUM_B) {
+#pragma unroll
+                for (int d = D * r / NR; d < D * (r + 1) / NR; ++d)
+                    bsum[d >> 2] = __builtin_amdgcn_sad_u8((uint32_t)fb[f][d >> 2][d & 3] ^ 0x80808080u, 0u, bsum[d >> 2]);
+            }
+#pragma unroll
+            for (int n = ld_lo + (ld_hi - ld_lo) * r / NR; n < ld_lo + (ld_hi - ld_lo) * (r + 1) / NR; ++n)
+                issue_load(ld_s, ld_buf, n);
+            if (t0 + 2 >= TN) a_cur = a_nxt;
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // One k-step: the LDS reads of the next fragment set are issued first and interleaved with
-    // the MFMAs of the current one.
-    auto phase = [&](int f, int rbuf, int jn, auto sum_b_c, int ld_s, int ld_buf, int ld_lo, int ld_hi)
-                     __attribute__((always_inline)) {
-        read_frags(rbuf, jn, f ^ 1);
-        mma(f, sum_b_c, ld_s, ld_buf, ld_lo, ld_hi);
-        hint_mfma_lds();
-    };
-
-    constexpr int LD_HALF = N_LD / 2;
+    // cut points of a stage's loads over the four k-steps in which they may be in flight
+    constexpr int LD_C0 = N_LD * ABFT_LD_CUT0 / 16, LD_C1 = N_LD * ABFT_LD_CUT1 / 16, LD_C2 = N_LD * ABFT_LD_CUT2 / 16;
     static_assert(N_LD % 2 == 0, "loads of a stage are issued in two halves");
 #pragma unroll
     for (int n = 0; n < N_LD; ++n) issue_load(0, 0, n);
@@ -264,7 +282,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     __syncthreads();
     // first half of stage 1 (the second half goes out during the first k-step of stage 0)
 #pragma unroll
-    for (int n = 0; n < LD_HALF; ++n) issue_load(min(1, NS - 1), 1, n);
+    for (int n = 0; n < LD_C0; ++n) issue_load(min(1, NS - 1), 1, n);
     read_frags(0, 0, 0);
     wait_lds();
     __builtin_amdgcn_sched_barrier(0);
@@ -287,13 +305,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
             const int s1 = min(s + 1, NS - 1), s2 = min(s + 2, NS - 1);
             // the digit operands of this stage are needed three quarters of a stage from now
             if (CHK) load_limbs(s);
-            phase(0, cur, 1, even_c{}, s1, cur ^ 1, LD_HALF, N_LD);
+            phase(0, cur, 1, even_c{}, s1, cur ^ 1, LD_C0, LD_C1);
             wait_lds();
             __builtin_amdgcn_sched_barrier(0);
-            phase(1, cur, 2, odd_c{}, 0, 0, 0, 0);
+            phase(1, cur, 2, odd_c{}, s1, cur ^ 1, LD_C1, LD_C2);
             wait_lds();
             __builtin_amdgcn_sched_barrier(0);
-            phase(0, cur, 3, even_c{}, 0, 0, 0, 0);
+            phase(0, cur, 3, even_c{}, s1, cur ^ 1, LD_C2, N_LD);
             wait_lds();
             __builtin_amdgcn_sched_barrier(0);
             if (CHK) {
@@ -314,7 +332,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
             wait_vmem();
             __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
-            phase(1, cur ^ 1, 0, odd_c{}, s2, cur, 0, LD_HALF);
+            phase(1, cur ^ 1, 0, odd_c{}, s2, cur, 0, LD_C0);
             wait_lds();
             __builtin_amdgcn_sched_barrier(0);
             cur ^= 1;
