@@ -29,12 +29,6 @@
 #include "../../include/abft_gemm.h"
 #include "abft_internal.h"
 
-#ifndef ABFT_LD_CUT0
-#define ABFT_LD_CUT0 6
-#define ABFT_LD_CUT1 12
-#define ABFT_LD_CUT2 16
-#endif
-
 namespace abft {
 namespace atile {
 
@@ -273,14 +267,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         }
     };
 
-    // cut points of a stage's loads over the four k-steps in which they may be in flight
-    constexpr int LD_C0 = N_LD * ABFT_LD_CUT0 / 16, LD_C1 = N_LD * ABFT_LD_CUT1 / 16, LD_C2 = N_LD * ABFT_LD_CUT2 / 16;
-    static_assert(N_LD % 2 == 0, "loads of a stage are issued in two halves");
+    // cut points of a stage's loads over the k-steps in which they may be in flight: 3/8 go out
+    // during the last k-step of the stage before, 3/8 during the first and 2/8 during the second
+    // k-step of the stage that precedes theirs (measured best among the even spreads; issuing
+    // any in the third k-step leaves them too little time to land)
+    constexpr int LD_C0 = N_LD * 3 / 8, LD_C1 = N_LD * 6 / 8, LD_C2 = N_LD;
 #pragma unroll
     for (int n = 0; n < N_LD; ++n) issue_load(0, 0, n);
     wait_vmem();
     __syncthreads();
-    // first half of stage 1 (the second half goes out during the first k-step of stage 0)
+    // first share of stage 1 (the rest goes out during the first two k-steps of stage 0)
 #pragma unroll
     for (int n = 0; n < LD_C0; ++n) issue_load(min(1, NS - 1), 1, n);
     read_frags(0, 0, 0);
@@ -292,10 +288,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     // keep every loop body one straight block).  PH says on which k-steps this wave adds the B
     // bytes it holds into the column sums: the waves that share a column range (same wn) take
     // alternate k-steps (0: even, 1: odd), a lone wave takes all (2).
-    // Load schedule: the loads of stage s+1 go out in two halves, the first during the last
-    // k-step of stage s-1 (into the buffer that has just been released), the second during the
-    // first k-step of stage s; they are awaited at the end of the third k-step of stage s.  A
-    // stage index past the end re-reads the last stage into a dead buffer.
+    // Load schedule: see the cut points above; the loads of stage s+1 are awaited at the end of
+    // the third k-step of stage s, where the single barrier of the stage sits.  A stage index
+    // past the end re-reads the last stage into a dead buffer.
     auto run = [&](int s_begin, int s_end, auto chk_c, auto ph_c) __attribute__((always_inline)) {
         constexpr bool CHK = decltype(chk_c)::value;
         constexpr int PH = decltype(ph_c)::value;
@@ -413,6 +408,48 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         }
     }
 
+    // ---- stores first: they drain to memory for several microseconds, and everything the check
+    // still has to do (row sums, atomics, arrival count, flags) runs underneath that.
+    // One running row pointer per lane; it is laundered through an empty asm
+    // so that the 64 row addresses are produced one after the other instead of all being
+    // kept in registers.
+    {
+        const int r_lane = wm * WTM + 4 * lhalf;   // first row of this lane inside the tile
+        const int c_lane = wn * WTN + lcol;
+        const bool full = (row0 + BM <= p.M) && (col0 + BN <= p.N);
+        int32_t zcs[TN];
+#pragma unroll
+        for (int t = 0; t < TN; ++t) zcs[t] = kWantQ ? p.colsum[col0 + c_lane + t * 32] : 0;
+        int32_t* cptr = kWantC ? p.C + (int64_t)(row0 + r_lane) * p.ldc + col0 + c_lane : nullptr;
+        uint8_t* qptr = kWantQ ? p.Cq + (int64_t)(row0 + r_lane) * p.ldcq + col0 + c_lane : nullptr;
+        const int rows_left = p.M - row0 - r_lane;  // rows of this lane's column that exist
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+#pragma unroll
+                for (int ee = 0; ee < 4; ++ee) {
+                    const int e = g * 4 + ee;
+                    const int roff = i * 32 + 8 * g + ee;
+                    if (full || roff < rows_left) {
+#pragma unroll
+                        for (int t = 0; t < TN; ++t) {
+                            if (full || col0 + c_lane + t * 32 < p.N) {
+                                if (kWantC) cptr[t * 32] = acc[i][t][e];
+                                if (kWantQ) qptr[t * 32] = requant_one(acc[i][t][e], zcs[t], col0 + c_lane + t * 32, p.rq);
+                            }
+                        }
+                    }
+                    if (kWantC) cptr += p.ldc;
+                    if (kWantQ) qptr += p.ldcq;
+                    asm volatile("" : "+v"(cptr), "+v"(qptr));
+                }
+                // rows 8g+4 .. 8g+7 belong to the other half-wave
+                if (kWantC) cptr += 4 * p.ldc;
+                if (kWantQ) qptr += 4 * p.ldcq;
+            }
+    }
+
     int32_t atom_old = 0;
     if (kCheck) {
 #pragma unroll
@@ -452,46 +489,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                                                        __HIP_MEMORY_SCOPE_AGENT);
             }
         }
-    }
-
-    // ---- stores.  One running row pointer per lane; it is laundered through an empty asm
-    // so that the 64 row addresses are produced one after the other instead of all being
-    // kept in registers.
-    {
-        const int r_lane = wm * WTM + 4 * lhalf;   // first row of this lane inside the tile
-        const int c_lane = wn * WTN + lcol;
-        const bool full = (row0 + BM <= p.M) && (col0 + BN <= p.N);
-        int32_t zcs[TN];
-#pragma unroll
-        for (int t = 0; t < TN; ++t) zcs[t] = kWantQ ? p.colsum[col0 + c_lane + t * 32] : 0;
-        int32_t* cptr = kWantC ? p.C + (int64_t)(row0 + r_lane) * p.ldc + col0 + c_lane : nullptr;
-        uint8_t* qptr = kWantQ ? p.Cq + (int64_t)(row0 + r_lane) * p.ldcq + col0 + c_lane : nullptr;
-        const int rows_left = p.M - row0 - r_lane;  // rows of this lane's column that exist
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-#pragma unroll
-                for (int ee = 0; ee < 4; ++ee) {
-                    const int e = g * 4 + ee;
-                    const int roff = i * 32 + 8 * g + ee;
-                    if (full || roff < rows_left) {
-#pragma unroll
-                        for (int t = 0; t < TN; ++t) {
-                            if (full || col0 + c_lane + t * 32 < p.N) {
-                                if (kWantC) cptr[t * 32] = acc[i][t][e];
-                                if (kWantQ) qptr[t * 32] = requant_one(acc[i][t][e], zcs[t], col0 + c_lane + t * 32, p.rq);
-                            }
-                        }
-                    }
-                    if (kWantC) cptr += p.ldc;
-                    if (kWantQ) qptr += p.ldcq;
-                    asm volatile("" : "+v"(cptr), "+v"(qptr));
-                }
-                // rows 8g+4 .. 8g+7 belong to the other half-wave
-                if (kWantC) cptr += 4 * p.ldc;
-                if (kWantQ) qptr += 4 * p.ldcq;
-            }
     }
 
     if (kCheck) {
