@@ -105,18 +105,20 @@ typedef struct {
     const int32_t* bias;
 } abft_requant_t;
 
-/* One simulated fault in the 32-bit intermediate (Section VI-B-1, "random bit
- * flip injection to the 32-bit intermediate result matrix"): C_temp[row][col]
- * ^= xor_mask after the product and before the row sums, the store and the
- * requantization. */
+/* One simulated fault in the 32-bit intermediate (the fault model of Section
+ * VI-B-1, a bit flip in the 32-bit result matrix): C_temp[row][col] ^= xor_mask
+ * after the product and before the row sums, the store and the
+ * requantization.  Entries that name the same element act as one entry with
+ * the XOR of their masks; entries outside the M x N matrix are ignored. */
 typedef struct {
     int32_t row;
     int32_t col;
     uint32_t xor_mask;
 } abft_inject_t;
 
-/* Scratch the checked GEMM needs for a problem with M rows against Bp:
- * per-row partial (row sum - checksum) accumulators and an arrival counter.
+/* Scratch the checked GEMM needs for a problem with M rows against Bp: one
+ * 64-bit word per row (partial row sum - checksum, and how many column blocks
+ * have contributed) and an arrival counter.
  * The memory must be zero before its first use (abft_workspace_init) and every
  * call leaves it zero again, so one workspace serves any number of calls that
  * are ordered on one stream.  Calls that may overlap need one workspace each. */
@@ -138,10 +140,9 @@ int abft_workspace_init(void* workspace, size_t bytes, void* stream);
  *   flags      ABFT_CHECK or ABFT_NOCHECK, optionally | ABFT_VARIANT_*.
  *   workspace  abft_gemm_workspace_bytes(M, Bp) bytes, zeroed once; may be
  *              NULL with ABFT_NOCHECK.
- * Errors: ABFT_EINVAL for null/shape/ld/workspace problems or an injection
- * outside the matrix (checked on the host only when inj is NULL-free of host
- * knowledge: the kernel ignores out-of-range entries); ABFT_EUNSUPPORTED for a
- * variant that cannot run the shape; ABFT_EHIP for a failed launch. */
+ * Errors: ABFT_EINVAL for null/shape/ld/workspace problems (inj is device
+ * memory and is not inspected on the host); ABFT_EUNSUPPORTED for a variant
+ * that cannot run the shape; ABFT_EHIP for a failed launch. */
 int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp,
                               int32_t* C, int64_t ldc, int32_t* row_flags, int32_t* err_count,
                               const abft_requant_t* rq, uint8_t* Cq, int64_t ldcq,

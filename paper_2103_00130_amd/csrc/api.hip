@@ -41,7 +41,7 @@ void free_handle(abft_packed_b* h) {
 }
 
 size_t ws_ints(int M) {
-    const size_t rows = (((size_t)M + 63) / 64) * 64;
+    const size_t rows = 2 * ((((size_t)M + 63) / 64) * 64);  // one 64-bit word per row
     const size_t streaming = (size_t)abft::kSmallMSlots * abft::kSmallMRows;
     return (size_t)abft::kWsHeaderInts + (rows > streaming ? rows : streaming);
 }

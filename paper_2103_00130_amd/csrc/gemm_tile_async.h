@@ -379,50 +379,27 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         if (SUM_WAVES == 2) v += (uint32_t)s_bs[BN + wn * WTN + t * 32 + lcol];
         cs[t] = 128 * (int32_t)(v - 128u * (uint32_t)(NS * BK));
     }
-    // C_temp values: undo the a - 128 shift
+    // C_temp = accumulator + cs (undoing the a - 128 shift); the sum is formed on the way to
+    // memory, the accumulators stay as they are
+    // ---- stores, with the row sums of Eq. 2b formed on the way.  One running row pointer per
+    // lane; it is laundered through an empty asm so that the 64 row addresses are produced one
+    // after the other instead of all being kept in registers.  The stores are limited by how
+    // fast memory takes them (several microseconds per tile), so the vector arithmetic placed
+    // between them - the add-back, the row sums and their cross-lane reduction - costs nothing.
+    int32_t cs_lane = 0;  // this lane's share of the add-back in a row sum
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int t = 0; t < TN; ++t) cs_lane += cs[t];
+    const int r_lane = wm * WTM + 4 * lhalf;   // first row of this lane inside the tile
+    const int c_lane = wn * WTN + lcol;
+    const bool full = (row0 + BM <= p.M) && (col0 + BN <= p.N);
+    int32_t zcs[TN];
 #pragma unroll
-        for (int t = 0; t < TN; ++t)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][t][e] += cs[t];
-
-    if (p.n_inj > 0) {
-        // simulated faults in the 32-bit intermediate (test hook): XOR before the row sums
-        const abft_inject_t* inj = reinterpret_cast<const abft_inject_t*>(p.inj);
-        for (int n = 0; n < p.n_inj; ++n) {
-            const int r = inj[n].row - (row0 + wm * WTM), c = inj[n].col - (col0 + wn * WTN);
-            const uint32_t mask = inj[n].xor_mask;
-            if (r < 0 || r >= WTM || c < 0 || c >= WTN) continue;
-            if (inj[n].row >= p.M || inj[n].col >= p.N) continue;
-            const int bi = r >> 5, rr = r & 31, bj = c >> 5;
-            const int e_hit = (rr >> 3) * 4 + (rr & 3), half_hit = (rr >> 2) & 1;
-            const bool mine = (lcol == (c & 31)) && (lhalf == half_hit);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int t = 0; t < TN; ++t)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        if (mine && i == bi && t == bj && e == e_hit) acc[i][t][e] ^= (int)mask;
-        }
-    }
-
-    // ---- stores first: they drain to memory for several microseconds, and everything the check
-    // still has to do (row sums, atomics, arrival count, flags) runs underneath that.
-    // One running row pointer per lane; it is laundered through an empty asm
-    // so that the 64 row addresses are produced one after the other instead of all being
-    // kept in registers.
-    {
-        const int r_lane = wm * WTM + 4 * lhalf;   // first row of this lane inside the tile
-        const int c_lane = wn * WTN + lcol;
-        const bool full = (row0 + BM <= p.M) && (col0 + BN <= p.N);
-        int32_t zcs[TN];
-#pragma unroll
-        for (int t = 0; t < TN; ++t) zcs[t] = kWantQ ? p.colsum[col0 + c_lane + t * 32] : 0;
-        int32_t* cptr = kWantC ? p.C + (int64_t)(row0 + r_lane) * p.ldc + col0 + c_lane : nullptr;
-        uint8_t* qptr = kWantQ ? p.Cq + (int64_t)(row0 + r_lane) * p.ldcq + col0 + c_lane : nullptr;
-        const int rows_left = p.M - row0 - r_lane;  // rows of this lane's column that exist
+    for (int t = 0; t < TN; ++t) zcs[t] = kWantQ ? p.colsum[col0 + c_lane + t * 32] : 0;
+    int32_t* cptr = kWantC ? p.C + (int64_t)(row0 + r_lane) * p.ldc + col0 + c_lane : nullptr;
+    uint8_t* qptr = kWantQ ? p.Cq + (int64_t)(row0 + r_lane) * p.ldcq + col0 + c_lane : nullptr;
+    const int rows_left = p.M - row0 - r_lane;  // rows of this lane's column that exist
+    auto store_blocks = [&](auto full_c) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full_c)::value;  // no bounds to test inside a whole tile
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -431,14 +408,20 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                 for (int ee = 0; ee < 4; ++ee) {
                     const int e = g * 4 + ee;
                     const int roff = i * 32 + 8 * g + ee;
-                    if (full || roff < rows_left) {
+                    uint32_t rs = (uint32_t)cs_lane;
 #pragma unroll
-                        for (int t = 0; t < TN; ++t) {
-                            if (full || col0 + c_lane + t * 32 < p.N) {
-                                if (kWantC) cptr[t * 32] = acc[i][t][e];
-                                if (kWantQ) qptr[t * 32] = requant_one(acc[i][t][e], zcs[t], col0 + c_lane + t * 32, p.rq);
-                            }
+                    for (int t = 0; t < TN; ++t) {
+                        const int32_t raw = acc[i][t][e];
+                        if (kCheck) rs += (uint32_t)raw;  // columns past N hold zeros
+                        const int32_t val = raw + cs[t];
+                        if (FULL || (roff < rows_left && col0 + c_lane + t * 32 < p.N)) {
+                            if (kWantC) cptr[t * 32] = val;
+                            if (kWantQ) qptr[t * 32] = requant_one(val, zcs[t], col0 + c_lane + t * 32, p.rq);
                         }
+                    }
+                    if (kCheck) {
+                        rs = sum32(rs);
+                        if (lcol == 0) s_rs[wn * BM + wm * WTM + roff + 4 * lhalf] = (int32_t)rs;
                     }
                     if (kWantC) cptr += p.ldc;
                     if (kWantQ) qptr += p.ldcq;
@@ -448,20 +431,51 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                 if (kWantC) cptr += 4 * p.ldc;
                 if (kWantQ) qptr += 4 * p.ldcq;
             }
+    };
+
+    if (full) store_blocks(std::true_type{});
+    else store_blocks(std::false_type{});
+
+    if (p.n_inj > 0) {
+        // Simulated faults in the 32-bit intermediate (test hook): the element is flipped where it
+        // now lies - in C, in Cq and in its row sum - by the lane that owns it, after that lane's
+        // own store of the clean value (same lane, same address: program order holds).  The
+        // accumulators are only read.  Entries that name the same element act as one entry
+        // with the XOR of their masks.
+        const abft_inject_t* inj = reinterpret_cast<const abft_inject_t*>(p.inj);
+        for (int n = 0; n < p.n_inj; ++n) {
+            const int row = inj[n].row, col = inj[n].col;
+            const int r = row - (row0 + wm * WTM), c = col - (col0 + wn * WTN);
+            if (r < 0 || r >= WTM || c < 0 || c >= WTN || row >= p.M || col >= p.N) continue;
+            bool seen = false;
+            for (int m = 0; m < n; ++m) seen |= (inj[m].row == row && inj[m].col == col);
+            if (seen) continue;
+            uint32_t mask = inj[n].xor_mask;
+            for (int m = n + 1; m < p.n_inj; ++m)
+                if (inj[m].row == row && inj[m].col == col) mask ^= inj[m].xor_mask;
+            const int bi = r >> 5, rr = r & 31, bj = c >> 5;
+            const int e_hit = (rr >> 3) * 4 + (rr & 3), half_hit = (rr >> 2) & 1;
+            int32_t raw = 0, cs_hit = 0, zcs_hit = 0;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int t = 0; t < TN; ++t)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        if (i == bi && t == bj && e == e_hit) raw = acc[i][t][e];
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+                if (t == bj) { cs_hit = cs[t]; zcs_hit = zcs[t]; }
+            if (lcol == (c & 31) && lhalf == half_hit) {
+                const int32_t val = raw + cs_hit, bad = (int32_t)((uint32_t)val ^ mask);
+                if (kWantC) p.C[(int64_t)row * p.ldc + col] = bad;
+                if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_one(bad, zcs_hit, col, p.rq);
+                if (kCheck) atomicAdd(&s_rs[wn * BM + wm * WTM + r], bad - val);
+            }
+        }
     }
 
-    int32_t atom_old = 0;
     if (kCheck) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                uint32_t v = 0;
-#pragma unroll
-                for (int t = 0; t < TN; ++t) v += (uint32_t)acc[i][t][e];
-                v = sum32(v);
-                if (lcol == 0) s_rs[wn * BM + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * lhalf + (e & 3)] = (int32_t)v;
-            }
         // 16x16 accumulator: lane l, element e is row 4*(l/16) + e, column l%16; columns 0..3
         // hold the four digit products
 #pragma unroll
@@ -474,7 +488,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                 v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);
                 if (d == 0) s_ck[wm * WTM + (wn * CB + c) * 16 + 4 * (lane >> 4) + e] = (int32_t)v;
             }
+        if (tid == 0) s_ctl[1] = 0;
         __syncthreads();
+        // Row r of the product is spread over the tile columns; each of them adds its share of
+        // (row sum - checksum) to the row's 64-bit workspace word with ONE returned atomic:
+        // the difference goes to the high half (it wraps there as int32 arithmetic does), an
+        // arrival count to the low half.  The tile column that finds tiles_n - 1 arrivals before
+        // it has the complete difference in hand: it writes the row's flag and clears the word.
+        // No cache maintenance is involved: all data that crosses workgroups moves through
+        // device-scope atomics.
+        unsigned long long* const ws_rows = reinterpret_cast<unsigned long long*>(p.ws + kWsHeaderInts);
+        int my_err = 0;
         for (int r = tid; r < BM; r += NT) {
             if (row0 + r < p.M) {
                 uint32_t d = 0;
@@ -482,56 +506,30 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                 for (int w = 0; w < WGN; ++w) d += (uint32_t)s_rs[w * BM + r];
                 d -= (uint32_t)s_ck[r];
                 if (tile_n == 0) d -= 128u * (uint32_t)(*p.total);  // sum_k 128*S_B[k], once per row
-                // fetch-add WITH return: once the old value is back the add has been
-                // performed at device scope, which is what the arrival counter relies on
-                if (d != 0)
-                    atom_old |= __hip_atomic_fetch_add(p.ws + kWsHeaderInts + row0 + r, (int)d, __ATOMIC_RELAXED,
-                                                       __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned long long old = __hip_atomic_fetch_add(ws_rows + row0 + r, ((unsigned long long)d << 32) | 1ull,
+                                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((uint32_t)old == (uint32_t)tiles_n - 1u) {
+                    const uint32_t diff = (uint32_t)(old >> 32) + d;
+                    __hip_atomic_store(ws_rows + row0 + r, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    p.row_flags[row0 + r] = diff != 0;
+                    my_err += diff != 0;
+                }
             }
         }
-    }
-
-    if (kCheck) {
-        // The last workgroup to arrive turns the accumulated differences into flags and
-        // puts the workspace back to zero.  No cache maintenance is involved: all data that
-        // crosses workgroups moves through device-scope atomics, and every thread has its
-        // fetch-add result back (the store of atom_old below waits for it) before the
-        // barrier that precedes the arrival count.
-        s_bs[tid] = atom_old;
+        // errCount: flagged rows are summed inside the workgroup, then one more returned atomic
+        // per workgroup carries them (high half) together with its arrival (low half); every
+        // thread has its row atomics back by then, since it branched on their results.  The
+        // last workgroup to arrive holds the total and clears the word.
+        if (my_err) atomicAdd(&s_ctl[1], my_err);
         __syncthreads();
         if (tid == 0) {
-            const int t = __hip_atomic_fetch_add(p.ws, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_ctl[0] = (t == (int)gridDim.x - 1);
-            s_ctl[1] = 0;
-        }
-        __syncthreads();
-        if (s_ctl[0]) {
-            int cnt = 0;
-            constexpr int U = 16;
-            for (int r0 = 0; r0 < p.M; r0 += NT * U) {
-                // sixteen independent device-scope loads in flight per thread, then the stores
-                int d[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int r = r0 + u * NT + tid;
-                    d[u] = r < p.M ? __hip_atomic_load(p.ws + kWsHeaderInts + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int r = r0 + u * NT + tid;
-                    if (r < p.M) {
-                        if (d[u] != 0)
-                            __hip_atomic_store(p.ws + kWsHeaderInts + r, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        p.row_flags[r] = d[u] != 0;
-                        cnt += d[u] != 0;
-                    }
-                }
-            }
-            if (cnt) atomicAdd(&s_ctl[1], cnt);
-            __syncthreads();
-            if (tid == 0) {
-                if (p.err_count) *p.err_count = s_ctl[1];
-                __hip_atomic_store(p.ws, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            unsigned long long* const ws_head = reinterpret_cast<unsigned long long*>(p.ws);
+            const uint32_t mine = (uint32_t)s_ctl[1];
+            const unsigned long long old = __hip_atomic_fetch_add(ws_head, ((unsigned long long)mine << 32) | 1ull, __ATOMIC_RELAXED,
+                                                                  __HIP_MEMORY_SCOPE_AGENT);
+            if ((uint32_t)old == gridDim.x - 1u) {
+                if (p.err_count) *p.err_count = (int32_t)((uint32_t)(old >> 32) + mine);
+                __hip_atomic_store(ws_head, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
