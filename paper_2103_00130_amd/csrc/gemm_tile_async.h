@@ -347,22 +347,19 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     if (WGM == 1) run_all(std::integral_constant<int, 2>{});
     else if ((wm & 1) == 0) run_all(std::integral_constant<int, 0>{});
     else run_all(std::integral_constant<int, 1>{});
-    // the last stage re-issued loads into a dead buffer: they must have landed before LDS is
-    // reused as scratch below
-    wait_vmem();
-    __syncthreads();
+    // (the last stage re-issued loads into a dead buffer; the epilogue keeps its scratch outside
+    // the stage buffers, so nobody waits for them before the very end of the kernel)
 
     // ---------------------------------- epilogue ----------------------------------
     // accumulator layout of the 32x32 MFMA: lane l, element e of block (i, t) is
     // row 8*(e/4) + 4*(l/32) + e%4, column l%32 of that block.
     const int lcol = lane & 31, lhalf = lane >> 5;
-    // LDS scratch (stage buffers are dead): [BN] column sums, [WGN][BM] row-sum parts,
+    // LDS scratch behind the stage buffers: [4][BN] column sums, [WGN][BM] row-sum parts,
     // [BM] checksum parts, 4 control words
-    int32_t* const s_bs = reinterpret_cast<int32_t*>(smem);
+    int32_t* const s_bs = reinterpret_cast<int32_t*>(smem + 2 * (A_STAGE + B_STAGE));
     int32_t* const s_rs = s_bs + 4 * BN;
     int32_t* const s_ck = s_rs + WGN * BM;
     int* const s_ctl = s_ck + BM;
-    static_assert((4 * BN + WGN * BM + BM + 4) * 4 <= A_STAGE, "epilogue scratch exceeds a stage buffer");
     // column sums of the streamed B: lane halves hold the two k-groups, waves wm = 0 and 1 (or a
     // lone wave) hold alternate k-steps; every byte carried a bias of 128
     constexpr int SUM_WAVES = WGM == 1 ? 1 : 2;
@@ -533,13 +530,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
             }
         }
     }
+    // direct-to-LDS loads that are still in flight must not outlive the workgroup's LDS
+    wait_vmem();
 }
 
 template <int BM, int BN, int WGM, int WGN>
 hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(WGM * WGN * 64);
-    const size_t lds = 2 * (size_t)(BM + BN) * BK;
+    const size_t lds = 2 * (size_t)(BM + BN) * BK + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t);
 #define ABFT_LAUNCH(CK, OUT)                                                                              \
     do {                                                                                                  \
         auto kern = gemm_tile_async_kernel<BM, BN, WGM, WGN, CK, OUT>;                                    \

@@ -64,14 +64,24 @@ __global__ void checksum_rows_kernel(const int8_t* __restrict__ B, int64_t ldb, 
 }
 
 // colsum[j] = sum_k B[k][j] (rank-1 term e_k^T B_I of Eq. 1); zeros for padded columns.
+// Workgroup (column group of 64, K slice of 256): thread (c, q) sums 64 k-values of column c,
+// the four q are combined in LDS and added to colsum (zeroed beforehand) with one integer
+// atomic per column and slice; integer addition makes the order irrelevant.
 __global__ void colsum_kernel(const int8_t* __restrict__ B, int64_t ldb, int transposed, int K, int N,
-                              int Npad, int32_t* __restrict__ colsum) {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= Npad) return;
+                              int32_t* __restrict__ colsum) {
+    __shared__ int32_t part[4][64];
+    const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int j = blockIdx.x * 64 + c;
+    const int k0 = blockIdx.y * 256 + q * 64;
     int32_t s = 0;
     if (j < N)
-        for (int k = 0; k < K; ++k) s += load_b(B, ldb, transposed, k, j, K, N);
-    colsum[j] = s;
+        for (int k = k0; k < min(k0 + 64, K); ++k) s += load_b(B, ldb, transposed, k, j, K, N);
+    part[q][c] = s;
+    __syncthreads();
+    if (q == 0 && j < N) {
+        s = part[0][c] + part[1][c] + part[2][c] + part[3][c];
+        if (s != 0) atomicAdd(&colsum[j], s);
+    }
 }
 
 // total = sum_k S_B[k] (wrap-around), single workgroup so the result is a plain store.
@@ -114,7 +124,9 @@ hipError_t launch_pack(const int8_t* B, int64_t ldb, int transposed, abft_packed
         B, ldb, transposed, h->K, h->N, h->KB, n_chunks, h->packed);
     checksum_rows_kernel<<<dim3((Kpad + 3) / 4), dim3(256), 0, s>>>(B, ldb, transposed, h->K, h->N, Kpad, h->S_B,
                                                                     h->limbs);
-    colsum_kernel<<<dim3((Npad + 255) / 256), dim3(256), 0, s>>>(B, ldb, transposed, h->K, h->N, Npad, h->colsum);
+    fill_zero_kernel<<<dim3((unsigned)((Npad + 255) / 256)), dim3(256), 0, s>>>(h->colsum, (size_t)Npad);
+    colsum_kernel<<<dim3((unsigned)(Npad / 64), (unsigned)((h->K + 255) / 256)), dim3(256), 0, s>>>(B, ldb, transposed, h->K, h->N,
+                                                                                                  h->colsum);
     total_kernel<<<dim3(1), dim3(256), 0, s>>>(h->S_B, Kpad, h->total);
     return hipGetLastError();
 }
