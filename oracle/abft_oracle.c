@@ -254,6 +254,56 @@ void oracle_campaign_b_flips(const uint8_t* A, int64_t lda, const int8_t* B, int
     }
 }
 
+/* The second fault model of Section IV-C (an element takes an arbitrary wrong value) and
+ * multi-bit upsets, in the 32-bit intermediate: element (r,c) of a clean C is XOR-ed with
+ * `mask` (mask = old ^ new for a replacement) before the row sums are taken.  Same procedure
+ * as for single bits: the row is copied, changed, summed and compared with chk[r]. */
+void oracle_campaign_c_masks(const int32_t* C, int64_t ldc, int N, const int32_t* chk,
+                             int n_inj, const int32_t* rows, const int32_t* cols,
+                             const uint32_t* masks, int32_t* out_flag, int32_t* out_value) {
+#pragma omp parallel
+    {
+        uint32_t* row = (uint32_t*)malloc((size_t)N * sizeof(uint32_t));
+#pragma omp for schedule(static)
+        for (int t = 0; t < n_inj; ++t) {
+            memcpy(row, C + (int64_t)rows[t] * ldc, (size_t)N * sizeof(uint32_t));
+            row[cols[t]] ^= masks[t];
+            uint32_t s = 0;
+            for (int j = 0; j < N; ++j) s += row[j];
+            out_flag[t] = ((int32_t)s != chk[rows[t]]) ? 1 : 0;
+            out_value[t] = (int32_t)row[cols[t]];
+        }
+        free(row);
+    }
+}
+
+/* The same two models in B after its checksum was taken: B[k][j] takes the value
+ * new_vals[t] (any int8), S_B stale.  Column j of C is recomputed from the changed B for
+ * every row, the row sums are re-taken over the whole row and compared with the
+ * (unchanged) chk.  out_flags and out_col are [n_inj][M]. */
+void oracle_campaign_b_values(const uint8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                              const int32_t* C_clean, int64_t ldc, int M, int N, int K,
+                              const int32_t* chk, int n_inj, const int32_t* ks, const int32_t* js,
+                              const int32_t* new_vals, int32_t* out_flags, int32_t* out_col) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < n_inj; ++t) {
+        const int kf = ks[t], jf = js[t];
+        const int8_t changed = (int8_t)new_vals[t];
+        for (int i = 0; i < M; ++i) {
+            uint32_t c = 0;
+            for (int k = 0; k < K; ++k) {
+                const int8_t b = (k == kf) ? changed : B[(int64_t)k * ldb + jf];
+                c += (uint32_t)A[(int64_t)i * lda + k] * (uint32_t)(int32_t)b;
+            }
+            uint32_t s = 0;
+            for (int j = 0; j < N; ++j)
+                s += (j == jf) ? c : (uint32_t)C_clean[(int64_t)i * ldc + j];
+            out_col[(int64_t)t * M + i] = (int32_t)c;
+            out_flags[(int64_t)t * M + i] = ((int32_t)s != chk[i]) ? 1 : 0;
+        }
+    }
+}
+
 /* Bit flip in A before the product: A[i][k] ^= 1<<b.  Row i of C and chk[i] are
  * both recomputed from the flipped A (A is not encoded, Section IV-C-3), the
  * row is summed and compared.  out_flag[t] = verdict of row i; out_row, when

@@ -22,6 +22,7 @@ _LIB = os.path.join(_HERE, "libabft_oracle.so")
 _i8p = ctypes.POINTER(ctypes.c_int8)
 _u8p = ctypes.POINTER(ctypes.c_uint8)
 _i32p = ctypes.POINTER(ctypes.c_int32)
+_u32p = ctypes.POINTER(ctypes.c_uint32)
 _f32p = ctypes.POINTER(ctypes.c_float)
 _i64 = ctypes.c_int64
 _int = ctypes.c_int
@@ -62,6 +63,9 @@ def lib() -> ctypes.CDLL:
         L.oracle_campaign_c_flips.argtypes = [_i32p, _i64, _int, _i32p, _int, _i32p, _i32p, _i32p, _i32p, _i32p]
         L.oracle_campaign_b_flips.argtypes = [_u8p, _i64, _i8p, _i64, _i32p, _i64, _int, _int, _int, _i32p,
                                               _int, _i32p, _i32p, _i32p, _i32p, _i32p]
+        L.oracle_campaign_c_masks.argtypes = [_i32p, _i64, _int, _i32p, _int, _i32p, _i32p, _u32p, _i32p, _i32p]
+        L.oracle_campaign_b_values.argtypes = [_u8p, _i64, _i8p, _i64, _i32p, _i64, _int, _int, _int, _i32p,
+                                               _int, _i32p, _i32p, _i32p, _i32p, _i32p]
         L.oracle_campaign_a_flips.argtypes = [_u8p, _i64, _i8p, _i64, _i32p, _int, _int, _int,
                                               _i32p, _i32p, _i32p, _i32p, _i32p]
         _lib = L
@@ -270,6 +274,41 @@ def campaign_b_flips(A, B, C_clean, chk, ks, js, bits):
     lib().oracle_campaign_b_flips(_p(A, _u8p), _ld(A), _p(B, _i8p), _ld(B), _p(C_clean, _i32p), _ld(C_clean),
                                   M, N, K, _p(chk, _i32p), n, _p(ks, _i32p), _p(js, _i32p), _p(bits, _i32p),
                                   _p(flags, _i32p), _p(col, _i32p))
+    return flags, col
+
+
+def campaign_c_masks(C_clean, chk, rows, cols, masks):
+    """Per injection of an arbitrary XOR mask (multi-bit upset, or old ^ new for a value
+    replacement): (flag of the hit row, value of the changed element)."""
+    C_clean = _c(C_clean, np.int32)
+    chk = _c(chk, np.int32)
+    rows, cols = _i32(rows), _i32(cols)
+    masks = np.ascontiguousarray(np.asarray(masks, np.uint32))
+    n = rows.size
+    flag = np.empty(n, np.int32)
+    val = np.empty(n, np.int32)
+    lib().oracle_campaign_c_masks(_p(C_clean, _i32p), _ld(C_clean), C_clean.shape[1], _p(chk, _i32p), n,
+                                  _p(rows, _i32p), _p(cols, _i32p), _p(masks, _u32p), _p(flag, _i32p),
+                                  _p(val, _i32p))
+    return flag, val
+
+
+def campaign_b_values(A, B, C_clean, chk, ks, js, new_vals):
+    """Per replacement of B[k][j] by new_vals[t] after the checksum was taken:
+    (flags[M], recomputed column j of C [M])."""
+    A = _c(A, np.uint8)
+    B = _c(B, np.int8)
+    C_clean = _c(C_clean, np.int32)
+    chk = _c(chk, np.int32)
+    ks, js, new_vals = _i32(ks), _i32(js), _i32(new_vals)
+    M, K = A.shape
+    N = B.shape[1]
+    n = ks.size
+    flags = np.empty((n, M), np.int32)
+    col = np.empty((n, M), np.int32)
+    lib().oracle_campaign_b_values(_p(A, _u8p), _ld(A), _p(B, _i8p), _ld(B), _p(C_clean, _i32p), _ld(C_clean),
+                                   M, N, K, _p(chk, _i32p), n, _p(ks, _i32p), _p(js, _i32p), _p(new_vals, _i32p),
+                                   _p(flags, _i32p), _p(col, _i32p))
     return flags, col
 
 

@@ -108,3 +108,36 @@ def draw_flips(cfg: int, target: str, n: int | None = None, rep: int = 0):
     i1 = rng.integers(0, d1, size=n, dtype=np.int32)
     bit = rng.integers(0, nb, size=n, dtype=np.int32)
     return i0, i1, bit
+
+
+def draw_value_faults(cfg: int, target: str, n: int, rep: int = 0):
+    """Fault list for the value-replacement model: arrays (idx0, idx1, new_value).
+
+    target "B": (row k, column j, new int8 value, uniform over all 256 codes);
+    "C": (row r, column c, new int32 value, uniform over all 2^32 codes).
+    """
+    wl = WORKLOADS[cfg]
+    rng = rng_for(cfg, rep, 510 + {"B": 1, "C": 2}[target])
+    d0, d1 = {"B": (wl.K, wl.N), "C": (wl.M, wl.N)}[target]
+    i0 = rng.integers(0, d0, size=n, dtype=np.int32)
+    i1 = rng.integers(0, d1, size=n, dtype=np.int32)
+    if target == "B":
+        new = rng.integers(-128, 128, size=n, dtype=np.int32)
+    else:
+        new = rng.integers(-2**31, 2**31, size=n, dtype=np.int64).astype(np.int32)
+    return i0, i1, new
+
+
+def draw_multibit_masks(cfg: int, target: str, n: int, n_bits: int, rep: int = 0):
+    """Fault list for multi-bit upsets: arrays (idx0, idx1, xor_mask) with exactly n_bits
+    distinct bits set in the mask (8-bit masks for "B", 32-bit for "C")."""
+    wl = WORKLOADS[cfg]
+    rng = rng_for(cfg, rep, 520 + {"B": 1, "C": 2}[target])
+    d0, d1, width = {"B": (wl.K, wl.N, 8), "C": (wl.M, wl.N, 32)}[target]
+    i0 = rng.integers(0, d0, size=n, dtype=np.int32)
+    i1 = rng.integers(0, d1, size=n, dtype=np.int32)
+    masks = np.zeros(n, dtype=np.uint32)
+    for t in range(n):
+        for b in rng.choice(width, size=n_bits, replace=False):
+            masks[t] |= np.uint32(1) << np.uint32(b)
+    return i0, i1, masks

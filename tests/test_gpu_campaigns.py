@@ -175,3 +175,78 @@ def test_campaign_workload2_a_b_c_flips(binding, oracle):
     assert np.array_equal(got_rows.cpu().numpy(), want_rows)
     assert np.array_equal(rig.A.cpu().numpy(), ops.A)
     say(f"  A flips: detected 0/{n} (silent by design: only B is encoded)")
+
+
+def test_value_replacement_and_multibit_faults(binding, oracle):
+    """The second fault model of Section IV-C (an element takes an arbitrary wrong value) and
+    multi-bit upsets, workload 2.  At modulus 2^32: a changed C element is always detected; a
+    changed B element is flagged in exactly the rows it corrupts."""
+    import torch
+    b = binding
+    cfg = 2
+    ops = wlmod.make_operands(cfg)
+    wl = ops.wl
+    ref = oracle.checked_gemm(ops.A, ops.B)
+    rig = Rig(b, cfg)
+    fl = torch.empty(wl.M, dtype=torch.int32, device="cuda")
+    ct = torch.empty(1, dtype=torch.int32, device="cuda")
+
+    def c_campaign(name, r, c, masks):
+        n = len(r)
+        want_flag, want_val = oracle.campaign_c_masks(ref.C, ref.chk, r, c, masks)
+        assert np.array_equal(want_flag, (masks != 0).astype(np.int32))
+        flags = torch.empty((n, wl.M), dtype=torch.int32, device="cuda")
+        cnt = torch.empty(n, dtype=torch.int32, device="cuda")
+        vals = torch.empty(n, dtype=torch.int32, device="cuda")
+        inj = torch.from_numpy(np.stack([r, c, masks.view(np.int32)], axis=1).astype(np.int32)).cuda().contiguous()
+        for t in range(n):
+            rig.run(flags[t], cnt[t:t + 1], inj=inj[t])
+            vals[t:t + 1].copy_(rig.C[int(r[t]), int(c[t]):int(c[t]) + 1])
+        torch.cuda.synchronize()
+        expect = np.zeros((n, wl.M), np.int32)
+        expect[np.arange(n), r] = want_flag
+        assert np.array_equal(flags.cpu().numpy(), expect)
+        assert np.array_equal(cnt.cpu().numpy(), want_flag)
+        assert np.array_equal(vals.cpu().numpy(), want_val)
+        say(f"  {name}: detected {int(want_flag.sum())}/{int((masks != 0).sum())} changed elements")
+
+    def b_campaign(name, k, j, new):
+        n = len(k)
+        want_flags, want_col = oracle.campaign_b_values(ops.A, ops.B, ref.C, ref.chk, k, j, new)
+        flags = torch.empty((n, wl.M), dtype=torch.int32, device="cuda")
+        cols = torch.empty((n, wl.M), dtype=torch.int32, device="cuda")
+        for t in range(n):
+            diff = (int(ops.B[k[t], j[t]]) & 0xFF) ^ (int(new[t]) & 0xFF)
+            bits = [bit for bit in range(8) if diff >> bit & 1]
+            for bit in bits:
+                b.abft_packed_b_flip_bit(rig.Bp, int(k[t]), int(j[t]), bit)
+            rig.run(flags[t], ct)
+            for bit in bits:
+                b.abft_packed_b_flip_bit(rig.Bp, int(k[t]), int(j[t]), bit)
+            cols[t].copy_(rig.C[:, int(j[t])])
+        torch.cuda.synchronize()
+        assert np.array_equal(flags.cpu().numpy(), want_flags)
+        assert np.array_equal(cols.cpu().numpy(), want_col)
+        corrupted = (want_col != ref.C[:, j].T).any(axis=1)
+        detected = want_flags.any(axis=1)
+        assert np.array_equal(corrupted, detected)
+        say(f"  {name}: C corrupted in {int(corrupted.sum())}/{n} runs, detected {int(detected.sum())}")
+
+    n = 2000
+    say("campaign: workload 2, value replacement in C")
+    r, c, new = wlmod.draw_value_faults(cfg, "C", n)
+    c_campaign("C value replacement", r, c, (ref.C[r, c].view(np.uint32) ^ new.view(np.uint32)).astype(np.uint32))
+    for nb in (2, 3):
+        say(f"campaign: workload 2, {nb}-bit upsets in C")
+        r, c, masks = wlmod.draw_multibit_masks(cfg, "C", n, nb)
+        c_campaign(f"C {nb}-bit upsets", r, c, masks)
+    say("campaign: workload 2, value replacement in B")
+    k, j, new = wlmod.draw_value_faults(cfg, "B", n)
+    b_campaign("B value replacement", k, j, new)
+    say("campaign: workload 2, 2-bit upsets in B")
+    k, j, masks = wlmod.draw_multibit_masks(cfg, "B", n, 2)
+    new = ((ops.B[k, j].astype(np.int32) & 0xFF) ^ masks.astype(np.int32)).astype(np.uint8).view(np.int8).astype(np.int32)
+    b_campaign("B 2-bit upsets", k, j, new)
+    rig.run(fl, ct)
+    torch.cuda.synchronize()
+    assert int(ct.item()) == 0 and not fl.any().item() and np.array_equal(rig.C.cpu().numpy(), ref.C)

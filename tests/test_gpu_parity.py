@@ -117,6 +117,12 @@ def test_c_flips_flag_exactly_their_rows(binding, gpu_util, oracle, variant):
         assert np.array_equal(out["flags"], ref.flags), f"bit {bit}"
         assert out["err_count"] == ref.err_count
         assert not out["ws"].any()
+    # entries that name the same element compose (XOR of the masks), in either order, also to nothing
+    for inj in ([(77, 100, 0x0000FF00), (5, 5, 2), (77, 100, 0x00F0F000)], [(20, 30, 0x80000001), (20, 30, 0x80000001)]):
+        ref = oracle.checked_gemm(A, B, flips_c=inj)
+        out = run.gemm(A, variant=variant, injections=inj, ws=ws)
+        assert np.array_equal(out["C"], ref.C) and np.array_equal(out["flags"], ref.flags)
+        assert out["err_count"] == ref.err_count and not out["ws"].any()
     # two flips in one row that cancel in the row sum (+2^5 and -2^5) are silent in both
     clean = oracle.gemm_u8s8s32(A, B)
     cols = [c for c in range(N) if not (clean[10, c] >> 5) & 1][:1] + [c for c in range(N) if (clean[10, c] >> 5) & 1][:1]
@@ -354,3 +360,22 @@ def test_calibration_copy_is_a_copy(binding):
     binding.abft_calib_copy(src, dst)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("variant", ["tile256w2x4", "tile256w4x2"])
+def test_eight_wavefront_variants(binding, gpu_util, oracle, variant):
+    M, N, K = 300, 520, 384
+    say(f"8-wavefront variant {variant} {M}x{N}x{K}")
+    A, B = operands(M, N, K, 41)
+    run = gpu_util.GpuRun(binding, B)
+    inj = [(299, 519, 1 << 30), (0, 0, 1), (131, 260, 0x00010000)]
+    ref = oracle.checked_gemm(A, B, flips_c=inj)
+    out = run.gemm(A, variant=variant, injections=inj)
+    assert np.array_equal(out["C"], ref.C) and np.array_equal(out["flags"], ref.flags)
+    assert out["err_count"] == ref.err_count == 3 and not out["ws"].any()
+    mult = np.full(N, 3e-4, np.float32)
+    clean = oracle.checked_gemm(A, B)
+    out = run.gemm(A, variant=variant, requant=(128, 128, mult, None), want_c=False)
+    want = oracle.requantize(clean.C, clean.colsum, 128, 128, mult, precision="f32")
+    assert np.array_equal(out["Cq"], want) and out["err_count"] == 0

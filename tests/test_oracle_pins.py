@@ -251,6 +251,36 @@ def test_campaign_helpers_match_full_recomputation(oracle):
         assert arow[t].tolist() == full.C[i_[t]].tolist()
 
 
+def test_value_and_multibit_campaign_helpers(oracle):
+    """The value-replacement and multi-bit helpers against full recomputation, and the closed
+    forms that hold at modulus 2^32: any change of a C element moves its row sum; a change of
+    B[k][j] by d (0 < |d| <= 255) moves row p by A[p][k]*d, which is 0 only when A[p][k] is."""
+    rng = wlmod.rng_for(0, 11)
+    M, N, K = 6, 17, 21
+    A = wlmod.draw_a(rng, M, K, relu_like=True)
+    B = wlmod.draw_b(rng, K, N)
+    base = oracle.checked_gemm(A, B)
+    n = 60
+    r_, c_ = rng.integers(M, size=n), rng.integers(N, size=n)
+    new_c = rng.integers(-2**31, 2**31, size=n, dtype=np.int64).astype(np.int32)
+    masks = (base.C[r_, c_].view(np.uint32) ^ new_c.view(np.uint32)).astype(np.uint32)
+    flag, val = oracle.campaign_c_masks(base.C, base.chk, r_, c_, masks)
+    assert val.tolist() == new_c.tolist()
+    assert flag.tolist() == (masks != 0).astype(np.int32).tolist()
+    k_, j_ = rng.integers(K, size=n), rng.integers(N, size=n)
+    new_b = rng.integers(-128, 128, size=n, dtype=np.int32)
+    bflags, bcol = oracle.campaign_b_values(A, B, base.C, base.chk, k_, j_, new_b)
+    for t in range(n):
+        full = oracle.checked_gemm(A, B, flips_c=[(int(r_[t]), int(c_[t]), int(masks[t]))])
+        assert flag[t] == full.flags[r_[t]] == full.err_count and val[t] == full.C[r_[t], c_[t]]
+        diff = (int(B[k_[t], j_[t]]) & 0xFF) ^ (int(new_b[t]) & 0xFF)
+        full = oracle.checked_gemm(A, B, flips_b=[(int(k_[t]), int(j_[t]), bit) for bit in range(8) if diff >> bit & 1])
+        assert bflags[t].tolist() == full.flags.tolist()
+        assert bcol[t].tolist() == full.C[:, j_[t]].tolist()
+        changed = int(new_b[t]) != int(B[k_[t], j_[t]])
+        assert bflags[t].tolist() == [int(changed and A[p, k_[t]] != 0) for p in range(M)]
+
+
 # ---- Algorithm 1 with the printed modulus ------------------------------------------------
 
 def golden():
