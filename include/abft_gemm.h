@@ -46,6 +46,11 @@ extern "C" {
 /* flags of abft_gemm_u8s8s32_checked */
 #define ABFT_CHECK 0u             /* default: verify every row (Algorithm 1) */
 #define ABFT_NOCHECK 1u           /* same kernel with the checksum work compiled out */
+#define ABFT_MOD127 2u            /* Algorithm 1 to the letter: the checksum column is
+                                     rowSum = (B e) mod 127, one 8-bit column (Section
+                                     IV-A-2), and a row is flagged when its sum and its
+                                     checksum entry differ modulo 127.  Tiled kernels,
+                                     16-byte aligned A, K <= 65536. */
 #define ABFT_VARIANT_MASK 0xF00u  /* 0 = choose by shape */
 #define ABFT_VARIANT_TILE256 0x100u
 #define ABFT_VARIANT_TILE128 0x200u
@@ -172,6 +177,10 @@ int abft_row_checksum(const uint8_t* A, int64_t lda, int M, const abft_packed_b*
  * the known-size reference that a profiler's HBM traffic counters are scaled
  * by when the GEMM kernels' traffic is reported. */
 int abft_calib_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+/* rowSum[k] = (B e)[k] mod 127 in [0,126] as int32 [K]: the 8-bit checksum column
+ * of Algorithm 1 as printed, for parity checks of ABFT_MOD127. */
+int abft_packed_b_get_checksum_mod127(const abft_packed_b* Bp, int32_t* rowSum, void* stream);
 
 /* Message for the last non-OK return on this host thread. */
 const char* abft_last_error(void);

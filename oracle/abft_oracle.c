@@ -254,6 +254,33 @@ void oracle_campaign_b_flips(const uint8_t* A, int64_t lda, const int8_t* B, int
     }
 }
 
+/* The same B-fault campaign under Algorithm 1 as printed: chk is the product with the
+ * 8-bit column rowSum = S_B mod 127 (stale after the flip), the row sums are taken without
+ * overflow and the comparison is modulo 127.  out_flags and out_col are [n_inj][M]. */
+void oracle_campaign_b_flips_mod127(const uint8_t* A, int64_t lda, const int8_t* B, int64_t ldb,
+                                    const int32_t* C_clean, int64_t ldc, int M, int N, int K,
+                                    const int32_t* chk127, int n_inj, const int32_t* ks,
+                                    const int32_t* js, const int32_t* bits, int32_t* out_flags,
+                                    int32_t* out_col) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < n_inj; ++t) {
+        const int kf = ks[t], jf = js[t];
+        const int8_t flipped = (int8_t)((uint8_t)B[(int64_t)kf * ldb + jf] ^ (uint8_t)(1u << bits[t]));
+        for (int i = 0; i < M; ++i) {
+            uint32_t c = 0;
+            for (int k = 0; k < K; ++k) {
+                const int8_t b = (k == kf) ? flipped : B[(int64_t)k * ldb + jf];
+                c += (uint32_t)A[(int64_t)i * lda + k] * (uint32_t)(int32_t)b;
+            }
+            int64_t s = 0;
+            for (int j = 0; j < N; ++j)
+                s += (j == jf) ? (int32_t)c : C_clean[(int64_t)i * ldc + j];
+            out_col[(int64_t)t * M + i] = (int32_t)c;
+            out_flags[(int64_t)t * M + i] = (floor_mod127(s) != floor_mod127(chk127[i])) ? 1 : 0;
+        }
+    }
+}
+
 /* The second fault model of Section IV-C (an element takes an arbitrary wrong value) and
  * multi-bit upsets, in the 32-bit intermediate: element (r,c) of a clean C is XOR-ed with
  * `mask` (mask = old ^ new for a replacement) before the row sums are taken.  Same procedure

@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_campaign_c_flips.argtypes = [_i32p, _i64, _int, _i32p, _int, _i32p, _i32p, _i32p, _i32p, _i32p]
         L.oracle_campaign_b_flips.argtypes = [_u8p, _i64, _i8p, _i64, _i32p, _i64, _int, _int, _int, _i32p,
                                               _int, _i32p, _i32p, _i32p, _i32p, _i32p]
+        L.oracle_campaign_b_flips_mod127.argtypes = [_u8p, _i64, _i8p, _i64, _i32p, _i64, _int, _int, _int, _i32p,
+                                                     _int, _i32p, _i32p, _i32p, _i32p, _i32p]
         L.oracle_campaign_c_masks.argtypes = [_i32p, _i64, _int, _i32p, _int, _i32p, _i32p, _u32p, _i32p, _i32p]
         L.oracle_campaign_b_values.argtypes = [_u8p, _i64, _i8p, _i64, _i32p, _i64, _int, _int, _int, _i32p,
                                                _int, _i32p, _i32p, _i32p, _i32p, _i32p]
@@ -274,6 +276,34 @@ def campaign_b_flips(A, B, C_clean, chk, ks, js, bits):
     lib().oracle_campaign_b_flips(_p(A, _u8p), _ld(A), _p(B, _i8p), _ld(B), _p(C_clean, _i32p), _ld(C_clean),
                                   M, N, K, _p(chk, _i32p), n, _p(ks, _i32p), _p(js, _i32p), _p(bits, _i32p),
                                   _p(flags, _i32p), _p(col, _i32p))
+    return flags, col
+
+
+def row_checksum_mod127(A, B) -> np.ndarray:
+    """C_temp[i][n] of Algorithm 1 as printed: A times the 8-bit column rowSum = (B e) mod 127."""
+    A = _c(A, np.uint8)
+    rs = b_checksum_mod127(B)
+    M, K = A.shape
+    chk = np.empty(M, np.int32)
+    lib().oracle_row_checksum_mod127(_p(A, _u8p), _ld(A), _p(rs, _i8p), M, K, _p(chk, _i32p))
+    return chk
+
+
+def campaign_b_flips_mod127(A, B, C_clean, chk127, ks, js, bits):
+    """campaign_b_flips under the printed modulus: (flags[M], recomputed column j of C [M])."""
+    A = _c(A, np.uint8)
+    B = _c(B, np.int8)
+    C_clean = _c(C_clean, np.int32)
+    chk127 = _c(chk127, np.int32)
+    ks, js, bits = _i32(ks), _i32(js), _i32(bits)
+    M, K = A.shape
+    N = B.shape[1]
+    n = ks.size
+    flags = np.empty((n, M), np.int32)
+    col = np.empty((n, M), np.int32)
+    lib().oracle_campaign_b_flips_mod127(_p(A, _u8p), _ld(A), _p(B, _i8p), _ld(B), _p(C_clean, _i32p), _ld(C_clean),
+                                         M, N, K, _p(chk127, _i32p), n, _p(ks, _i32p), _p(js, _i32p), _p(bits, _i32p),
+                                         _p(flags, _i32p), _p(col, _i32p))
     return flags, col
 
 

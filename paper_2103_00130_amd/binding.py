@@ -16,11 +16,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libabftgemm.so")
 
 ABFT_OK, ABFT_EINVAL, ABFT_EUNSUPPORTED, ABFT_EHIP = 0, -1, -2, -3
-ABFT_CHECK, ABFT_NOCHECK = 0, 1
+ABFT_CHECK, ABFT_NOCHECK, ABFT_MOD127 = 0, 1, 2
 ABFT_VARIANT_TILE256, ABFT_VARIANT_TILE128, ABFT_VARIANT_TILE64, ABFT_VARIANT_SMALLM = 0x100, 0x200, 0x300, 0x400
 
 EXPORTS = (
-    "abft_pack_b_checksum", "abft_packed_b_dims", "abft_packed_b_get_checksum", "abft_packed_b_get_col_offsets",
+    "abft_pack_b_checksum", "abft_packed_b_dims", "abft_packed_b_get_checksum", "abft_packed_b_get_checksum_mod127",
+    "abft_packed_b_get_col_offsets",
     "abft_packed_b_flip_bit", "abft_packed_b_flip_checksum_bit", "abft_packed_b_destroy",
     "abft_gemm_workspace_bytes", "abft_workspace_init", "abft_gemm_u8s8s32_checked", "abft_requantize_u8",
     "abft_verify_rows", "abft_row_checksum", "abft_calib_copy", "abft_last_error",
@@ -51,6 +52,7 @@ def _load() -> ctypes.CDLL:
     L.abft_pack_b_checksum.argtypes = [vp, i64, i32, i32, i32, vp, ctypes.POINTER(vp)]
     L.abft_packed_b_dims.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.abft_packed_b_get_checksum.argtypes = [vp, vp, vp]
+    L.abft_packed_b_get_checksum_mod127.argtypes = [vp, vp, vp]
     L.abft_packed_b_get_col_offsets.argtypes = [vp, vp, vp]
     L.abft_packed_b_flip_bit.argtypes = [vp, i32, i32, i32, vp]
     L.abft_packed_b_flip_checksum_bit.argtypes = [vp, i32, i32, vp]
@@ -135,6 +137,11 @@ def abft_packed_b_dims(Bp: PackedB):
 def abft_packed_b_get_checksum(Bp: PackedB, S_B: torch.Tensor, stream=None):
     assert S_B.numel() >= Bp.K
     _check(lib.abft_packed_b_get_checksum(Bp.handle, _ptr(S_B, torch.int32, "S_B"), _stream(stream)))
+
+
+def abft_packed_b_get_checksum_mod127(Bp: PackedB, row_sum: torch.Tensor, stream=None):
+    assert row_sum.numel() >= Bp.K
+    _check(lib.abft_packed_b_get_checksum_mod127(Bp.handle, _ptr(row_sum, torch.int32, "row_sum"), _stream(stream)))
 
 
 def abft_packed_b_get_col_offsets(Bp: PackedB, colsum: torch.Tensor, stream=None):

@@ -49,7 +49,9 @@ struct abft_packed_b {
     int8_t* limbs;     // KB*64*4 bytes
     int32_t* S_B;      // [KB*64], zero past K
     int32_t* colsum;   // [NT*256], zero past N
-    int32_t* total;    // [1] sum of S_B (wrap-around)
+    int32_t* total;    // [0] sum of S_B (wrap-around), [1] sum of S_B127
+    int8_t* limbs127;  // as limbs, for rowSum = S_B mod 127 (digit 0 only)
+    int32_t* S_B127;   // [KB*64] S_B mod 127 in [0,126], zero past K
 };
 
 namespace abft {
@@ -67,6 +69,7 @@ struct GemmParams {
     int M, N, K, KB;           // KB: k-blocks of 64 in the packed weight (even)
     int KB2;                   // stages of 128 k-values = KB / 2
     int a_vec_ok;              // A and lda are multiples of 16 bytes
+    int mod127;                // compare modulo 127 (Algorithm 1 as printed) instead of 2^32
     const int8_t* packed;
     const int8_t* limbs;
     const int32_t* colsum;

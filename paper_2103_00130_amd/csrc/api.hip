@@ -37,6 +37,8 @@ void free_handle(abft_packed_b* h) {
     (void)hipFree(h->S_B);
     (void)hipFree(h->colsum);
     (void)hipFree(h->total);
+    (void)hipFree(h->limbs127);
+    (void)hipFree(h->S_B127);
     delete h;
 }
 
@@ -73,6 +75,8 @@ int abft_pack_b_checksum(const int8_t* B, int64_t ldb, int K, int N, int b_is_tr
     if (e == hipSuccess) e = hipMalloc(&h->S_B, (size_t)h->KB * abft::kUnitK * sizeof(int32_t));
     if (e == hipSuccess) e = hipMalloc(&h->colsum, (size_t)h->NT * abft::kTileN * sizeof(int32_t));
     if (e == hipSuccess) e = hipMalloc(&h->total, 64);
+    if (e == hipSuccess) e = hipMalloc(&h->limbs127, (size_t)h->KB * abft::kUnitK * abft::kLimbs);
+    if (e == hipSuccess) e = hipMalloc(&h->S_B127, (size_t)h->KB * abft::kUnitK * sizeof(int32_t));
     if (e == hipSuccess) e = abft::launch_pack(B, ldb, b_is_transposed ? 1 : 0, h, (hipStream_t)stream);
     if (e != hipSuccess) {
         free_handle(h);
@@ -92,6 +96,13 @@ int abft_packed_b_dims(const abft_packed_b* Bp, int* K, int* N) {
 int abft_packed_b_get_checksum(const abft_packed_b* Bp, int32_t* S_B, void* stream) {
     if (!Bp || !S_B) return fail(ABFT_EINVAL, "abft_packed_b_get_checksum: null pointer");
     HIP_TRY(hipMemcpyAsync(S_B, Bp->S_B, (size_t)Bp->K * sizeof(int32_t), hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+int abft_packed_b_get_checksum_mod127(const abft_packed_b* Bp, int32_t* rowSum, void* stream) {
+    if (!Bp || !rowSum) return fail(ABFT_EINVAL, "abft_packed_b_get_checksum_mod127: null pointer");
+    HIP_TRY(hipMemcpyAsync(rowSum, Bp->S_B127, (size_t)Bp->K * sizeof(int32_t), hipMemcpyDeviceToDevice,
+                           (hipStream_t)stream));
     return ABFT_OK;
 }
 
@@ -188,6 +199,14 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
     p.inj = inj;
     p.n_inj = n_inj;
     p.ws = (int32_t*)workspace;
+    const bool mod127 = check && (flags & ABFT_MOD127) != 0;
+    if (mod127) {
+        // exact (unwrapped) 32-bit entries are what the congruence modulo 127 needs
+        if (Bp->K > 65536) return fail(ABFT_EUNSUPPORTED, "%s: modulus 127 needs K <= 65536, got %d", fn, Bp->K);
+        p.mod127 = 1;
+        p.limbs = Bp->limbs127;
+        p.total = Bp->total + 1;
+    }
 
     int variant = (int)((flags & ABFT_VARIANT_MASK) >> 8);
     const bool chosen = variant != 0;
@@ -198,7 +217,9 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
         if (tiles(128) >= 192) return (int)abft::kTile128;
         return (int)abft::kTile64;
     };
-    if (!chosen) variant = M <= 64 ? (int)abft::kSmallM : pick_tile();
+    if (!chosen) variant = (M <= 64 && !mod127) ? (int)abft::kSmallM : pick_tile();
+    if (mod127 && variant == abft::kSmallM)
+        return fail(ABFT_EUNSUPPORTED, "%s: modulus 127 is implemented by the tiled kernels only", fn);
     hipError_t e;
     if (variant == abft::kSmallM) {
         if (M > 64) return fail(ABFT_EUNSUPPORTED, "%s: the streaming variant takes M <= 64, got %d", fn, M);

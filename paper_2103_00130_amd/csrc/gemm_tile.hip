@@ -17,6 +17,7 @@ hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, c
     // (and 32-bit byte offsets into A)
     const bool fast_a = p.a_vec_ok && (p.K % 16 == 0) && ((int64_t)(p.M - 1) * p.lda + p.K <= 0x7fffffffll);
     if (!fast_a) {
+        if (p.mod127) return hipErrorNotSupported;
         if (variant == kTile64) return launch_gemm_tile_g64(check, want_c, want_q, p, s);
         return launch_gemm_tile_g128(check, want_c, want_q, p, s);
     }

@@ -61,6 +61,14 @@ __device__ inline uint32_t sum32(uint32_t s) {
     return sw[0] + sw[1];
 }
 
+// v mod 127 in [0,126] for |v| < 2^59: 2^28 = (2^7)^4 is 1 modulo 127, so the two parts of
+// v = hi * 2^28 + lo (floor split) may simply be added before the 32-bit remainder
+__device__ inline int32_t floor_mod127(long long v) {
+    const int32_t x = (int32_t)(v >> 28) + (int32_t)(v & 0x0FFFFFFF);
+    const int32_t r = x % 127;
+    return r < 0 ? r + 127 : r;
+}
+
 template <int BM, int BN, int WGM, int WGN, bool kCheck, int kOut>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const GemmParams p, const int tiles_m,
                                                                         const int tiles_n) {
@@ -384,8 +392,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     // fast memory takes them (several microseconds per tile), so the vector arithmetic placed
     // between them - the add-back, the row sums and their cross-lane reduction - costs nothing.
     int32_t cs_lane = 0;  // this lane's share of the add-back in a row sum
+    long long cs_lane64 = 0;
 #pragma unroll
-    for (int t = 0; t < TN; ++t) cs_lane += cs[t];
+    for (int t = 0; t < TN; ++t) {
+        cs_lane += cs[t];
+        cs_lane64 += cs[t];
+    }
     const int r_lane = wm * WTM + 4 * lhalf;   // first row of this lane inside the tile
     const int c_lane = wn * WTN + lcol;
     const bool full = (row0 + BM <= p.M) && (col0 + BN <= p.N);
@@ -395,8 +407,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     int32_t* cptr = kWantC ? p.C + (int64_t)(row0 + r_lane) * p.ldc + col0 + c_lane : nullptr;
     uint8_t* qptr = kWantQ ? p.Cq + (int64_t)(row0 + r_lane) * p.ldcq + col0 + c_lane : nullptr;
     const int rows_left = p.M - row0 - r_lane;  // rows of this lane's column that exist
-    auto store_blocks = [&](auto full_c) __attribute__((always_inline)) {
+    auto store_blocks = [&](auto full_c, auto mod_c) __attribute__((always_inline)) {
         constexpr bool FULL = decltype(full_c)::value;  // no bounds to test inside a whole tile
+        constexpr bool MOD = decltype(mod_c)::value;    // row sums as residues modulo 127 (Algorithm 1 as printed)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -406,10 +419,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                     const int e = g * 4 + ee;
                     const int roff = i * 32 + 8 * g + ee;
                     uint32_t rs = (uint32_t)cs_lane;
+                    long long rs64 = cs_lane64;  // exact sum for the residue (a wrapped sum would break it)
 #pragma unroll
                     for (int t = 0; t < TN; ++t) {
                         const int32_t raw = acc[i][t][e];
-                        if (kCheck) rs += (uint32_t)raw;  // columns past N hold zeros
+                        if (kCheck && !MOD) rs += (uint32_t)raw;  // columns past N hold zeros
+                        if (kCheck && MOD) rs64 += raw;
                         const int32_t val = raw + cs[t];
                         if (FULL || (roff < rows_left && col0 + c_lane + t * 32 < p.N)) {
                             if (kWantC) cptr[t * 32] = val;
@@ -417,6 +432,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                         }
                     }
                     if (kCheck) {
+                        if (MOD) rs = (uint32_t)floor_mod127(rs64);
                         rs = sum32(rs);
                         if (lcol == 0) s_rs[wn * BM + wm * WTM + roff + 4 * lhalf] = (int32_t)rs;
                     }
@@ -430,8 +446,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
             }
     };
 
-    if (full) store_blocks(std::true_type{});
-    else store_blocks(std::false_type{});
+    const bool mod127 = kCheck && p.mod127 != 0;
+    if (mod127) {
+        if (full) store_blocks(std::true_type{}, std::true_type{});
+        else store_blocks(std::false_type{}, std::true_type{});
+    } else {
+        if (full) store_blocks(std::true_type{}, std::false_type{});
+        else store_blocks(std::false_type{}, std::false_type{});
+    }
 
     if (p.n_inj > 0) {
         // Simulated faults in the 32-bit intermediate (test hook): the element is flipped where it
@@ -467,7 +489,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                 const int32_t val = raw + cs_hit, bad = (int32_t)((uint32_t)val ^ mask);
                 if (kWantC) p.C[(int64_t)row * p.ldc + col] = bad;
                 if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_one(bad, zcs_hit, col, p.rq);
-                if (kCheck) atomicAdd(&s_rs[wn * BM + wm * WTM + r], bad - val);
+                if (kCheck) atomicAdd(&s_rs[wn * BM + wm * WTM + r], mod127 ? floor_mod127((long long)bad - val) : bad - val);
             }
         }
     }
@@ -501,15 +523,24 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                 uint32_t d = 0;
 #pragma unroll
                 for (int w = 0; w < WGN; ++w) d += (uint32_t)s_rs[w * BM + r];
-                d -= (uint32_t)s_ck[r];
-                if (tile_n == 0) d -= 128u * (uint32_t)(*p.total);  // sum_k 128*S_B[k], once per row
+                if (mod127) {
+                    // residues: sums of at most 32 lanes x WGN waves of values below 127, minus the exact
+                    // checksum share, as a residue again so that the workspace word cannot wrap
+                    long long dd = (long long)d - (long long)s_ck[r];
+                    if (tile_n == 0) dd -= 128ll * (long long)(*p.total);
+                    d = (uint32_t)floor_mod127(dd);
+                } else {
+                    d -= (uint32_t)s_ck[r];
+                    if (tile_n == 0) d -= 128u * (uint32_t)(*p.total);  // sum_k 128*S_B[k], once per row
+                }
                 const unsigned long long old = __hip_atomic_fetch_add(ws_rows + row0 + r, ((unsigned long long)d << 32) | 1ull,
                                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if ((uint32_t)old == (uint32_t)tiles_n - 1u) {
                     const uint32_t diff = (uint32_t)(old >> 32) + d;
+                    const int bad_row = mod127 ? (diff % 127u != 0) : (diff != 0);
                     __hip_atomic_store(ws_rows + row0 + r, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    p.row_flags[row0 + r] = diff != 0;
-                    my_err += diff != 0;
+                    p.row_flags[row0 + r] = bad_row;
+                    my_err += bad_row;
                 }
             }
         }

@@ -48,8 +48,11 @@ __device__ inline void write_digits(int8_t* limbs, int k, int32_t s) {
     }
 }
 
+// For Algorithm 1 as printed (Section IV-A-2) the same pass also emits rowSum[k] = S_B[k] mod 127
+// in [0,126]: as an int32 array and, in the digit layout, as a single live digit column.
 __global__ void checksum_rows_kernel(const int8_t* __restrict__ B, int64_t ldb, int transposed, int K, int N,
-                                     int Kpad, int32_t* __restrict__ S_B, int8_t* __restrict__ limbs) {
+                                     int Kpad, int32_t* __restrict__ S_B, int8_t* __restrict__ limbs,
+                                     int32_t* __restrict__ S_B127, int8_t* __restrict__ limbs127) {
     const int k = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
     const int lane = threadIdx.x % 64;
     if (k >= Kpad) return;
@@ -60,6 +63,10 @@ __global__ void checksum_rows_kernel(const int8_t* __restrict__ B, int64_t ldb, 
     if (lane == 0) {
         S_B[k] = s;
         write_digits(limbs, k, s);
+        int32_t r = s % 127;
+        if (r < 0) r += 127;
+        S_B127[k] = r;
+        write_digits(limbs127, k, r);
     }
 }
 
@@ -123,11 +130,12 @@ hipError_t launch_pack(const int8_t* B, int64_t ldb, int transposed, abft_packed
     pack_units_kernel<<<dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, s>>>(
         B, ldb, transposed, h->K, h->N, h->KB, n_chunks, h->packed);
     checksum_rows_kernel<<<dim3((Kpad + 3) / 4), dim3(256), 0, s>>>(B, ldb, transposed, h->K, h->N, Kpad, h->S_B,
-                                                                    h->limbs);
+                                                                    h->limbs, h->S_B127, h->limbs127);
     fill_zero_kernel<<<dim3((unsigned)((Npad + 255) / 256)), dim3(256), 0, s>>>(h->colsum, (size_t)Npad);
     colsum_kernel<<<dim3((unsigned)(Npad / 64), (unsigned)((h->K + 255) / 256)), dim3(256), 0, s>>>(B, ldb, transposed, h->K, h->N,
                                                                                                   h->colsum);
     total_kernel<<<dim3(1), dim3(256), 0, s>>>(h->S_B, Kpad, h->total);
+    total_kernel<<<dim3(1), dim3(256), 0, s>>>(h->S_B127, Kpad, h->total + 1);
     return hipGetLastError();
 }
 

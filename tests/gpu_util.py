@@ -32,7 +32,7 @@ class GpuRun:
         self.b.abft_packed_b_get_col_offsets(self.Bp, out)
         return out.cpu().numpy()
 
-    def gemm(self, A, variant="auto", check=True, injections=(), requant=None, want_c=True, ws=None):
+    def gemm(self, A, variant="auto", check=True, injections=(), requant=None, want_c=True, ws=None, mod127=False):
         """A: numpy uint8 [M,K] or a device tensor.  requant = (zA, zC, mult_np, bias_np|None).
         Returns dict with C, flags, err_count, Cq (numpy; None where not produced)."""
         b = self.b
@@ -53,7 +53,7 @@ class GpuRun:
             rq = b.make_requant(zA, zC, mult_d, bias_d)
             Cq = torch.full((M, self.N), 7, dtype=torch.uint8, device="cuda")
         inj = b.make_injections(list(injections)) if len(injections) else None
-        fl = VARIANTS[variant] | (b.ABFT_CHECK if check else b.ABFT_NOCHECK)
+        fl = VARIANTS[variant] | (b.ABFT_CHECK if check else b.ABFT_NOCHECK) | (b.ABFT_MOD127 if mod127 else 0)
         b.abft_gemm_u8s8s32_checked(A_dev, self.Bp, C, flags, cnt, rq=rq, Cq=Cq, inj=inj, n_inj=len(injections),
                                     flags=fl, workspace=ws.tensor)
         torch.cuda.synchronize()

@@ -250,3 +250,45 @@ def test_value_replacement_and_multibit_faults(binding, oracle):
     rig.run(fl, ct)
     torch.cuda.synchronize()
     assert int(ct.item()) == 0 and not fl.any().item() and np.array_equal(rig.C.cpu().numpy(), ref.C)
+
+
+def test_campaign_mod127_b_flips(binding, oracle):
+    """Algorithm 1 as printed (ABFT_MOD127), workload 2, 10000 bit flips in B after the checksum
+    was taken (the protocol behind Table II): run by run the flags of the oracle, and the miss
+    rate per corrupted row that Section IV-C-1 predicts (operand values 127 and 254 out of the 255
+    that corrupt)."""
+    import torch
+    b = binding
+    cfg = 2
+    ops = wlmod.make_operands(cfg)
+    wl = ops.wl
+    clean = oracle.gemm_u8s8s32(ops.A, ops.B)
+    chk127 = oracle.row_checksum_mod127(ops.A, ops.B)
+    n = wl.n_flips["B"]
+    k, j, bit = wlmod.draw_flips(cfg, "B", n)
+    say(f"campaign: workload 2, {n} B flips, modulus 127")
+    want_flags, want_col = oracle.campaign_b_flips_mod127(ops.A, ops.B, clean, chk127, k, j, bit)
+    rig = Rig(b, cfg)
+    flags = torch.empty((n, wl.M), dtype=torch.int32, device="cuda")
+    cnt = torch.empty(n, dtype=torch.int32, device="cuda")
+    cols = torch.empty((n, wl.M), dtype=torch.int32, device="cuda")
+    for t in range(n):
+        b.abft_packed_b_flip_bit(rig.Bp, int(k[t]), int(j[t]), int(bit[t]))
+        b.abft_gemm_u8s8s32_checked(rig.A, rig.Bp, rig.C, flags[t], cnt[t:t + 1], flags=b.ABFT_MOD127,
+                                    workspace=rig.ws.tensor)
+        b.abft_packed_b_flip_bit(rig.Bp, int(k[t]), int(j[t]), int(bit[t]))
+        cols[t].copy_(rig.C[:, int(j[t])])
+    torch.cuda.synchronize()
+    assert np.array_equal(flags.cpu().numpy(), want_flags)
+    assert np.array_equal(cnt.cpu().numpy(), want_flags.sum(axis=1))
+    assert np.array_equal(cols.cpu().numpy(), want_col)
+    corrupted_rows = want_col != clean[:, j].T
+    missed_rows = corrupted_rows & (want_flags == 0)
+    runs_corrupted = corrupted_rows.any(axis=1)
+    runs_detected = want_flags.any(axis=1)
+    assert not (runs_detected & ~runs_corrupted).any()
+    rate = missed_rows.sum() / corrupted_rows.sum()
+    say(f"  modulus 127: C corrupted in {int(runs_corrupted.sum())}/{n} runs, detected {int(runs_detected.sum())} "
+        f"({100.0 * runs_detected.sum() / runs_corrupted.sum():.2f} %); corrupted rows missed "
+        f"{int(missed_rows.sum())}/{int(corrupted_rows.sum())} = {100 * rate:.3f} % (predicted 2/255 = 0.784 %)")
+    assert abs(rate - 2 / 255) < 0.002

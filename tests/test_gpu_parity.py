@@ -379,3 +379,76 @@ def test_eight_wavefront_variants(binding, gpu_util, oracle, variant):
     out = run.gemm(A, variant=variant, requant=(128, 128, mult, None), want_c=False)
     want = oracle.requantize(clean.C, clean.colsum, 128, 128, mult, precision="f32")
     assert np.array_equal(out["Cq"], want) and out["err_count"] == 0
+
+
+# ---- Algorithm 1 with its printed modulus (ABFT_MOD127) -----------------------------------
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("variant", ["auto", "tile64", "tile128", "tile256"])
+def test_mod127_matches_oracle(binding, gpu_util, oracle, variant):
+    import torch
+    M, N, K = 150, 290, 144            # the modulus is implemented on the aligned path: K a multiple of 16
+    say(f"mod 127: {M}x{N}x{K} variant={variant}")
+    A, B = operands(M, N, K, 17, relu_like=True)
+    A[3, 9], A[40, 9], A[41, 9] = 127, 254, 0      # operands on which a B fault at k = 9 is invisible modulo 127
+    run = gpu_util.GpuRun(binding, B)
+    rs = torch.empty(K, dtype=torch.int32, device="cuda")
+    binding.abft_packed_b_get_checksum_mod127(run.Bp, rs)
+    assert np.array_equal(rs.cpu().numpy(), oracle.b_checksum_mod127(B).astype(np.int32))
+    ws = binding.Workspace(M, run.Bp)
+    C0, flags0, n0 = oracle.checked_gemm_mod127(A, B)
+    out = run.gemm(A, variant=variant, mod127=True, ws=ws)
+    assert n0 == 0 and out["err_count"] == 0 and not out["flags"].any()
+    assert np.array_equal(out["C"], C0) and not out["ws"].any()
+    # C faults: every bit of the 32 (127 does not divide 2^b), several per launch, composed masks
+    rng = np.random.default_rng(5)
+    for bit in list(range(32)) + [None]:
+        inj = [(3, 7, 1 << 31), (3, 200, 1 << 4), (149, 289, 1), (64, 128, 0x00F0F000)] if bit is None else \
+              [(int(rng.integers(M)), int(rng.integers(N)), 1 << bit)]
+        Cw, fw, nw = oracle.checked_gemm_mod127(A, B, flips_c=inj)
+        out = run.gemm(A, variant=variant, mod127=True, injections=inj, ws=ws)
+        assert np.array_equal(out["C"], Cw) and np.array_equal(out["flags"], fw) and out["err_count"] == nw
+        assert bit is None or nw == 1
+    # a mask whose value change is a multiple of 127 is missed by both
+    clean = oracle.gemm_u8s8s32(A, B)
+    r, c = 20, 30
+    for delta in (127, 254, 127 * 4096):
+        mask = int(np.uint32(clean[r, c]) ^ np.uint32(np.int64(clean[r, c]) + delta))
+        Cw, fw, nw = oracle.checked_gemm_mod127(A, B, flips_c=[(r, c, mask)])
+        out = run.gemm(A, variant=variant, mod127=True, injections=[(r, c, mask)], ws=ws)
+        assert nw == 0 and out["err_count"] == 0 and np.array_equal(out["C"], Cw)
+    # B faults after the checksum was taken: flags follow the oracle row by row, misses included
+    missed_rows = 0
+    for (k, j, bit) in [(9, 11, 0), (9, 250, 7), (0, 0, 3), (139, 289, 6), (77, 128, 1)]:
+        Cw, fw, nw = oracle.checked_gemm_mod127(A, B, flips_b=[(k, j, bit)])
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        out = run.gemm(A, variant=variant, mod127=True, ws=ws)
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        assert np.array_equal(out["C"], Cw) and np.array_equal(out["flags"], fw) and out["err_count"] == nw
+        corrupted = (Cw != clean).any(axis=1)
+        missed_rows += int((corrupted & (fw == 0)).sum())
+    assert missed_rows >= 2, "rows with A = 127 or 254 at the faulty k are corrupted yet pass modulo 127"
+    out = run.gemm(A, variant=variant, ws=ws)           # the exact check on the same workspace afterwards
+    assert out["err_count"] == 0 and not out["ws"].any()
+
+
+@pytest.mark.gpu
+def test_mod127_full_size_and_refusals(binding, gpu_util, oracle):
+    import torch
+    ops = wlmod.make_operands(3)
+    say("mod 127: workload 3 full size")
+    run = gpu_util.GpuRun(binding, ops.B)
+    inj = [(1000, 1000, 1 << 20), (5, 6, 0x7)]
+    Cw, fw, nw = oracle.checked_gemm_mod127(ops.A, ops.B, flips_c=inj)
+    out = run.gemm(ops.A, mod127=True, injections=inj)
+    assert np.array_equal(out["C"], Cw) and np.array_equal(out["flags"], fw) and out["err_count"] == nw == 2
+    # the streaming kernel and unaligned operands do not implement the modulus
+    A, B = operands(16, 64, 64, 1)
+    small = gpu_util.GpuRun(binding, B)
+    out = small.gemm(A, mod127=True)                      # M <= 64 goes to a tiled kernel by itself
+    assert out["err_count"] == 0 and np.array_equal(out["C"], oracle.gemm_u8s8s32(A, B))
+    with pytest.raises(binding.AbftError):
+        small.gemm(A, variant="smallm", mod127=True)
+    buf = torch.zeros(16 * 64 + 1, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.AbftError):
+        small.gemm(buf[1:].view(16, 64), mod127=True)

@@ -251,6 +251,26 @@ def test_campaign_helpers_match_full_recomputation(oracle):
         assert arow[t].tolist() == full.C[i_[t]].tolist()
 
 
+def test_mod127_b_campaign_helper(oracle):
+    """The modulus-127 B-fault helper against full recomputation and against the closed form of
+    Section IV-C-1: the row sum moves by A[p][k]*d with d = +-2^b, which 127 divides only when it
+    divides A[p][k], i.e. for A[p][k] in {0, 127, 254}."""
+    rng = wlmod.rng_for(0, 13)
+    M, N, K = 9, 15, 20
+    A = wlmod.draw_a(rng, M, K)
+    A[0, :], A[1, :], A[2, :] = 127, 254, 0
+    B = wlmod.draw_b(rng, K, N)
+    clean = oracle.gemm_u8s8s32(A, B)
+    chk127 = oracle.row_checksum_mod127(A, B)
+    n = 40
+    k_, j_, b_ = rng.integers(K, size=n), rng.integers(N, size=n), rng.integers(8, size=n)
+    flags, col = oracle.campaign_b_flips_mod127(A, B, clean, chk127, k_, j_, b_)
+    for t in range(n):
+        Cw, fw, nw = oracle.checked_gemm_mod127(A, B, flips_b=[(int(k_[t]), int(j_[t]), int(b_[t]))])
+        assert flags[t].tolist() == fw.tolist() and col[t].tolist() == Cw[:, j_[t]].tolist()
+        assert flags[t].tolist() == [int(A[p, k_[t]] % 127 != 0) for p in range(M)]
+
+
 def test_value_and_multibit_campaign_helpers(oracle):
     """The value-replacement and multi-bit helpers against full recomputation, and the closed
     forms that hold at modulus 2^32: any change of a C element moves its row sum; a change of
