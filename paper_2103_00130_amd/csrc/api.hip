@@ -211,10 +211,12 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
     int variant = (int)((flags & ABFT_VARIANT_MASK) >> 8);
     const bool chosen = variant != 0;
     auto pick_tile = [&]() {
-        // largest tile that still gives (nearly) every compute unit a workgroup
+        // The larger the tile the better the matrix cores are fed, but a grid that leaves most of the
+        // 256 compute units without a workgroup loses more than that: thresholds from timing the
+        // three tile shapes on shapes between 128x2048 and 4096x4096.
         auto tiles = [&](int b) { return (int64_t)((M + b - 1) / b) * ((Bp->N + b - 1) / b); };
-        if (tiles(256) >= 192) return (int)abft::kTile256;
-        if (tiles(128) >= 192) return (int)abft::kTile128;
+        if (tiles(256) >= 128) return (int)abft::kTile256;
+        if (tiles(128) >= 96) return (int)abft::kTile128;
         return (int)abft::kTile64;
     };
     if (!chosen) variant = (M <= 64 && !mod127) ? (int)abft::kSmallM : pick_tile();

@@ -3,6 +3,6 @@
 
 namespace abft {
 hipError_t launch_gemm_tile_a64(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
-    return atile::launch_cfg<64, 64, 2, 1>(check, want_c, want_q, p, s);
+    return atile::launch_cfg<64, 64, 2, 1, 2>(check, want_c, want_q, p, s);
 }
 }  // namespace abft

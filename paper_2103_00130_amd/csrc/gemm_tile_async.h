@@ -69,13 +69,15 @@ __device__ inline int32_t floor_mod127(long long v) {
     return r < 0 ? r + 127 : r;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool kCheck, int kOut>
+template <int BM, int BN, int WGM, int WGN, int kStages, bool kCheck, int kOut>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const GemmParams p, const int tiles_m,
                                                                         const int tiles_n) {
     constexpr int NW = WGM * WGN, NT = NW * 64;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
     constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 blocks per wave
     constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK;
+    constexpr int S = kStages;                     // stages resident in LDS
+    static_assert(S >= 2, "at least a double buffer");
     constexpr int A_LD = (BM / 8) / NW;            // async A loads per wave per stage (8 rows each)
     constexpr int B_LD = (BN / 8) / NW;            // async B loads per wave per stage (1 KiB each)
     constexpr int CB = (WTM / 16) / WGN;           // 16-row checksum blocks per wave
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     static_assert(A_LD >= 1 && B_LD >= 1 && CB >= 1 && (WTM / 16) % WGN == 0, "tile too small for the workgroup");
     static_assert(BN >= 64 && NT <= 4 * BN, "epilogue scratch layout");
 
-    // LDS: [2][A_STAGE] then [2][B_STAGE]
+    // LDS: [S][A_STAGE] then [S][B_STAGE], then the scratch of the epilogue
     extern __shared__ __align__(1024) uint8_t smem[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) uint8_t*)smem);
 
@@ -150,7 +152,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         const int bc0 = wave * B_LD, kbl = bc0 / B_CHUNKS_PER_KB, cc0 = bc0 % B_CHUNKS_PER_KB;
         b_wave = p.packed + packed_unit_offset(tile_n / TILES_PER_NT, 0, (tile_n % TILES_PER_NT) * (BN / 32), p.KB2 * 2) +
                  (int64_t)kbl * B_KB_STRIDE + cc0 * 1024;
-        b_lds = lds_base + 2 * A_STAGE + kbl * (BN * 64) + cc0 * 1024;
+        b_lds = lds_base + S * A_STAGE + kbl * (BN * 64) + cc0 * 1024;
     }
 
     // load n of stage s into buffer buf: n < A_LD is an A load (8 rows x 128 B), the rest are
@@ -179,7 +181,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     int a_off[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) a_off[j] = (wm * WTM + (lane & 31)) * BK + (((2 * j + (lane >> 5)) ^ a_swz) << 4);
-    const int b_off = 2 * A_STAGE + wn * TN * 2048 + lane * 16;
+    const int b_off = S * A_STAGE + wn * TN * 2048 + lane * 16;
 
     v16i acc[TM][TN];
 #pragma unroll
@@ -212,13 +214,27 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     // is row (l&15) of a 16-row block, chunk 4*kbl + (l>>4) of the stage.
     v4i limb[2];
     limb[0] = limb[1] = v4i{0, 0, 0, 0};
+    // This tile column's contiguous share [ck_lo, ck_hi) of the checksum product's K range.  Its
+    // digits (512 bytes per stage) are copied to LDS once, before the main loop, when they fit
+    // (kLimbStages stages): the stages that use them then read LDS instead of waiting on a global
+    // load behind all the direct-to-LDS loads in flight.
+    constexpr int kLimbStages = 32;
+    const int ck_lo = kCheck ? (int)(((int64_t)tile_n * NS) / tiles_n) : 0;
+    const int ck_hi = kCheck ? (int)(((int64_t)(tile_n + 1) * NS) / tiles_n) : 0;
+    const bool limbs_in_lds = ck_hi - ck_lo <= kLimbStages;
+    uint8_t* const s_limb = smem + S * (A_STAGE + B_STAGE) + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t);
+    if (kCheck && limbs_in_lds)
+        for (int i = tid; i < (ck_hi - ck_lo) * 32; i += NT)
+            reinterpret_cast<v4i*>(s_limb)[i] = reinterpret_cast<const v4i*>(p.limbs + (int64_t)ck_lo * 512)[i];
     auto load_limbs = [&](int s) __attribute__((always_inline)) {
+        const int q = ((lane >> 4) * kLimbs + (lane & 15)) << 4;  // this lane's digit inside a k-block
 #pragma unroll
         for (int kbl = 0; kbl < 2; ++kbl) {
             limb[kbl] = v4i{0, 0, 0, 0};
-            if ((lane & 15) < kLimbs)
-                limb[kbl] = *reinterpret_cast<const v4i*>(
-                    p.limbs + ((((int64_t)(2 * s + kbl) * 4 + (lane >> 4)) * kLimbs + (lane & 15)) << 4));
+            if ((lane & 15) < kLimbs) {
+                if (limbs_in_lds) limb[kbl] = *reinterpret_cast<const v4i*>(s_limb + ((s - ck_lo) * 2 + kbl) * 256 + q);
+                else limb[kbl] = *reinterpret_cast<const v4i*>(p.limbs + (int64_t)(2 * s + kbl) * 256 + q);
+            }
         }
     };
     int ck_off[2];
@@ -227,6 +243,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         ck_off[kbl] = (wm * WTM + wn * CB * 16 + (lane & 15)) * BK + (((4 * kbl + (lane >> 4)) ^ a_swz) << 4);
     auto wait_lds = []() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0xC07F); };
     auto wait_vmem = []() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };
+    // at most n vector-memory operations still in flight (they complete in order)
+    auto wait_vmem_but = [](auto n_c) __attribute__((always_inline)) {
+        constexpr int n = decltype(n_c)::value;
+        static_assert(n >= 0 && n < 64, "vmcnt is a 6-bit field");
+        __builtin_amdgcn_s_waitcnt(((n >> 4) << 14) | (n & 15) | 0x0F70);
+    };
 
     // One k-step of 32: TM x TN MFMAs on fragment set f while fragment set f^1 is read for
     // k-step jn of buffer rbuf and loads [ld_lo, ld_hi) of stage ld_s go out to buffer ld_buf.
@@ -275,18 +297,28 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         }
     };
 
-    // cut points of a stage's loads over the k-steps in which they may be in flight: 3/8 go out
-    // during the last k-step of the stage before, 3/8 during the first and 2/8 during the second
-    // k-step of the stage that precedes theirs (measured best among the even spreads; issuing
-    // any in the third k-step leaves them too little time to land)
-    constexpr int LD_C0 = N_LD * 3 / 8, LD_C1 = N_LD * 6 / 8, LD_C2 = N_LD;
+    // Load schedule.
+    // Double buffer (S = 2): 3/8 of the loads of stage s+1 go out during the last k-step of
+    // stage s-1, 3/8 during the first and 2/8 during the second k-step of stage s (measured best
+    // among the even spreads; issuing any in the third k-step leaves them too little time to
+    // land before the barrier that follows it).
+    // Ring (S > 2, the small tiles, whose k-steps are too short to cover the latency of a load
+    // with one stage of lookahead): the slot of stage s is released by the barrier that follows
+    // its third k-step and is refilled with stage s+S, a quarter per k-step from the fourth
+    // k-step of stage s on; a stage therefore has S-1 stages of time to land, and at each
+    // barrier only what is older than the (S-2)*N_LD most recent loads is awaited.
+    constexpr int LD_C0 = S == 2 ? N_LD * 3 / 8 : N_LD / 4, LD_C1 = S == 2 ? N_LD * 6 / 8 : N_LD / 2,
+                  LD_C2 = S == 2 ? N_LD : N_LD * 3 / 4;
+    using pending_c = std::integral_constant<int, (S - 2) * N_LD>;
 #pragma unroll
-    for (int n = 0; n < N_LD; ++n) issue_load(0, 0, n);
-    wait_vmem();
+    for (int st = 0; st < S - 1; ++st)
+#pragma unroll
+        for (int n = 0; n < N_LD; ++n) issue_load(min(st, NS - 1), st, n);
+    wait_vmem_but(pending_c{});
     __syncthreads();
-    // first share of stage 1 (the rest goes out during the first two k-steps of stage 0)
+    // first share of the stage after those
 #pragma unroll
-    for (int n = 0; n < LD_C0; ++n) issue_load(min(1, NS - 1), 1, n);
+    for (int n = 0; n < LD_C0; ++n) issue_load(min(S - 1, NS - 1), S - 1, n);
     read_frags(0, 0, 0);
     wait_lds();
     __builtin_amdgcn_sched_barrier(0);
@@ -305,16 +337,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         using even_c = std::integral_constant<bool, PH != 1>;
         using odd_c = std::integral_constant<bool, PH != 0>;
         for (int s = s_begin; s < s_end; ++s) {
-            const int s1 = min(s + 1, NS - 1), s2 = min(s + 2, NS - 1);
+            // stage whose loads go out now, the slot they go to, and the slot of the next stage
+            const int s1 = min(s + S - 1, NS - 1), s2 = min(s + S, NS - 1);
+            const int nxt = cur + 1 == S ? 0 : cur + 1, tgt = cur == 0 ? S - 1 : cur - 1;
             // the digit operands of this stage are needed three quarters of a stage from now
             if (CHK) load_limbs(s);
-            phase(0, cur, 1, even_c{}, s1, cur ^ 1, LD_C0, LD_C1);
+            phase(0, cur, 1, even_c{}, s1, tgt, LD_C0, LD_C1);
             wait_lds();
             __builtin_amdgcn_sched_barrier(0);
-            phase(1, cur, 2, odd_c{}, s1, cur ^ 1, LD_C1, LD_C2);
+            phase(1, cur, 2, odd_c{}, s1, tgt, LD_C1, LD_C2);
             wait_lds();
             __builtin_amdgcn_sched_barrier(0);
-            phase(0, cur, 3, even_c{}, s1, cur ^ 1, LD_C2, N_LD);
+            phase(0, cur, 3, even_c{}, s1, tgt, LD_C2, N_LD);
             wait_lds();
             __builtin_amdgcn_sched_barrier(0);
             if (CHK) {
@@ -330,24 +364,22 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                         cacc[c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, limb[kbl], cacc[c], 0, 0, 0);
                     }
             }
-            // publish the next stage: this wave's loads have landed, and after the barrier
-            // nobody reads the old stage any more
-            wait_vmem();
+            // publish the next stage: this wave's loads of it have landed, and after the
+            // barrier nobody reads the current stage any more
+            wait_vmem_but(pending_c{});
             __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
-            phase(1, cur ^ 1, 0, odd_c{}, s2, cur, 0, LD_C0);
+            phase(1, nxt, 0, odd_c{}, s2, cur, 0, LD_C0);
             wait_lds();
             __builtin_amdgcn_sched_barrier(0);
-            cur ^= 1;
+            cur = nxt;
         }
     };
     auto run_all = [&](auto ph_c) __attribute__((always_inline)) {
         if (kCheck) {
-            // this tile column's contiguous share of the checksum product's K range
-            const int lo = (int)(((int64_t)tile_n * NS) / tiles_n), hi = (int)(((int64_t)(tile_n + 1) * NS) / tiles_n);
-            run(0, lo, std::false_type{}, ph_c);
-            run(lo, hi, std::true_type{}, ph_c);
-            run(hi, NS, std::false_type{}, ph_c);
+            run(0, ck_lo, std::false_type{}, ph_c);
+            run(ck_lo, ck_hi, std::true_type{}, ph_c);
+            run(ck_hi, NS, std::false_type{}, ph_c);
         } else {
             run(0, NS, std::false_type{}, ph_c);
         }
@@ -364,7 +396,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     const int lcol = lane & 31, lhalf = lane >> 5;
     // LDS scratch behind the stage buffers: [4][BN] column sums, [WGN][BM] row-sum parts,
     // [BM] checksum parts, 4 control words
-    int32_t* const s_bs = reinterpret_cast<int32_t*>(smem + 2 * (A_STAGE + B_STAGE));
+    int32_t* const s_bs = reinterpret_cast<int32_t*>(smem + S * (A_STAGE + B_STAGE));
     int32_t* const s_rs = s_bs + 4 * BN;
     int32_t* const s_ck = s_rs + WGN * BM;
     int* const s_ctl = s_ck + BM;
@@ -565,14 +597,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     wait_vmem();
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int kStages>
 hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(WGM * WGN * 64);
-    const size_t lds = 2 * (size_t)(BM + BN) * BK + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t);
+    const size_t lds = kStages * (size_t)(BM + BN) * BK + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t) + 32 * 512;
 #define ABFT_LAUNCH(CK, OUT)                                                                              \
     do {                                                                                                  \
-        auto kern = gemm_tile_async_kernel<BM, BN, WGM, WGN, CK, OUT>;                                    \
+        auto kern = gemm_tile_async_kernel<BM, BN, WGM, WGN, kStages, CK, OUT>;                                    \
         static bool attr_set = false;                                                                     \
         if (!attr_set) {                                                                                  \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                       \
