@@ -12,17 +12,21 @@
 //    row) straight into LDS; each lane picks the 16-byte chunk  slot ^ ((row >> 1) & 7)  of
 //    its row, so the 128-byte-pitch LDS image is XOR-swizzled and the MFMA fragment reads
 //    (32 rows x 16 B) spread over all banks.  Packed B is already in fragment order and is
-//    copied 1 KiB per wavefront instruction.  Two stages are resident (2 x (BM+BN) x 128 B);
-//    the loads of stage s+1 are issued at the top of stage s and awaited at its last
-//    quarter, where the single barrier of the stage sits.
+//    copied 1 KiB per wavefront instruction.  kStages stages are resident; their loads are
+//    spread over the k-steps of the stages before them and one barrier per stage publishes
+//    the next stage and releases the oldest.
 //  * A is uint8, the matrix cores are signed x signed: fragments of A are XOR-ed with 0x80
 //    (a - 128) after the LDS read and 128 * (column sum of the streamed B bytes) is added
-//    back in the epilogue: exact modulo 2^32 for whatever B is in memory.
+//    back on the way to memory: exact modulo 2^32 for whatever B is in memory.
 //  * The int32 checksum column S_B enters the same MFMA pipeline as four signed base-256
 //    digit columns (a fifth B operand with 4 live columns); the tile columns of the grid
-//    split its K range (tile column c takes a contiguous share of the stages).  Row sums
-//    minus checksum go per row into the workspace with one returned integer atomic; the
-//    last workgroup to arrive writes flags and count and zeroes the workspace.
+//    split its K range (tile column c takes a contiguous share of the stages).  Row sums are
+//    formed while C is stored; each row's (row sum - checksum) share goes to the row's 64-bit
+//    workspace word with one returned atomic that also counts arrivals, and the tile column
+//    that arrives last writes the row's flag.
+//  * With p.mod127 the same kernel follows Algorithm 1 to the letter: the fifth operand is
+//    rowSum = S_B mod 127 (one live digit column) and the row sums are kept unwrapped and
+//    reduced modulo 127 (Section IV-A-2).
 #pragma once
 #include <type_traits>
 
@@ -34,8 +38,6 @@ namespace atile {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
-#define ABFT_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
-#define ABFT_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 constexpr int kOutC = 1, kOutQ = 2;
 constexpr int BK = 128;  // k-values per stage
