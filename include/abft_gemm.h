@@ -171,6 +171,25 @@ int abft_verify_rows(const int32_t* C, int64_t ldc, int M, int N, const int32_t*
 int abft_row_checksum(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp,
                       int32_t* row_chk, void* stream);
 
+/* What the method does once a row is flagged: recompute it (Section I: on
+ * detection the affected result is recomputed; Section IV keeps the scheme to
+ * detection so that this is the only recovery).  The rows whose flag is set are
+ * gathered from A, multiplied and checked again in passes of at most
+ * max_rows_per_pass rows, and written back into C / Cq; row_flags and err_count
+ * are updated to the verdicts of the recomputation, so a transient fault leaves
+ * them at zero and a fault that persists in memory (in B, say) leaves them set.
+ * UNLIKE EVERY OTHER CALL THIS ONE SYNCHRONISES `stream`: the number of flagged
+ * rows has to reach the host.  rows_before / rows_after (host, may be NULL)
+ * receive the number of flagged rows found and the number still flagged.
+ * scratch: device memory of abft_recover_scratch_bytes(M, max_rows_per_pass, Bp)
+ * bytes, contents irrelevant.  A, lda, rq as for abft_gemm_u8s8s32_checked. */
+size_t abft_recover_scratch_bytes(int M, int max_rows_per_pass, const abft_packed_b* Bp);
+int abft_recompute_flagged_rows(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp,
+                                int32_t* C, int64_t ldc, int32_t* row_flags, int32_t* err_count,
+                                const abft_requant_t* rq, uint8_t* Cq, int64_t ldcq,
+                                int max_rows_per_pass, void* scratch, size_t scratch_bytes, void* stream,
+                                int* rows_before, int* rows_after);
+
 /* Measurement aid, not part of the method: a plain device-to-device copy of
  * `bytes` (a positive multiple of 16; both pointers 16-byte aligned, buffers
  * must not overlap).  It reads and writes exactly `bytes` once, which makes it

@@ -24,7 +24,8 @@ EXPORTS = (
     "abft_packed_b_get_col_offsets",
     "abft_packed_b_flip_bit", "abft_packed_b_flip_checksum_bit", "abft_packed_b_destroy",
     "abft_gemm_workspace_bytes", "abft_workspace_init", "abft_gemm_u8s8s32_checked", "abft_requantize_u8",
-    "abft_verify_rows", "abft_row_checksum", "abft_calib_copy", "abft_last_error",
+    "abft_verify_rows", "abft_row_checksum", "abft_recover_scratch_bytes", "abft_recompute_flagged_rows",
+    "abft_calib_copy", "abft_last_error",
 )
 
 
@@ -67,6 +68,10 @@ def _load() -> ctypes.CDLL:
     L.abft_verify_rows.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
     L.abft_row_checksum.argtypes = [vp, i64, i32, vp, vp, vp]
     L.abft_calib_copy.argtypes = [vp, vp, sz, vp]
+    L.abft_recover_scratch_bytes.argtypes = [i32, i32, vp]
+    L.abft_recover_scratch_bytes.restype = sz
+    L.abft_recompute_flagged_rows.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64,
+                                              i32, vp, sz, vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     return L
 
 
@@ -218,6 +223,27 @@ def abft_verify_rows(C, row_chk, row_flags, err_count=None, stream=None):
 def abft_row_checksum(A, Bp: PackedB, row_chk, stream=None):
     _check(lib.abft_row_checksum(_ptr(A, torch.uint8, "A"), _ld(A, "A"), A.shape[0], Bp.handle,
                                  _ptr(row_chk, torch.int32, "row_chk"), _stream(stream)))
+
+
+def abft_recover_scratch_bytes(M: int, max_rows_per_pass: int, Bp: PackedB) -> int:
+    return int(lib.abft_recover_scratch_bytes(M, max_rows_per_pass, Bp.handle))
+
+
+def abft_recompute_flagged_rows(A, Bp: PackedB, C, row_flags, err_count=None, rq=None, Cq=None, max_rows_per_pass=256,
+                                scratch=None, stream=None):
+    """Recomputes the flagged rows in place (synchronises the stream).  Returns
+    (rows found flagged, rows still flagged after the recomputation)."""
+    M = A.shape[0]
+    if scratch is None:
+        scratch = torch.empty(abft_recover_scratch_bytes(M, max_rows_per_pass, Bp), dtype=torch.uint8, device=A.device)
+    before, after = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib.abft_recompute_flagged_rows(
+        _ptr(A, torch.uint8, "A"), _ld(A, "A"), M, Bp.handle,
+        _ptr(C, torch.int32, "C"), _ld(C, "C") if C is not None else 0,
+        _ptr(row_flags, torch.int32, "row_flags"), _ptr(err_count, torch.int32, "err_count"),
+        ctypes.byref(rq) if rq is not None else None, _ptr(Cq, torch.uint8, "Cq"), _ld(Cq, "Cq") if Cq is not None else 0,
+        max_rows_per_pass, scratch.data_ptr(), scratch.numel(), _stream(stream), ctypes.byref(before), ctypes.byref(after)))
+    return before.value, after.value
 
 
 def abft_calib_copy(src, dst, stream=None):

@@ -267,6 +267,88 @@ int abft_row_checksum(const uint8_t* A, int64_t lda, int M, const abft_packed_b*
     return ABFT_OK;
 }
 
+namespace {
+// layout of the recovery scratch for batches of `rows` rows against Bp
+struct RecoverLayout {
+    size_t idx, count, cnt2, flags2, a2, c2, q2, ws, total;
+    int64_t lda2;
+    size_t ws_bytes;
+};
+RecoverLayout recover_layout(int M, int rows, const abft_packed_b* Bp) {
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    RecoverLayout L;
+    L.lda2 = ((int64_t)Bp->K + 15) / 16 * 16;
+    L.ws_bytes = ws_ints(rows) * sizeof(int32_t);
+    size_t o = 0;
+    L.idx = o; o = up(o + (size_t)M * 4);
+    L.count = o; o = up(o + 4);
+    L.cnt2 = o; o = up(o + 4);
+    L.flags2 = o; o = up(o + (size_t)rows * 4);
+    L.a2 = o; o = up(o + (size_t)rows * L.lda2);
+    L.c2 = o; o = up(o + (size_t)rows * Bp->N * 4);
+    L.q2 = o; o = up(o + (size_t)rows * Bp->N);
+    L.ws = o; o = up(o + L.ws_bytes);
+    L.total = o;
+    return L;
+}
+}  // namespace
+
+size_t abft_recover_scratch_bytes(int M, int max_rows_per_pass, const abft_packed_b* Bp) {
+    if (M < 1 || max_rows_per_pass < 1 || !Bp) return 0;
+    return recover_layout(M, max_rows_per_pass, Bp).total;
+}
+
+int abft_recompute_flagged_rows(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp, int32_t* C, int64_t ldc,
+                                int32_t* row_flags, int32_t* err_count, const abft_requant_t* rq, uint8_t* Cq,
+                                int64_t ldcq, int max_rows_per_pass, void* scratch, size_t scratch_bytes, void* stream,
+                                int* rows_before, int* rows_after) {
+    const char* fn = "abft_recompute_flagged_rows";
+    if (!A || !Bp || !row_flags || !scratch) return fail(ABFT_EINVAL, "%s: null pointer", fn);
+    if (M < 1 || max_rows_per_pass < 1 || lda < Bp->K) return fail(ABFT_EINVAL, "%s: bad shape", fn);
+    if (!C && !rq) return fail(ABFT_EINVAL, "%s: C is NULL and no requantization was asked for", fn);
+    if ((C && ldc < Bp->N) || (rq && (!Cq || ldcq < Bp->N))) return fail(ABFT_EINVAL, "%s: bad output", fn);
+    const RecoverLayout L = recover_layout(M, max_rows_per_pass, Bp);
+    if (scratch_bytes < L.total) return fail(ABFT_EINVAL, "%s: scratch of %zu bytes, %zu needed", fn, scratch_bytes, L.total);
+    hipStream_t s = (hipStream_t)stream;
+    uint8_t* const base = (uint8_t*)scratch;
+    int32_t* const idx = (int32_t*)(base + L.idx);
+    int32_t* const count = (int32_t*)(base + L.count);
+    int32_t* const cnt2 = (int32_t*)(base + L.cnt2);
+    int32_t* const flags2 = (int32_t*)(base + L.flags2);
+    uint8_t* const A2 = base + L.a2;
+    int32_t* const C2 = (int32_t*)(base + L.c2);
+    uint8_t* const Q2 = base + L.q2;
+    HIP_TRY(abft::launch_list_flagged(row_flags, M, idx, count, s));
+    int n = 0;
+    HIP_TRY(hipMemcpyAsync(&n, count, sizeof n, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (rows_before) *rows_before = n;
+    int remaining = 0;
+    if (n > 0) {
+        HIP_TRY(abft::launch_fill_zero((int32_t*)(base + L.ws), L.ws_bytes / 4, s));
+        if (err_count) HIP_TRY(abft::launch_fill_zero(err_count, 1, s));
+        for (int at = 0; at < n; at += max_rows_per_pass) {
+            const int m = n - at < max_rows_per_pass ? n - at : max_rows_per_pass;
+            HIP_TRY(abft::launch_gather_rows(A, lda, idx + at, m, Bp->K, A2, L.lda2, s));
+            const int rc = abft_gemm_u8s8s32_checked(A2, L.lda2, m, Bp, C ? C2 : nullptr, Bp->N, flags2, cnt2, rq,
+                                                     rq ? Q2 : nullptr, Bp->N, nullptr, 0, ABFT_CHECK, base + L.ws,
+                                                     L.ws_bytes, stream);
+            if (rc != ABFT_OK) return rc;
+            HIP_TRY(abft::launch_scatter_rows(C ? C2 : nullptr, rq ? Q2 : nullptr, flags2, idx + at, m, Bp->N, C, ldc,
+                                              rq ? Cq : nullptr, ldcq, row_flags, s));
+            if (err_count) HIP_TRY(abft::launch_add_int(err_count, cnt2, s));
+            if (rows_after) {
+                int c = 0;
+                HIP_TRY(hipMemcpyAsync(&c, cnt2, sizeof c, hipMemcpyDeviceToHost, s));
+                HIP_TRY(hipStreamSynchronize(s));
+                remaining += c;
+            }
+        }
+    }
+    if (rows_after) *rows_after = remaining;
+    return ABFT_OK;
+}
+
 int abft_calib_copy(const void* src, void* dst, size_t bytes, void* stream) {
     const char* fn = "abft_calib_copy";
     if (!src || !dst) return fail(ABFT_EINVAL, "%s: null pointer", fn);

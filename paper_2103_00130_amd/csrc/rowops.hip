@@ -68,7 +68,59 @@ __global__ void calib_copy_kernel(const uint4* __restrict__ src, uint4* __restri
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Recovery helpers: list the flagged rows, gather them, put recomputed rows back.
+__global__ void list_flagged_kernel(const int32_t* __restrict__ flags, int M, int32_t* __restrict__ idx,
+                                    int32_t* __restrict__ count) {
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < M && flags[r] != 0) idx[atomicAdd(count, 1)] = r;   // any order will do
+}
+
+__global__ void gather_rows_kernel(const uint8_t* __restrict__ A, int64_t lda, const int32_t* __restrict__ idx,
+                                   int K, uint8_t* __restrict__ A2, int64_t lda2) {
+    const uint8_t* src = A + (int64_t)idx[blockIdx.x] * lda;
+    uint8_t* dst = A2 + (int64_t)blockIdx.x * lda2;
+    for (int k = threadIdx.x; k < (int)lda2; k += blockDim.x) dst[k] = k < K ? src[k] : (uint8_t)0;
+}
+
+__global__ void scatter_rows_kernel(const int32_t* __restrict__ C2, const uint8_t* __restrict__ Cq2,
+                                    const int32_t* __restrict__ flags2, const int32_t* __restrict__ idx, int N,
+                                    int32_t* __restrict__ C, int64_t ldc, uint8_t* __restrict__ Cq, int64_t ldcq,
+                                    int32_t* __restrict__ flags) {
+    const int r = idx[blockIdx.x];
+    for (int j = threadIdx.x; j < N; j += blockDim.x) {
+        if (C) C[(int64_t)r * ldc + j] = C2[(int64_t)blockIdx.x * N + j];
+        if (Cq) Cq[(int64_t)r * ldcq + j] = Cq2[(int64_t)blockIdx.x * N + j];
+    }
+    if (threadIdx.x == 0) flags[r] = flags2[blockIdx.x];
+}
+
+__global__ void add_int_kernel(int32_t* dst, const int32_t* src) { *dst += *src; }
+
 }  // namespace
+
+hipError_t launch_list_flagged(const int32_t* flags, int M, int32_t* idx, int32_t* count, hipStream_t s) {
+    hipError_t e = launch_fill_zero(count, 1, s);
+    if (e != hipSuccess) return e;
+    list_flagged_kernel<<<dim3((unsigned)((M + 255) / 256)), dim3(256), 0, s>>>(flags, M, idx, count);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const uint8_t* A, int64_t lda, const int32_t* idx, int n, int K, uint8_t* A2,
+                              int64_t lda2, hipStream_t s) {
+    gather_rows_kernel<<<dim3((unsigned)n), dim3(256), 0, s>>>(A, lda, idx, K, A2, lda2);
+    return hipGetLastError();
+}
+
+hipError_t launch_scatter_rows(const int32_t* C2, const uint8_t* Cq2, const int32_t* flags2, const int32_t* idx, int n,
+                               int N, int32_t* C, int64_t ldc, uint8_t* Cq, int64_t ldcq, int32_t* flags, hipStream_t s) {
+    scatter_rows_kernel<<<dim3((unsigned)n), dim3(256), 0, s>>>(C2, Cq2, flags2, idx, N, C, ldc, Cq, ldcq, flags);
+    return hipGetLastError();
+}
+
+hipError_t launch_add_int(int32_t* dst, const int32_t* src, hipStream_t s) {
+    add_int_kernel<<<dim3(1), dim3(1), 0, s>>>(dst, src);
+    return hipGetLastError();
+}
 
 hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
     const size_t n16 = bytes / 16;

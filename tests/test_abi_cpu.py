@@ -47,6 +47,9 @@ def test_bad_arguments_are_rejected_on_the_host(binding):
     assert L.abft_verify_rows(None, 0, 1, 1, None, None, None, None) == binding.ABFT_EINVAL
     assert L.abft_requantize_u8(None, 0, 1, 1, None, None, None, 0, None) == binding.ABFT_EINVAL
     assert L.abft_row_checksum(None, 0, 1, None, None, None) == binding.ABFT_EINVAL
+    assert L.abft_recover_scratch_bytes(0, 1, None) == 0
+    assert L.abft_recompute_flagged_rows(None, 0, 1, None, None, 0, None, None, None, None, 0, 1, None, 0, None, None,
+                                         None) == binding.ABFT_EINVAL
     assert L.abft_calib_copy(None, None, 16, None) == binding.ABFT_EINVAL
     assert L.abft_calib_copy(4096, 8192, 24, None) == binding.ABFT_EINVAL      # not a multiple of 16
     assert L.abft_calib_copy(4096, 8200, 32, None) == binding.ABFT_EINVAL      # misaligned

@@ -452,3 +452,46 @@ def test_mod127_full_size_and_refusals(binding, gpu_util, oracle):
     buf = torch.zeros(16 * 64 + 1, dtype=torch.uint8, device="cuda")
     with pytest.raises(binding.AbftError):
         small.gemm(buf[1:].view(16, 64), mod127=True)
+
+
+# ---- recovery: recompute the flagged rows ---------------------------------------------------
+
+@pytest.mark.gpu
+def test_recompute_flagged_rows(binding, gpu_util, oracle):
+    import torch
+    b = binding
+    M, N, K = 300, 520, 384
+    say(f"recovery {M}x{N}x{K}")
+    A, B = operands(M, N, K, 43)
+    clean = oracle.checked_gemm(A, B)
+    run = gpu_util.GpuRun(b, B)
+    A_dev = gpu_util.dev(A)
+    mult = gpu_util.dev(np.full(N, 2e-4, np.float32))
+    rq = b.make_requant(128, 128, mult)
+    want_q = oracle.requantize(clean.C, clean.colsum, 128, 128, np.full(N, 2e-4, np.float32), precision="f32")
+    C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    Cq = torch.empty((M, N), dtype=torch.uint8, device="cuda")
+    flags = torch.empty(M, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+    ws = b.Workspace(M, run.Bp)
+    # transient faults in the 32-bit intermediate: five rows flagged, all five recovered
+    inj = [(0, 0, 1 << 31), (17, 300, 1 << 3), (17, 301, 1 << 9), (128, 519, 0x00FF0000), (255, 256, 1), (299, 1, 1 << 20)]
+    b.abft_gemm_u8s8s32_checked(A_dev, run.Bp, C, flags, cnt, rq=rq, Cq=Cq, inj=b.make_injections(inj), n_inj=len(inj),
+                                workspace=ws.tensor)
+    assert int(cnt.item()) == 5 and not np.array_equal(C.cpu().numpy(), clean.C)
+    before, after = b.abft_recompute_flagged_rows(A_dev, run.Bp, C, flags, cnt, rq=rq, Cq=Cq, max_rows_per_pass=2)
+    assert (before, after) == (5, 0) and int(cnt.item()) == 0 and not flags.any().item()
+    assert np.array_equal(C.cpu().numpy(), clean.C) and np.array_equal(Cq.cpu().numpy(), want_q)
+    before, after = b.abft_recompute_flagged_rows(A_dev, run.Bp, C, flags, cnt)       # nothing to do
+    assert (before, after) == (0, 0) and np.array_equal(C.cpu().numpy(), clean.C)
+    # a fault that sits in the weight is still there when the rows are recomputed: flags stay
+    b.abft_packed_b_flip_bit(run.Bp, 100, 200, 6)
+    bad = oracle.checked_gemm(A, B, flips_b=[(100, 200, 6)])
+    b.abft_gemm_u8s8s32_checked(A_dev, run.Bp, C, flags, cnt, workspace=ws.tensor)
+    assert np.array_equal(flags.cpu().numpy(), bad.flags) and bad.err_count > 200
+    before, after = b.abft_recompute_flagged_rows(A_dev, run.Bp, C, flags, cnt, max_rows_per_pass=64)   # several passes
+    assert before == after == bad.err_count == int(cnt.item())
+    assert np.array_equal(flags.cpu().numpy(), bad.flags) and np.array_equal(C.cpu().numpy(), bad.C)
+    b.abft_packed_b_flip_bit(run.Bp, 100, 200, 6)                     # repair the weight: now recovery succeeds
+    before, after = b.abft_recompute_flagged_rows(A_dev, run.Bp, C, flags, cnt, max_rows_per_pass=64)
+    assert (before, after) == (bad.err_count, 0) and np.array_equal(C.cpu().numpy(), clean.C)
