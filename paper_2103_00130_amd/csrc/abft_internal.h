@@ -63,6 +63,21 @@ struct RequantDev {
     const int32_t* bias;
 };
 
+#ifdef __HIPCC__
+// Requantization of one 32-bit value (Section III-B with the rank-1 correction of Eq. 1 for a
+// symmetric B): t = v - zA * colsum (+ bias) in wrap-around int32, one binary32 multiply, round
+// to nearest even, + zC, clamp to [0, 255].  The one place this arithmetic is written down.
+__device__ inline uint8_t requant_one(int32_t v, int32_t cs, int col, const RequantDev& rq) {
+    uint32_t t = (uint32_t)v - (uint32_t)rq.zA * (uint32_t)cs;
+    if (rq.bias) t += (uint32_t)rq.bias[col];
+    const float m = rq.mult[rq.per_channel ? col : 0];
+    const float p = __fmul_rn((float)(int32_t)t, m);
+    float y = __builtin_rintf(p) + (float)rq.zC;
+    y = fminf(fmaxf(y, 0.0f), 255.0f);
+    return (uint8_t)y;
+}
+#endif
+
 struct GemmParams {
     const uint8_t* A;
     int64_t lda;

@@ -25,16 +25,6 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kOutC = 1, kOutQ = 2;
 
-__device__ inline uint8_t requant_one(int32_t v, int32_t cs, int col, const RequantDev& rq) {
-    uint32_t t = (uint32_t)v - (uint32_t)rq.zA * (uint32_t)cs;
-    if (rq.bias) t += (uint32_t)rq.bias[col];
-    const float m = rq.mult[rq.per_channel ? col : 0];
-    const float p = __fmul_rn((float)(int32_t)t, m);
-    float y = __builtin_rintf(p) + (float)rq.zC;
-    y = fminf(fmaxf(y, 0.0f), 255.0f);
-    return (uint8_t)y;
-}
-
 // sum over the 16 lanes of a DPP row; every lane of the row ends up with the total
 __device__ inline uint32_t row_sum16(uint32_t s) {
     s += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)s, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]

@@ -42,16 +42,6 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int kOutC = 1, kOutQ = 2;
 constexpr int BK = 128;  // k-values per stage
 
-__device__ inline uint8_t requant_one(int32_t v, int32_t cs, int col, const RequantDev& rq) {
-    uint32_t t = (uint32_t)v - (uint32_t)rq.zA * (uint32_t)cs;
-    if (rq.bias) t += (uint32_t)rq.bias[col];
-    const float m = rq.mult[rq.per_channel ? col : 0];
-    const float p = __fmul_rn((float)(int32_t)t, m);
-    float y = __builtin_rintf(p) + (float)rq.zC;
-    y = fminf(fmaxf(y, 0.0f), 255.0f);
-    return (uint8_t)y;
-}
-
 // sum over the 32 lanes that share lane>>5: DPP adds inside rows of 16 lanes, then one
 // v_permlane16_swap (rows 0<->1 and 2<->3 change places) for the last step; all VALU
 __device__ inline uint32_t sum32(uint32_t s) {

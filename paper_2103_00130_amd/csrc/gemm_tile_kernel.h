@@ -46,16 +46,6 @@ __device__ inline int a_lds_off(int r, int kg) {
     return (r >> 5) * 2048 + (kg * 32 + ((r + 4 * kg) & 31)) * 16;
 }
 
-__device__ inline uint8_t requant_one(int32_t v, int32_t cs, int col, const RequantDev& rq) {
-    uint32_t t = (uint32_t)v - (uint32_t)rq.zA * (uint32_t)cs;
-    if (rq.bias) t += (uint32_t)rq.bias[col];
-    const float m = rq.mult[rq.per_channel ? col : 0];
-    const float p = __fmul_rn((float)(int32_t)t, m);
-    float y = __builtin_rintf(p) + (float)rq.zC;
-    y = fminf(fmaxf(y, 0.0f), 255.0f);
-    return (uint8_t)y;
-}
-
 // This is the general path: A may have any alignment, leading dimension and K; its
 // chunks are assembled byte by byte.  Aligned problems take the kernel of
 // gemm_tile_async.h instead.

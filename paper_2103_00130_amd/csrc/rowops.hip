@@ -20,13 +20,7 @@ __global__ void requantize_kernel(const int32_t* __restrict__ C, int64_t ldc, in
     const int n = min(4, N - j0);
     for (int e = 0; e < n; ++e) {
         const int col = j0 + e;
-        uint32_t t = (uint32_t)C[(int64_t)row * ldc + col] - (uint32_t)rq.zA * (uint32_t)colsum[col];
-        if (rq.bias) t += (uint32_t)rq.bias[col];
-        const float m = rq.mult[rq.per_channel ? col : 0];
-        const float p = __fmul_rn((float)(int32_t)t, m);
-        float y = __builtin_rintf(p) + (float)rq.zC;
-        y = fminf(fmaxf(y, 0.0f), 255.0f);
-        Cq[(int64_t)row * ldcq + col] = (uint8_t)y;
+        Cq[(int64_t)row * ldcq + col] = requant_one(C[(int64_t)row * ldc + col], colsum[col], col, rq);
     }
 }
 
