@@ -495,3 +495,43 @@ def test_recompute_flagged_rows(binding, gpu_util, oracle):
     b.abft_packed_b_flip_bit(run.Bp, 100, 200, 6)                     # repair the weight: now recovery succeeds
     before, after = b.abft_recompute_flagged_rows(A_dev, run.Bp, C, flags, cnt, max_rows_per_pass=64)
     assert (before, after) == (bad.err_count, 0) and np.array_equal(C.cpu().numpy(), clean.C)
+
+
+@pytest.mark.gpu
+def test_seeded_sweep_of_shapes_variants_and_faults(binding, gpu_util, oracle):
+    """120 seeded cases: ragged and tiny shapes, every kernel family, aligned and unaligned K, clean and
+    faulty runs, with and without requantization; everything compared with the oracle."""
+    rng = np.random.default_rng(20210300130)
+    n_cases = 120
+    for case in range(n_cases):
+        M = int(rng.choice([1, 2, 15, 16, 17, 33, 64, 65, 100, 129, 255, 256, 257, 300, 513]))
+        N = int(rng.choice([1, 3, 16, 31, 32, 33, 64, 100, 128, 255, 256, 257, 300, 520]))
+        K = int(rng.choice([16, 32, 48, 64, 80, 128, 144, 256, 272, 384, 1, 7, 63, 65, 130, 200]))
+        variant = str(rng.choice(["auto", "tile64", "tile128", "tile256", "tile256w2x4", "tile256w4x2"] + (["smallm"] if M <= 64 else [])))
+        aligned = K % 16 == 0
+        if variant == "smallm" and not aligned:
+            variant = "auto"
+        mod127 = bool(aligned and variant != "smallm" and rng.random() < 0.25)
+        n_inj = int(rng.choice([0, 0, 1, 3]))
+        inj = [(int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(1, 2**32))) for _ in range(n_inj)]
+        with_q = bool(rng.random() < 0.3) and not mod127
+        say(f"sweep {case}: {M}x{N}x{K} {variant} mod127={mod127} inj={n_inj} requant={with_q}")
+        A, B = operands(M, N, K, 1000 + case, relu_like=bool(rng.random() < 0.3), full_range_b=bool(rng.random() < 0.3))
+        run = gpu_util.GpuRun(binding, B)
+        rq = None
+        if with_q:
+            mult = wlmod.draw_mult(rng, N, "channel")
+            bias = rng.integers(-5000, 5000, size=N, dtype=np.int32)
+            rq = (int(rng.choice([0, 128])), 128, mult, bias)
+        out = run.gemm(A, variant=variant, injections=inj, requant=rq, mod127=mod127)
+        if mod127:
+            Cw, fw, nw = oracle.checked_gemm_mod127(A, B, flips_c=inj)
+        else:
+            ref = oracle.checked_gemm(A, B, flips_c=inj)
+            Cw, fw, nw = ref.C, ref.flags, ref.err_count
+        assert np.array_equal(out["C"], Cw), f"case {case}: C"
+        assert np.array_equal(out["flags"], fw) and out["err_count"] == nw, f"case {case}: flags"
+        assert not out["ws"].any(), f"case {case}: workspace not restored"
+        if with_q:
+            want = oracle.requantize(Cw, oracle.b_colsum(B), rq[0], rq[1], rq[2], bias=rq[3], precision="f32")
+            assert np.array_equal(out["Cq"], want), f"case {case}: Cq"
