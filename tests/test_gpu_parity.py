@@ -535,3 +535,18 @@ def test_seeded_sweep_of_shapes_variants_and_faults(binding, gpu_util, oracle):
         if with_q:
             want = oracle.requantize(Cw, oracle.b_colsum(B), rq[0], rq[1], rq[2], bias=rq[3], precision="f32")
             assert np.array_equal(out["Cq"], want), f"case {case}: Cq"
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("M,N,K", [(20000, 384, 160), (513, 9000, 272), (70000, 64, 64)])
+def test_long_and_wide_ragged_shapes(binding, gpu_util, oracle, M, N, K):
+    """Many tile rows or tile columns (several rounds of workgroups per compute unit, hundreds of
+    arrivals per workspace word), ragged in both dimensions."""
+    say(f"long/wide {M}x{N}x{K}")
+    A, B = operands(M, N, K, M + N + K)
+    inj = [(M - 1, N - 1, 1 << 31), (0, 0, 1), (M // 2, N // 2, 0x00100000)]
+    ref = oracle.checked_gemm(A, B, flips_c=inj)
+    run = gpu_util.GpuRun(binding, B)
+    out = run.gemm(A, injections=inj)
+    assert np.array_equal(out["C"], ref.C) and np.array_equal(out["flags"], ref.flags)
+    assert out["err_count"] == ref.err_count == 3 and not out["ws"].any()
