@@ -98,13 +98,52 @@ struct GemmParams {
     RequantDev rq;
     const void* inj;           // abft_inject_t[n_inj]
     int n_inj;
-    int32_t* ws;               // workspace: [0] arrival counter, [16..) per-row differences (tiled: [M]; streaming: [32][64])
+    int32_t* ws;               // workspace: arrival words in the first kWsHeaderInts ints, then the per-row words
 };
 
-constexpr int kWsHeaderInts = 16;
+constexpr int kWsHeaderInts = 64;   // top arrival word, 16 group arrival words, padding
+constexpr int kTicketGroups = 16;
+constexpr int kTicketFlatMax = 128;  // grids up to this size count their arrivals on one word
 // the streaming kernel spreads its per-row sums over kSmallMSlots slots of kSmallMRows rows
 constexpr int kSmallMSlots = 32;
 constexpr int kSmallMRows = 64;
+
+#ifdef __HIPCC__
+// Arrival count of the workgroups of a grid in two levels, so that no workspace word takes more
+// than a few dozen atomics at once (hundreds of returned atomics on one address serialise for
+// microseconds): a workgroup arrives at the word of its group (block id modulo kTicketGroups) with
+// its contribution `mine` in the high half; the last of a group carries the group's sum on to
+// the top word (grids of at most kTicketFlatMax workgroups skip the first level).  True for the one workgroup that completes the top word, *total then holds the
+// sum over the grid; both levels leave their words at zero.  Everything a workgroup did with
+// returned device-scope atomics before it arrives is complete when the last one gets here.
+__device__ inline bool arrive_two_level(int32_t* ws, uint32_t mine, uint32_t n_blocks, uint32_t block, uint32_t* total) {
+    unsigned long long* const top0 = reinterpret_cast<unsigned long long*>(ws);
+    if (n_blocks <= (uint32_t)kTicketFlatMax) {
+        // a small grid arrives at the top word directly: one round trip less
+        const unsigned long long old0 = __hip_atomic_fetch_add(top0, ((unsigned long long)mine << 32) | 1ull, __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)old0 != n_blocks - 1u) return false;
+        *total = (uint32_t)(old0 >> 32) + mine;
+        __hip_atomic_store(top0, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return true;
+    }
+    const uint32_t g = block & (kTicketGroups - 1);
+    const uint32_t n_g = (n_blocks - g + kTicketGroups - 1) / kTicketGroups;
+    const uint32_t n_active = n_blocks < (uint32_t)kTicketGroups ? n_blocks : (uint32_t)kTicketGroups;
+    unsigned long long* const top = reinterpret_cast<unsigned long long*>(ws);
+    unsigned long long* const grp = reinterpret_cast<unsigned long long*>(ws + 16) + g;
+    unsigned long long old = __hip_atomic_fetch_add(grp, ((unsigned long long)mine << 32) | 1ull, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+    if ((uint32_t)old != n_g - 1u) return false;
+    const uint32_t gsum = (uint32_t)(old >> 32) + mine;
+    __hip_atomic_store(grp, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __hip_atomic_fetch_add(top, ((unsigned long long)gsum << 32) | 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((uint32_t)old != n_active - 1u) return false;
+    *total = (uint32_t)(old >> 32) + gsum;
+    __hip_atomic_store(top, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
+}
+#endif
 
 enum Variant { kTile256 = 1, kTile128 = 2, kTile64 = 3, kSmallM = 4, kTile256w24 = 5, kTile256w42 = 6, kVariantEnd = 7 };
 

@@ -210,8 +210,8 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
         if (wave == 0) s_bsum[0][lane] = (uint32_t)atom_old;  // waits for the returned adds
         __syncthreads();
         if (tid == 0) {
-            const int t = __hip_atomic_fetch_add(p.ws, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_ctl[0] = (t == (int)gridDim.x - 1);
+            uint32_t unused = 0;
+            s_ctl[0] = arrive_two_level(p.ws, 0u, gridDim.x, blockIdx.x, &unused);
             s_ctl[1] = 0;
         }
         __syncthreads();
@@ -240,10 +240,7 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
                 if (d != 0) atomicAdd(&s_ctl[1], 1);
             }
             __syncthreads();
-            if (tid == 0) {
-                if (p.err_count) *p.err_count = s_ctl[1];
-                __hip_atomic_store(p.ws, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+            if (tid == 0 && p.err_count) *p.err_count = s_ctl[1];
         }
     }
 }

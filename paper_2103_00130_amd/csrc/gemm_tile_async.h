@@ -568,21 +568,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                 }
             }
         }
-        // errCount: flagged rows are summed inside the workgroup, then one more returned atomic
-        // per workgroup carries them (high half) together with its arrival (low half); every
-        // thread has its row atomics back by then, since it branched on their results.  The
-        // last workgroup to arrive holds the total and clears the word.
+        // errCount: flagged rows are summed inside the workgroup and carried by its arrival (two
+        // levels of returned atomics, see arrive_two_level); every thread has its row atomics back
+        // by then, since it branched on their results.  The last arrival holds the total.
         if (my_err) atomicAdd(&s_ctl[1], my_err);
         __syncthreads();
         if (tid == 0) {
-            unsigned long long* const ws_head = reinterpret_cast<unsigned long long*>(p.ws);
-            const uint32_t mine = (uint32_t)s_ctl[1];
-            const unsigned long long old = __hip_atomic_fetch_add(ws_head, ((unsigned long long)mine << 32) | 1ull, __ATOMIC_RELAXED,
-                                                                  __HIP_MEMORY_SCOPE_AGENT);
-            if ((uint32_t)old == gridDim.x - 1u) {
-                if (p.err_count) *p.err_count = (int32_t)((uint32_t)(old >> 32) + mine);
-                __hip_atomic_store(ws_head, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+            uint32_t total = 0;
+            if (arrive_two_level(p.ws, (uint32_t)s_ctl[1], gridDim.x, blockIdx.x, &total) && p.err_count)
+                *p.err_count = (int32_t)total;
         }
     }
     // direct-to-LDS loads that are still in flight must not outlive the workgroup's LDS

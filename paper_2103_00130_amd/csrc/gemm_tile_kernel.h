@@ -383,8 +383,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_kernel(const GemmPara
         s_bs[tid] = atom_old;
         __syncthreads();
         if (tid == 0) {
-            const int t = __hip_atomic_fetch_add(p.ws, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_ctl[0] = (t == (int)gridDim.x - 1);
+            uint32_t unused = 0;
+            s_ctl[0] = arrive_two_level(p.ws, 0u, gridDim.x, blockIdx.x, &unused);
             s_ctl[1] = 0;
         }
         __syncthreads();
@@ -411,10 +411,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_kernel(const GemmPara
             }
             if (cnt) atomicAdd(&s_ctl[1], cnt);
             __syncthreads();
-            if (tid == 0) {
-                if (p.err_count) *p.err_count = s_ctl[1];
-                __hip_atomic_store(p.ws, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+            if (tid == 0 && p.err_count) *p.err_count = s_ctl[1];
         }
     }
 }
