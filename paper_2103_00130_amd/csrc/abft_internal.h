@@ -103,6 +103,7 @@ struct GemmParams {
 
 constexpr int kWsHeaderInts = 64;   // top arrival word, 16 group arrival words, padding
 constexpr int kTicketGroups = 16;
+constexpr int kWsDoneWord = 48;     // int offset of the streaming kernel's finished-rows word inside the header
 constexpr int kTicketFlatMax = 128;  // grids up to this size count their arrivals on one word
 // the streaming kernel spreads its per-row sums over kSmallMSlots slots of kSmallMRows rows
 constexpr int kSmallMSlots = 32;

@@ -44,7 +44,8 @@ void free_handle(abft_packed_b* h) {
 
 size_t ws_ints(int M) {
     const size_t rows = 2 * ((((size_t)M + 63) / 64) * 64);  // one 64-bit word per row
-    const size_t streaming = (size_t)abft::kSmallMSlots * abft::kSmallMRows;
+    // streaming kernel: one 64-bit word per (slot, row) and one per row
+    const size_t streaming = 2 * ((size_t)abft::kSmallMSlots * abft::kSmallMRows + abft::kSmallMRows);
     return (size_t)abft::kWsHeaderInts + (rows > streaming ? rows : streaming);
 }
 

@@ -13,9 +13,11 @@
 //    back; the checksum column S_B rides as four base-256 digit columns on a second MFMA; the
 //    column blocks split its K range between them.
 //  * The four partial accumulators meet in LDS; wavefront 0 adds them, forms the row sums with
-//    DPP row reductions, and adds (row sum - checksum) per row into one of 32 workspace slots
-//    (returned integer atomics, at most a handful of workgroups per address).  The last
-//    workgroup to arrive sums the slots, writes flags and count, and zeroes the workspace.
+//    DPP row reductions, stores C, and then adds (row sum - checksum) per row into 64-bit
+//    workspace words that also count arrivals (returned integer atomics, a few dozen arrivals
+//    per word at most): whoever completes a row's word writes its flag, whoever completes the
+//    count of finished rows writes errCount, and each clears what it completed.  No workgroup
+//    waits for another and there is no closing pass.
 #include "../../include/abft_gemm.h"
 #include "abft_internal.h"
 
@@ -43,7 +45,6 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
     __shared__ v4i s_chk[3][RB][64];
     __shared__ uint32_t s_bsum[3][64];
     __shared__ uint32_t s_d[64];
-    __shared__ int s_ctl[2];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int cb = blockIdx.x, col0 = cb * 16;
@@ -127,7 +128,6 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
         s_bsum[wave - 1][lane] = bsum;
     }
     __syncthreads();
-    int32_t atom_old = 0;
     if (wave == 0) {
 #pragma unroll
         for (int w = 0; w < 3; ++w) {
@@ -166,6 +166,18 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
             }
         }
 
+        // stores first (they need no answer), then the check, whose atomics wait for theirs;
+        // per (rb, e) one store instruction covers 4 rows x 16 columns
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int row = rb * 16 + 4 * lkg + e, col = col0 + lcol;
+                if (row < p.M && col < p.N) {
+                    if (kWantC) p.C[(int64_t)row * p.ldc + col] = acc[rb][e];
+                    if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_one(acc[rb][e], p.colsum[col], col, p.rq);
+                }
+            }
         if (kCheck) {
             const int slot = cb & (kSmallMSlots - 1);
             const uint32_t total128 = cb == 0 ? 128u * (uint32_t)(*p.total) : 0u;  // sum_k 128*S_B[k], once per row
@@ -180,67 +192,55 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
                     const int row = rb * 16 + 4 * lkg + e;
                     if (lcol == 0) s_d[row] = rs - ck - total128;
                 }
-            // one row per lane, so that all returned atomics of the workgroup are in flight together.
-            // fetch-add WITH return: the add has been performed at device scope once the old
-            // value is back, which is what the arrival counter relies on
+            // One row per lane.  The row's difference climbs workspace words, each a 64-bit
+            // (value << 32 | arrivals) taken with one returned atomic.  With more than 32 column
+            // blocks the first word is that of (slot, row), shared by the blocks of one slot, whose
+            // last arrival carries the slot's sum on; the next is the word of the row, where the last
+            // arrival has the complete difference and writes the flag.  The rows a wavefront finishes
+            // are counted with one atomic on the word of finished rows, whose last arrival writes
+            // errCount.  Every word is cleared by the arrival that completes it.  No word sees more
+            // than a few dozen arrivals, and nobody waits for anybody.
+            bool fin = false, bad = false;
             if (lane < 16 * RB && lane < p.M) {
-                const uint32_t d = s_d[lane];
-                if (d != 0)
-                    atom_old = __hip_atomic_fetch_add(p.ws + kWsHeaderInts + slot * kSmallMRows + lane, (int)d,
-                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-
-        // stores: per (rb, e) one instruction covers 4 rows x 16 columns
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int row = rb * 16 + 4 * lkg + e, col = col0 + lcol;
-                if (row < p.M && col < p.N) {
-                    if (kWantC) p.C[(int64_t)row * p.ldc + col] = acc[rb][e];
-                    if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_one(acc[rb][e], p.colsum[col], col, p.rq);
+                unsigned long long* const w_slot =
+                    reinterpret_cast<unsigned long long*>(p.ws + kWsHeaderInts) + slot * kSmallMRows + lane;
+                unsigned long long* const w_row =
+                    reinterpret_cast<unsigned long long*>(p.ws + kWsHeaderInts) + kSmallMSlots * kSmallMRows + lane;
+                uint32_t t = s_d[lane], n_row = (uint32_t)n_blocks;
+                bool go = true;
+                if (n_blocks > kSmallMSlots) {
+                    const uint32_t n_slot = ((uint32_t)n_blocks - (uint32_t)slot + kSmallMSlots - 1) / kSmallMSlots;
+                    const unsigned long long old = __hip_atomic_fetch_add(w_slot, ((unsigned long long)t << 32) | 1ull,
+                                                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    go = (uint32_t)old == n_slot - 1u;
+                    if (go) {
+                        t += (uint32_t)(old >> 32);
+                        __hip_atomic_store(w_slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    n_row = (uint32_t)kSmallMSlots;
+                }
+                if (go) {
+                    const unsigned long long old = __hip_atomic_fetch_add(w_row, ((unsigned long long)t << 32) | 1ull,
+                                                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((uint32_t)old == n_row - 1u) {
+                        bad = ((uint32_t)(old >> 32) + t) != 0u;
+                        __hip_atomic_store(w_row, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        p.row_flags[lane] = (int32_t)bad;
+                        fin = true;
+                    }
                 }
             }
-    }
-
-    if (kCheck) {
-        // arrival count; the last workgroup sums the slots (see the tiled kernel for why no
-        // cache maintenance is needed)
-        if (wave == 0) s_bsum[0][lane] = (uint32_t)atom_old;  // waits for the returned adds
-        __syncthreads();
-        if (tid == 0) {
-            uint32_t unused = 0;
-            s_ctl[0] = arrive_two_level(p.ws, 0u, gridDim.x, blockIdx.x, &unused);
-            s_ctl[1] = 0;
-        }
-        __syncthreads();
-        if (s_ctl[0]) {
-            // thread (row, part): 4 threads per row, each sums 8 of the 32 slots
-            const int row = tid >> 2, part = tid & 3;
-            uint32_t d = 0;
-            if (row < p.M) {
-                int v[kSmallMSlots / 4];
-#pragma unroll
-                for (int u = 0; u < kSmallMSlots / 4; ++u)
-                    v[u] = __hip_atomic_load(p.ws + kWsHeaderInts + (part * (kSmallMSlots / 4) + u) * kSmallMRows + row,
-                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-                for (int u = 0; u < kSmallMSlots / 4; ++u) {
-                    d += (uint32_t)v[u];
-                    if (v[u] != 0)
-                        __hip_atomic_store(p.ws + kWsHeaderInts + (part * (kSmallMSlots / 4) + u) * kSmallMRows + row, 0,
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned long long fin_mask = __ballot(fin), bad_mask = __ballot(fin && bad);
+            if (fin_mask != 0ull && lane == __builtin_ctzll(fin_mask)) {
+                unsigned long long* const w_done = reinterpret_cast<unsigned long long*>(p.ws + kWsDoneWord);
+                const uint32_t n_fin = (uint32_t)__builtin_popcountll(fin_mask), n_bad = (uint32_t)__builtin_popcountll(bad_mask);
+                const unsigned long long old = __hip_atomic_fetch_add(w_done, ((unsigned long long)n_bad << 32) | n_fin,
+                                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((uint32_t)old + n_fin == (uint32_t)p.M) {
+                    if (p.err_count) *p.err_count = (int32_t)((uint32_t)(old >> 32) + n_bad);
+                    __hip_atomic_store(w_done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
-            d += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)d, 0xB1, 0xF, 0xF, true);
-            d += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)d, 0x4E, 0xF, 0xF, true);
-            if (part == 0 && row < p.M) {
-                p.row_flags[row] = d != 0;
-                if (d != 0) atomicAdd(&s_ctl[1], 1);
-            }
-            __syncthreads();
-            if (tid == 0 && p.err_count) *p.err_count = s_ctl[1];
         }
     }
 }

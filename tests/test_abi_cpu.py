@@ -42,7 +42,7 @@ def test_bad_arguments_are_rejected_on_the_host(binding):
     assert L.abft_packed_b_dims(None, None, None) == binding.ABFT_EINVAL
     assert L.abft_workspace_init(None, 64, None) == binding.ABFT_EINVAL
     assert L.abft_gemm_workspace_bytes(0, None) == 0
-    assert L.abft_gemm_workspace_bytes(100, None) == (64 + 2048) * 4
+    assert L.abft_gemm_workspace_bytes(100, None) == (64 + 2 * (32 * 64 + 64)) * 4
     assert L.abft_gemm_workspace_bytes(4096, None) == (64 + 2 * 4096) * 4
     assert L.abft_verify_rows(None, 0, 1, 1, None, None, None, None) == binding.ABFT_EINVAL
     assert L.abft_requantize_u8(None, 0, 1, 1, None, None, None, 0, None) == binding.ABFT_EINVAL
