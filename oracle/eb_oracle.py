@@ -148,7 +148,7 @@ def check(R, rows, scale, bias, C_T, indices, offsets, weights=None, bound: floa
         exact = math.fsum(row)
         slack = 2.0 * d * eps * float(np.abs(row).sum()) + abs(exact - rsum[b])
         gap = abs(abs(exact - csum[b]) - bound * max(abs(exact), abs(csum[b])))
-        robust[b] = gap > slack + bound * slack
+        robust[b] = slack == 0.0 or gap > slack + bound * slack  # (all-zero rows sum to zero in any order)
     return EbCheck(flags, rsum, csum, robust)
 
 

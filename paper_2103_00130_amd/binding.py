@@ -1,4 +1,4 @@
-"""ctypes binding of libabftgemm.so: same names as include/abft_gemm.h.
+"""ctypes binding of libabftgemm.so: same names as include/abft_gemm.h and include/abft_eb.h.
 
 Argument marshalling only.  torch tensors supply device memory and the current
 stream; every step of the method runs in the HIP kernels behind the C ABI.
@@ -27,6 +27,13 @@ EXPORTS = (
     "abft_verify_rows", "abft_row_checksum", "abft_recover_scratch_bytes", "abft_recompute_flagged_rows",
     "abft_calib_copy", "abft_last_error",
 )
+EXPORTS_EB = (
+    "abft_eb_pack_rowsum", "abft_eb_table_dims", "abft_eb_table_get_rowsums", "abft_eb_table_flip_bit",
+    "abft_eb_table_destroy", "abft_eb_u8_checked",
+)
+ABFT_EB_CHECK, ABFT_EB_NOCHECK = 0, 1
+ABFT_EB_VARIANT_BATCH, ABFT_EB_VARIANT_WAVE = 0x100, 0x200
+ABFT_EB_ERR, ABFT_EB_BAD_INDEX = 1, 2
 
 
 class abft_requant_t(ctypes.Structure):
@@ -72,6 +79,13 @@ def _load() -> ctypes.CDLL:
     L.abft_recover_scratch_bytes.restype = sz
     L.abft_recompute_flagged_rows.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64,
                                               i32, vp, sz, vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.abft_eb_pack_rowsum.argtypes = [vp, i64, vp, vp, i64, i32, vp, ctypes.POINTER(vp)]
+    L.abft_eb_table_dims.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.abft_eb_table_get_rowsums.argtypes = [vp, vp, vp]
+    L.abft_eb_table_flip_bit.argtypes = [vp, i64, i32, i32, vp]
+    L.abft_eb_table_destroy.argtypes = [vp]
+    L.abft_eb_table_destroy.restype = None
+    L.abft_eb_u8_checked.argtypes = [vp, vp, i64, vp, i64, vp, vp, i64, vp, vp, vp, ctypes.c_double, u32, vp]
     return L
 
 
@@ -260,3 +274,76 @@ class Workspace:
     def __init__(self, M: int, Bp: PackedB, device="cuda"):
         self.tensor = torch.empty(abft_gemm_workspace_bytes(M, Bp) // 4, dtype=torch.int32, device=device)
         abft_workspace_init(self.tensor)
+
+
+# ---------------------------------------------------------------------------------------------
+# include/abft_eb.h
+
+class EbTable:
+    """Owner of an abft_eb_table handle."""
+
+    def __init__(self, handle: int, rows: int, d: int):
+        self.handle, self.rows, self.d = handle, rows, d
+
+    def destroy(self):
+        if self.handle:
+            torch.cuda.synchronize()
+            lib.abft_eb_table_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def abft_eb_pack_rowsum(T: torch.Tensor, scale: torch.Tensor, bias: torch.Tensor, stream=None) -> EbTable:
+    """T: uint8 device tensor rows x d; scale, bias: float32 [rows]."""
+    ptr = _ptr(T, torch.uint8, "T")
+    ldt = _ld(T, "T")
+    rows, d = T.shape
+    if scale.numel() != rows or bias.numel() != rows or not scale.is_contiguous() or not bias.is_contiguous():
+        raise ValueError("scale and bias must be contiguous with one entry per table row")
+    out = ctypes.c_void_p()
+    _check(lib.abft_eb_pack_rowsum(ptr, ldt, _ptr(scale, torch.float32, "scale"), _ptr(bias, torch.float32, "bias"),
+                                   rows, d, _stream(stream), ctypes.byref(out)))
+    return EbTable(out.value, rows, d)
+
+
+def abft_eb_table_dims(Tp: EbTable):
+    rows, d, rec = ctypes.c_int64(), ctypes.c_int(), ctypes.c_int()
+    _check(lib.abft_eb_table_dims(Tp.handle, ctypes.byref(rows), ctypes.byref(d), ctypes.byref(rec)))
+    return rows.value, d.value, rec.value
+
+
+def abft_eb_table_get_rowsums(Tp: EbTable, C_T: torch.Tensor, stream=None):
+    if C_T.numel() < Tp.rows or not C_T.is_contiguous():
+        raise ValueError("C_T must be contiguous with one entry per table row")
+    _check(lib.abft_eb_table_get_rowsums(Tp.handle, _ptr(C_T, torch.int32, "C_T"), _stream(stream)))
+
+
+def abft_eb_table_flip_bit(Tp: EbTable, row: int, col: int, bit: int, stream=None):
+    _check(lib.abft_eb_table_flip_bit(Tp.handle, int(row), int(col), int(bit), _stream(stream)))
+
+
+def abft_eb_u8_checked(Tp: EbTable, indices: torch.Tensor, offsets: torch.Tensor, R: torch.Tensor,
+                       bag_flags: torch.Tensor | None, weights: torch.Tensor | None = None,
+                       rsum: torch.Tensor | None = None, csum: torch.Tensor | None = None,
+                       rel_bound: float = 1e-5, flags: int = 0, stream=None):
+    """Algorithm 2 for a batch: offsets has one entry more than there are lookups."""
+    n_bags = offsets.numel() - 1
+    if n_bags < 0 or not offsets.is_contiguous() or not indices.is_contiguous():
+        raise ValueError("indices and offsets must be contiguous; offsets needs n_bags + 1 entries")
+    if R.dim() != 2 or R.shape[0] < n_bags or R.shape[1] != Tp.d:
+        raise ValueError("R must be n_bags x d")
+    for name, t in (("bag_flags", bag_flags), ("rsum", rsum), ("csum", csum)):
+        if t is not None and (t.numel() < n_bags or not t.is_contiguous()):
+            raise ValueError(f"{name} must be contiguous with one entry per lookup")
+    if weights is not None and (weights.numel() != indices.numel() or not weights.is_contiguous()):
+        raise ValueError("weights must be contiguous with one entry per index")
+    _check(lib.abft_eb_u8_checked(Tp.handle, _ptr(indices, torch.int64, "indices"), indices.numel(),
+                                  _ptr(offsets, torch.int64, "offsets"), n_bags, _ptr(weights, torch.float32, "weights"),
+                                  _ptr(R, torch.float32, "R"), _ld(R, "R"), _ptr(bag_flags, torch.int32, "bag_flags"),
+                                  _ptr(rsum, torch.float64, "rsum"), _ptr(csum, torch.float64, "csum"),
+                                  float(rel_bound), int(flags), _stream(stream)))

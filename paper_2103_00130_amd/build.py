@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libabftgemm.so")
 SOURCES = ["api.hip", "pack.hip", "gemm_tile.hip", "gemm_tile_a256.hip", "gemm_tile_a256w24.hip", "gemm_tile_a256w42.hip",
            "gemm_tile_a128.hip", "gemm_tile_a64.hip", "gemm_tile_g128.hip", "gemm_tile_g64.hip", "gemm_smallm.hip",
-           "rowops.hip"]
+           "rowops.hip", "eb.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
@@ -24,7 +24,7 @@ FLAGS = [
 def build_library(force: bool = True, verbose: bool = False) -> str:
     build_dir = os.path.join(HERE, "_build")
     os.makedirs(build_dir, exist_ok=True)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", "abft_gemm.h")]
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", h) for h in ("abft_gemm.h", "abft_eb.h")]
     newest = max(os.path.getmtime(d) for d in deps)
     objs = []
     procs = []

@@ -51,6 +51,16 @@ size_t ws_ints(int M) {
 
 }  // namespace
 
+namespace abft {
+int set_error(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+}  // namespace abft
+
 extern "C" {
 
 const char* abft_last_error(void) { return g_err; }

@@ -1,0 +1,457 @@
+// ABFT-checked row-wise quantized EmbeddingBag (include/abft_eb.h): Algorithm 2 of
+// arXiv 2103.00130 (Section V) on the operator of Section III-C.
+//
+// The work is a gather: every pooled row is read once from a table far larger than any
+// cache, so the kernels are built around bytes in flight, not arithmetic.
+//
+//  * The table is kept as fused records [d codes][scale][bias][C_T][unused]: the row sum that
+//    Eq. 4 needs arrives in the same memory transaction as the scale and bias the lookup needs
+//    anyway, so the check adds no memory traffic at all.
+//  * Batch kernel (large batches): d/16 lanes per lookup, every lane owns 16 columns and reads
+//    16 code bytes per pooled row straight into registers, eight rows in flight per lane; the
+//    chip is filled by lookups, and the lanes of a lookup walk its index list in order.
+//  * Wave kernel (small batches): one wavefront per lookup.  All lanes fetch different 16-byte
+//    pieces of the lookup's records into LDS (up to 1024 pieces in flight per wavefront), then
+//    the lanes, now owning columns, walk the staged rows in index order.
+//  Both accumulate every output column in the same order (index order, one fused multiply-add
+//  per row, biases summed apart), so they give the same bits; RSum and CSum are taken in
+//  binary64, CSum in index order.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "../../include/abft_eb.h"
+#include "abft_internal.h"
+
+struct abft_eb_table {
+    uint8_t* rec;   // rows * (d + 16) bytes
+    int64_t rows;
+    int d;
+    int device;
+};
+
+namespace abft {
+namespace {
+
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct EbParams {
+    const uint8_t* tab;
+    int64_t rows;
+    const int64_t* indices;
+    int64_t n_indices;
+    const int64_t* offsets;
+    int64_t n_bags;
+    const float* weights;
+    float* R;
+    int64_t ldr;
+    int32_t* flags;
+    double* rsum;
+    double* csum;
+    double bound;
+};
+
+__device__ inline float as_f32(unsigned int u) { return __builtin_bit_cast(float, u); }
+
+__device__ inline void bag_range(const EbParams& p, int64_t bag, int64_t* beg, int64_t* end) {
+    int64_t b = p.offsets[bag], e = p.offsets[bag + 1];
+    b = b < 0 ? 0 : (b > p.n_indices ? p.n_indices : b);
+    e = e < b ? b : (e > p.n_indices ? p.n_indices : e);
+    *beg = b;
+    *end = e;
+}
+
+// Algorithm 2, the comparison: err unless |RSum - CSum| <= bound * max(|RSum|, |CSum|) and finite
+__device__ inline int compare_sums(double rs, double cs, double bound) {
+    const double diff = fabs(rs - cs);
+    return (!(diff <= bound * fmax(fabs(rs), fabs(cs))) || !(diff < (double)INFINITY)) ? ABFT_EB_ERR : 0;
+}
+
+// 16 columns of one pooled row: acc[k] = a * code[k] + acc[k]
+__device__ inline void fma16(float (&acc)[16], float a, v4u q) {
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        acc[4 * w + 0] = __builtin_fmaf(a, (float)(q[w] & 0xffu), acc[4 * w + 0]);
+        acc[4 * w + 1] = __builtin_fmaf(a, (float)((q[w] >> 8) & 0xffu), acc[4 * w + 1]);
+        acc[4 * w + 2] = __builtin_fmaf(a, (float)((q[w] >> 16) & 0xffu), acc[4 * w + 2]);
+        acc[4 * w + 3] = __builtin_fmaf(a, (float)(q[w] >> 24), acc[4 * w + 3]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Batch kernel: G = d/16 lanes per lookup.
+template <int G, bool kCheck, bool kWeighted>
+__global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
+    constexpr int D = 16 * G, REC = D + 16, U = 8;
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t bag = t / G;
+    const int piece = (int)(t % G);
+    if (bag >= p.n_bags) return;  // whole lane groups leave together (256 is a multiple of G)
+    int64_t beg, end;
+    bag_range(p, bag, &beg, &end);
+
+    float acc[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) acc[k] = 0.0f;
+    float beta_sum = 0.0f;
+    double cs = 0.0;
+    int flag = 0;
+    const uint8_t* const base = p.tab + piece * 16;
+
+    for (int64_t pos = beg; pos < end; pos += U) {
+        int64_t idx[U];
+        bool ok[U];
+        v4u q[U], tl[U];
+        float wv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool in = pos + u < end;
+            idx[u] = in ? p.indices[pos + u] : 0;
+            if (kWeighted) wv[u] = in ? p.weights[pos + u] : 0.0f;
+            ok[u] = in && (uint64_t)idx[u] < (uint64_t)p.rows;
+            if (in && !ok[u]) flag |= ABFT_EB_BAD_INDEX;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            q[u] = tl[u] = v4u{0, 0, 0, 0};
+            if (ok[u]) {
+                const uint8_t* r = base + idx[u] * REC;
+                q[u] = *reinterpret_cast<const v4u*>(r);
+                tl[u] = *reinterpret_cast<const v4u*>(r + (D - piece * 16));
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (ok[u]) {
+                float a = as_f32(tl[u][0]), c = as_f32(tl[u][1]);
+                if (kWeighted) {
+                    a = wv[u] * a;
+                    c = wv[u] * c;
+                }
+                fma16(acc, a, q[u]);
+                beta_sum = beta_sum + c;
+                if (kCheck) {
+                    // Eq. 4, one lookup row: scale * C_T + d * bias (both products are exact in binary64)
+                    cs = fma((double)a, (double)(int32_t)tl[u][2], cs);
+                    cs = fma((double)D, (double)c, cs);
+                }
+            }
+        }
+    }
+
+    float* const out = p.R + bag * p.ldr + piece * 16;
+    double rs = 0.0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        v4f v;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[k] = acc[4 * w + k] + beta_sum;
+            if (kCheck) rs += (double)v[k];
+        }
+        *reinterpret_cast<v4f*>(out + 4 * w) = v;
+    }
+    if (kCheck) {
+#pragma unroll
+        for (int m = 1; m < G; m <<= 1) rs += __shfl_xor(rs, m);
+        if (piece == 0) {
+            p.flags[bag] = flag | compare_sums(rs, cs, p.bound);
+            if (p.rsum) p.rsum[bag] = rs;
+            if (p.csum) p.csum[bag] = cs;
+        }
+    } else if (p.flags && piece == 0) {
+        p.flags[bag] = flag;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Wave kernel: one wavefront per lookup, rows staged through LDS.
+template <int G, bool kCheck, bool kWeighted>
+__global__ __launch_bounds__(64) void eb_wave_kernel(const EbParams p) {
+    constexpr int D = 16 * G, REC = D + 16;
+    constexpr int P = G + 1;                 // 16-byte pieces per record
+    constexpr int NL = 16;                   // load instructions per chunk
+    constexpr int ROWS = (NL * 64) / P;      // whole records per chunk
+    constexpr int CPL = D >= 64 ? D / 64 : 1;  // columns per lane in the pooling phase
+    __shared__ v4u s_rec[NL * 64];
+    __shared__ float s_w[ROWS];
+
+    const int lane = threadIdx.x;
+    const int64_t bag = blockIdx.x;
+    int64_t beg, end;
+    bag_range(p, bag, &beg, &end);
+
+    float acc[CPL];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) acc[k] = 0.0f;
+    float beta_sum = 0.0f;
+    double cs = 0.0;
+    int flag = 0;
+    const bool col_lane = lane * CPL < D;
+    const uint8_t* const s_bytes = reinterpret_cast<const uint8_t*>(s_rec);
+
+    for (int64_t pos = beg; pos < end; pos += ROWS) {
+        const int n = (int)(end - pos < ROWS ? end - pos : ROWS);
+        // fetch: piece g of the chunk's records, g = l*64 + lane, is piece g % P of row g / P
+        int64_t idx[NL];
+#pragma unroll
+        for (int l = 0; l < NL; ++l) {
+            const int r = (l * 64 + lane) / P;
+            idx[l] = r < n ? p.indices[pos + r] : -1;
+        }
+        v4u v[NL];
+#pragma unroll
+        for (int l = 0; l < NL; ++l) {
+            const int g = l * 64 + lane, r = g / P, pc = g - r * P;
+            v[l] = v4u{0, 0, 0, 0};
+            const bool ok = (uint64_t)idx[l] < (uint64_t)p.rows;
+            if (ok) v[l] = *reinterpret_cast<const v4u*>(p.tab + idx[l] * REC + pc * 16);
+            // the last word of a record's tail is unused in memory; staged, it marks a row that is not pooled
+            if (pc == G) v[l][3] = ok ? 0u : 1u;
+        }
+        if (kWeighted)
+            for (int r = lane; r < n; r += 64) s_w[r] = p.weights[pos + r];
+        __syncthreads();  // the previous chunk has been pooled
+#pragma unroll
+        for (int l = 0; l < NL; ++l) s_rec[l * 64 + lane] = v[l];
+        __syncthreads();
+        // pool: rows in index order, lanes own columns lane*CPL .. +CPL-1
+#pragma unroll 4
+        for (int r = 0; r < n; ++r) {
+            const v4u tl = s_rec[r * P + G];
+            if (tl[3] != 0u) {
+                flag |= ABFT_EB_BAD_INDEX;
+                continue;
+            }
+            float a = as_f32(tl[0]), c = as_f32(tl[1]);
+            if (kWeighted) {
+                const float w = s_w[r];
+                a = w * a;
+                c = w * c;
+            }
+            if (col_lane) {
+                const uint8_t* codes = s_bytes + r * REC + lane * CPL;  // aligned to CPL: REC is a multiple of 16
+                unsigned int cw[(CPL + 3) / 4];
+                if (CPL == 1) cw[0] = *codes;
+                else if (CPL == 2) cw[0] = *reinterpret_cast<const uint16_t*>(codes);
+                else
+#pragma unroll
+                    for (int w = 0; w < CPL / 4; ++w) cw[w] = reinterpret_cast<const unsigned int*>(codes)[w];
+#pragma unroll
+                for (int k = 0; k < CPL; ++k) acc[k] = __builtin_fmaf(a, (float)((cw[k / 4] >> (8 * (k % 4))) & 0xffu), acc[k]);
+            }
+            beta_sum = beta_sum + c;
+            if (kCheck) {
+                cs = fma((double)a, (double)(int32_t)tl[2], cs);
+                cs = fma((double)D, (double)c, cs);
+            }
+        }
+    }
+
+    double rs = 0.0;
+    if (col_lane) {
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) {
+            const float v = acc[k] + beta_sum;
+            p.R[bag * p.ldr + lane * CPL + k] = v;
+            if (kCheck) rs += (double)v;
+        }
+    }
+    if (kCheck) {
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) rs += __shfl_xor(rs, m);
+        if (lane == 0) {
+            p.flags[bag] = flag | compare_sums(rs, cs, p.bound);
+            if (p.rsum) p.rsum[bag] = rs;
+            if (p.csum) p.csum[bag] = cs;
+        }
+    } else if (p.flags && lane == 0) {
+        p.flags[bag] = flag;
+    }
+}
+
+template <int G>
+hipError_t launch_g(bool wave, bool check, bool weighted, const EbParams& p, hipStream_t s) {
+#define ABFT_EB_LAUNCH(CK, WT)                                                                         \
+    do {                                                                                               \
+        if (wave) eb_wave_kernel<G, CK, WT><<<dim3((unsigned)p.n_bags), dim3(64), 0, s>>>(p);          \
+        else eb_batch_kernel<G, CK, WT><<<dim3((unsigned)((p.n_bags * G + 255) / 256)), dim3(256), 0, s>>>(p); \
+        return hipGetLastError();                                                                      \
+    } while (0)
+    if (check && weighted) ABFT_EB_LAUNCH(true, true);
+    if (check) ABFT_EB_LAUNCH(true, false);
+    if (weighted) ABFT_EB_LAUNCH(false, true);
+    ABFT_EB_LAUNCH(false, false);
+#undef ABFT_EB_LAUNCH
+}
+
+hipError_t launch_eb(int d, bool wave, bool check, bool weighted, const EbParams& p, hipStream_t s) {
+    switch (d) {
+        case 16: return launch_g<1>(wave, check, weighted, p, s);
+        case 32: return launch_g<2>(wave, check, weighted, p, s);
+        case 64: return launch_g<4>(wave, check, weighted, p, s);
+        case 128: return launch_g<8>(wave, check, weighted, p, s);
+        case 256: return launch_g<16>(wave, check, weighted, p, s);
+        case 512: return launch_g<32>(wave, check, weighted, p, s);
+    }
+    return hipErrorNotSupported;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Table build (Section V: row sums computed once), and the small helpers.
+// One thread per 16-byte piece of a record; the thread of the tail piece sums the row's codes.
+__global__ __launch_bounds__(256) void eb_pack_kernel(const uint8_t* T, int64_t ldt, const float* scale, const float* bias,
+                                                      int64_t rows, int d, uint8_t* rec) {
+    const int P = d / 16 + 1;
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t row = t / P;
+    const int pc = (int)(t - row * P);
+    if (row >= rows) return;
+    const uint8_t* src = T + row * ldt;
+    v4u out;
+    if (pc < P - 1) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            unsigned int x = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) x |= (unsigned int)src[pc * 16 + 4 * w + b] << (8 * b);
+            out[w] = x;
+        }
+    } else {
+        int32_t sum = 0;
+        for (int j = 0; j < d; ++j) sum += src[j];
+        out[0] = __builtin_bit_cast(unsigned int, scale[row]);
+        out[1] = __builtin_bit_cast(unsigned int, bias[row]);
+        out[2] = (unsigned int)sum;
+        out[3] = 0u;
+    }
+    *reinterpret_cast<v4u*>(rec + row * (int64_t)(d + 16) + pc * 16) = out;
+}
+
+__global__ __launch_bounds__(256) void eb_get_rowsums_kernel(const uint8_t* rec, int64_t rows, int d, int32_t* C_T) {
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row < rows) C_T[row] = *reinterpret_cast<const int32_t*>(rec + row * (int64_t)(d + 16) + d + 8);
+}
+
+__global__ void eb_flip_kernel(uint8_t* rec, int64_t off, int bit) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) rec[off] = (uint8_t)(rec[off] ^ (1u << bit));
+}
+
+}  // namespace
+}  // namespace abft
+
+#define HIP_TRY(expr)                                                                        \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess) return abft::set_error(ABFT_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+extern "C" {
+
+int abft_eb_pack_rowsum(const uint8_t* T, int64_t ldt, const float* scale, const float* bias, int64_t rows, int d,
+                        void* stream, abft_eb_table** out) {
+    if (!T || !scale || !bias || !out) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: null pointer");
+    if (rows < 1) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: rows=%lld must be >= 1", (long long)rows);
+    if (d != 16 && d != 32 && d != 64 && d != 128 && d != 256 && d != 512)
+        return abft::set_error(ABFT_EUNSUPPORTED, "abft_eb_pack_rowsum: d=%d (supported: 16, 32, 64, 128, 256, 512)", d);
+    if (ldt < d) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: ldt=%lld smaller than d=%d", (long long)ldt, d);
+    const int64_t pieces = rows * (d / 16 + 1);
+    if ((pieces + 255) / 256 > 0x7fffffffll) return abft::set_error(ABFT_EUNSUPPORTED, "abft_eb_pack_rowsum: table too large");
+    abft_eb_table* h = new (std::nothrow) abft_eb_table();
+    if (!h) return abft::set_error(ABFT_EHIP, "abft_eb_pack_rowsum: out of host memory");
+    std::memset(h, 0, sizeof *h);
+    h->rows = rows;
+    h->d = d;
+    hipError_t e = hipGetDevice(&h->device);
+    if (e == hipSuccess) e = hipMalloc(&h->rec, (size_t)rows * (size_t)(d + 16));
+    if (e == hipSuccess) {
+        abft::eb_pack_kernel<<<dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+            T, ldt, scale, bias, rows, d, h->rec);
+        e = hipGetLastError();
+    }
+    if (e != hipSuccess) {
+        (void)hipFree(h->rec);
+        delete h;
+        return abft::set_error(ABFT_EHIP, "abft_eb_pack_rowsum: %s", hipGetErrorString(e));
+    }
+    *out = h;
+    return ABFT_OK;
+}
+
+int abft_eb_table_dims(const abft_eb_table* Tp, int64_t* rows, int* d, int* record_bytes) {
+    if (!Tp) return abft::set_error(ABFT_EINVAL, "abft_eb_table_dims: null handle");
+    if (rows) *rows = Tp->rows;
+    if (d) *d = Tp->d;
+    if (record_bytes) *record_bytes = Tp->d + 16;
+    return ABFT_OK;
+}
+
+int abft_eb_table_get_rowsums(const abft_eb_table* Tp, int32_t* C_T, void* stream) {
+    if (!Tp || !C_T) return abft::set_error(ABFT_EINVAL, "abft_eb_table_get_rowsums: null pointer");
+    abft::eb_get_rowsums_kernel<<<dim3((unsigned)((Tp->rows + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+        Tp->rec, Tp->rows, Tp->d, C_T);
+    HIP_TRY(hipGetLastError());
+    return ABFT_OK;
+}
+
+int abft_eb_table_flip_bit(abft_eb_table* Tp, int64_t row, int col, int bit, void* stream) {
+    if (!Tp) return abft::set_error(ABFT_EINVAL, "abft_eb_table_flip_bit: null handle");
+    if (row < 0 || row >= Tp->rows || col < 0 || col >= Tp->d || bit < 0 || bit > 7)
+        return abft::set_error(ABFT_EINVAL, "abft_eb_table_flip_bit: row=%lld col=%d bit=%d outside the table", (long long)row, col, bit);
+    abft::eb_flip_kernel<<<dim3(1), dim3(64), 0, (hipStream_t)stream>>>(Tp->rec, row * (int64_t)(Tp->d + 16) + col, bit);
+    HIP_TRY(hipGetLastError());
+    return ABFT_OK;
+}
+
+void abft_eb_table_destroy(abft_eb_table* Tp) {
+    if (!Tp) return;
+    (void)hipFree(Tp->rec);
+    delete Tp;
+}
+
+int abft_eb_u8_checked(const abft_eb_table* Tp, const int64_t* indices, int64_t n_indices, const int64_t* offsets,
+                       int64_t n_bags, const float* weights, float* R, int64_t ldr, int32_t* bag_flags,
+                       double* rsum, double* csum, double rel_bound, unsigned flags, void* stream) {
+    const char* fn = "abft_eb_u8_checked";
+    if (!Tp || !offsets) return abft::set_error(ABFT_EINVAL, "%s: null pointer", fn);
+    if (n_indices < 0 || n_bags < 0) return abft::set_error(ABFT_EINVAL, "%s: negative count", fn);
+    if (n_bags == 0) return ABFT_OK;  // nothing to pool, nothing is written
+    if (!R) return abft::set_error(ABFT_EINVAL, "%s: null pointer", fn);
+    if (n_indices > 0 && !indices) return abft::set_error(ABFT_EINVAL, "%s: null indices", fn);
+    if (flags & ~(ABFT_EB_NOCHECK | ABFT_EB_VARIANT_MASK)) return abft::set_error(ABFT_EINVAL, "%s: unknown flag bits %#x", fn, flags);
+    const bool check = (flags & ABFT_EB_NOCHECK) == 0;
+    if (check && !bag_flags) return abft::set_error(ABFT_EINVAL, "%s: bag_flags is required unless ABFT_EB_NOCHECK", fn);
+    if (check && !(rel_bound >= 0.0)) return abft::set_error(ABFT_EINVAL, "%s: rel_bound must be >= 0", fn);
+    if (ldr < Tp->d || ldr % 4 != 0 || (reinterpret_cast<uintptr_t>(R) & 15) != 0)
+        return abft::set_error(ABFT_EINVAL, "%s: R needs ldr >= d, ldr a multiple of 4 and 16-byte alignment", fn);
+    const unsigned variant = flags & ABFT_EB_VARIANT_MASK;
+    if (variant != 0 && variant != ABFT_EB_VARIANT_BATCH && variant != ABFT_EB_VARIANT_WAVE)
+        return abft::set_error(ABFT_EINVAL, "%s: unknown variant %#x", fn, variant);
+    const int G = Tp->d / 16;
+    if (n_bags > 0x7fffffffll || (n_bags * G + 255) / 256 > 0x7fffffffll)
+        return abft::set_error(ABFT_EUNSUPPORTED, "%s: n_bags=%lld too large for one launch", fn, (long long)n_bags);
+    // the batch kernel needs enough lookups to fill the chip with lanes; below that one wavefront per lookup
+    // keeps more bytes in flight
+    bool wave = n_bags * G < abft::kEbBatchMinLanes;
+    if (variant == ABFT_EB_VARIANT_BATCH) wave = false;
+    if (variant == ABFT_EB_VARIANT_WAVE) wave = true;
+    abft::EbParams p;
+    p.tab = Tp->rec;
+    p.rows = Tp->rows;
+    p.indices = indices;
+    p.n_indices = n_indices;
+    p.offsets = offsets;
+    p.n_bags = n_bags;
+    p.weights = weights;
+    p.R = R;
+    p.ldr = ldr;
+    p.flags = bag_flags;
+    p.rsum = check ? rsum : nullptr;
+    p.csum = check ? csum : nullptr;
+    p.bound = rel_bound;
+    HIP_TRY(abft::launch_eb(Tp->d, wave, check, weights != nullptr, p, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+}  // extern "C"

@@ -15,8 +15,8 @@ def binding():
     return b
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "abft_gemm.h")).read()
+def declared_functions(header="abft_gemm.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(abft_[a-z0-9_]+)\s*\(", text)))
 
@@ -27,6 +27,12 @@ def test_every_declared_symbol_is_exported(binding):
     for n in names:
         assert hasattr(binding.lib, n), f"{n} is declared in include/abft_gemm.h but not exported"
     assert sorted(binding.EXPORTS) == names
+    names_eb = declared_functions("abft_eb.h")
+    assert len(names_eb) >= 6
+    for n in names_eb:
+        assert hasattr(binding.lib, n), f"{n} is declared in include/abft_eb.h but not exported"
+    assert sorted(binding.EXPORTS_EB) == names_eb
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["abft_eb.h", "abft_gemm.h"]
 
 
 def test_bad_arguments_are_rejected_on_the_host(binding):
@@ -53,6 +59,22 @@ def test_bad_arguments_are_rejected_on_the_host(binding):
     assert L.abft_calib_copy(None, None, 16, None) == binding.ABFT_EINVAL
     assert L.abft_calib_copy(4096, 8192, 24, None) == binding.ABFT_EINVAL      # not a multiple of 16
     assert L.abft_calib_copy(4096, 8200, 32, None) == binding.ABFT_EINVAL      # misaligned
+
+
+def test_eb_bad_arguments_are_rejected_on_the_host(binding):
+    L = binding.lib
+    out = ctypes.c_void_p()
+    dummy = ctypes.c_void_p(0x1000)
+    assert L.abft_eb_pack_rowsum(None, 64, dummy, dummy, 10, 64, None, ctypes.byref(out)) == binding.ABFT_EINVAL
+    assert L.abft_eb_pack_rowsum(dummy, 64, dummy, dummy, 0, 64, None, ctypes.byref(out)) == binding.ABFT_EINVAL
+    assert L.abft_eb_pack_rowsum(dummy, 32, dummy, dummy, 10, 64, None, ctypes.byref(out)) == binding.ABFT_EINVAL  # ldt < d
+    assert L.abft_eb_pack_rowsum(dummy, 100, dummy, dummy, 10, 100, None, ctypes.byref(out)) == binding.ABFT_EUNSUPPORTED
+    assert b"d=100" in L.abft_last_error()
+    assert L.abft_eb_table_dims(None, None, None, None) == binding.ABFT_EINVAL
+    assert L.abft_eb_table_get_rowsums(None, dummy, None) == binding.ABFT_EINVAL
+    assert L.abft_eb_table_flip_bit(None, 0, 0, 0, None) == binding.ABFT_EINVAL
+    assert L.abft_eb_u8_checked(None, dummy, 0, dummy, 0, None, dummy, 64, dummy, None, None, 1e-5, 0, None) == binding.ABFT_EINVAL
+    L.abft_eb_table_destroy(None)
 
 
 def test_injection_struct_layout(binding):

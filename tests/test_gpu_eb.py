@@ -1,0 +1,235 @@
+"""GPU parity of the ABFT-checked EmbeddingBag (include/abft_eb.h) against the CPU oracle
+(oracle/eb_oracle.*), through the C ABI.
+
+Bar: the table's row sums and CSum are bit-exact; R is bit-exact against the oracle's float
+evaluation (same stated order) and within the derived round-off tolerance of the oracle's
+double evaluation; RSum agrees to double rounding (the kernels add the same doubles in a tree,
+the oracle in sequence); the flags are equal wherever the oracle says the comparison cannot
+depend on that order, which the tests require to be everywhere for their seeds."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import eb_oracle as eb
+from paper_2103_00130_amd import eb_workloads as w
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = {"auto": 0, "batch": 0x100, "wave": 0x200}
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2103_00130_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+
+
+class GpuTable:
+    def __init__(self, b, T, scale, bias):
+        self.b = b
+        self.Tp = b.abft_eb_pack_rowsum(dev(T), dev(scale), dev(bias))
+        torch.cuda.synchronize()
+
+    def rowsums(self):
+        out = torch.empty(self.Tp.rows, dtype=torch.int32, device="cuda")
+        self.b.abft_eb_table_get_rowsums(self.Tp, out)
+        return out.cpu().numpy()
+
+    def run(self, indices, offsets, weights=None, variant="auto", check=True, bound=1e-5, ldr=None):
+        b, d = self.b, self.Tp.d
+        n_bags = offsets.size - 1
+        ldr = d if ldr is None else ldr
+        Rbuf = torch.full((max(n_bags, 1), ldr), -7.0, dtype=torch.float32, device="cuda")
+        R = Rbuf[:, :d]
+        flags = torch.full((max(n_bags, 1),), -1, dtype=torch.int32, device="cuda")
+        rsum = torch.full((max(n_bags, 1),), -1.0, dtype=torch.float64, device="cuda")
+        csum = torch.full((max(n_bags, 1),), -1.0, dtype=torch.float64, device="cuda")
+        b.abft_eb_u8_checked(self.Tp, dev(indices) if indices.size else torch.empty(0, dtype=torch.int64, device="cuda"),
+                             dev(offsets), R[:n_bags] if n_bags else R[:0], flags, dev(weights), rsum, csum, bound,
+                             VARIANTS[variant] | (0 if check else b.ABFT_EB_NOCHECK))
+        torch.cuda.synchronize()
+        return {"R": R[:n_bags].cpu().numpy(), "flags": flags[:n_bags].cpu().numpy(), "rsum": rsum[:n_bags].cpu().numpy(),
+                "csum": csum[:n_bags].cpu().numpy(), "pad": Rbuf[:, d:].cpu().numpy()}
+
+
+def same_bits(x, y):
+    return np.array_equal(np.ascontiguousarray(x).view(np.uint32), np.ascontiguousarray(y).view(np.uint32))
+
+
+def compare(out, ref, T, scale, bias, indices, offsets, weights, exact_nan=False):
+    assert same_bits(out["R"], ref.R), "R differs from the oracle's float evaluation"
+    assert np.array_equal(out["csum"].view(np.uint64), ref.csum.view(np.uint64)), "CSum differs"
+    fin = np.isfinite(ref.rsum)
+    assert np.allclose(out["rsum"][fin], ref.rsum[fin], rtol=1e-13, atol=0)
+    assert ref.robust.all(), "seed gives a comparison that depends on summation order; pick another"
+    assert np.array_equal(out["flags"], ref.flags)
+    R64 = eb.forward(T, scale, bias, indices, offsets, weights, "f64")
+    tol = eb.roundoff_tolerance(T, scale, bias, indices, offsets, weights)
+    ok = np.isfinite(R64)
+    assert np.all(np.abs(out["R"].astype(np.float64) - R64)[ok] <= (tol[:, None] + np.zeros_like(R64))[ok] + 1e-30)
+
+
+@pytest.mark.parametrize("d", [16, 32, 64, 128, 256, 512])
+@pytest.mark.parametrize("variant", ["batch", "wave"])
+def test_eb_matches_oracle(b, d, variant):
+    for weighted, regime, lengths in ((False, "uniform", "spread"), (True, "gauss", "ragged"), (False, "integer", "ragged")):
+        rng = w.rng_for(100 + d, 0, int(weighted))
+        T, scale, bias = w.draw_table(rng, 3000, d, regime)
+        indices, offsets = w.draw_bags(rng, 3000, 150, 40, lengths)
+        # one lookup long enough to span several staging chunks of the wave kernel at every d
+        extra = rng.integers(0, 3000, size=1300, dtype=np.int64)
+        indices = np.concatenate([indices, extra])
+        offsets = np.concatenate([offsets, [indices.size]]).astype(np.int64)
+        weights = w.draw_weights(rng, indices.size) if weighted else None
+        g = GpuTable(b, T, scale, bias)
+        assert b.abft_eb_table_dims(g.Tp) == (3000, d, d + 16)
+        assert np.array_equal(g.rowsums(), eb.table_rowsums(T))
+        ref = eb.checked_eb(T, scale, bias, indices, offsets, weights)
+        out = g.run(indices, offsets, weights, variant)
+        compare(out, ref, T, scale, bias, indices, offsets, weights)
+        if regime != "gauss":
+            assert not out["flags"].any()
+
+
+def test_variants_agree_and_nocheck_is_the_same_lookup(b):
+    rng = w.rng_for(7)
+    T, scale, bias = w.draw_table(rng, 5000, 64, "gauss")
+    indices, offsets = w.draw_bags(rng, 5000, 700, 30, "ragged")
+    weights = w.draw_weights(rng, indices.size)
+    g = GpuTable(b, T, scale, bias)
+    outs = [g.run(indices, offsets, weights, v, check=c, ldr=72) for v in ("batch", "wave") for c in (True, False)]
+    for o in outs[1:]:
+        assert same_bits(o["R"], outs[0]["R"])
+        assert np.all(o["pad"] == -7.0)          # columns past d are not written
+    assert np.array_equal(outs[0]["flags"], outs[2]["flags"])
+    assert not outs[1]["flags"].any() and not outs[3]["flags"].any()   # no check: only bad indices are reported
+    assert np.all(outs[1]["rsum"] == -1.0)                              # and the diagnostics are left alone
+
+
+def test_bad_indices_empty_batches_and_clamped_offsets(b):
+    rng = w.rng_for(8)
+    T, scale, bias = w.draw_table(rng, 100, 32, "uniform")
+    g = GpuTable(b, T, scale, bias)
+    indices = np.array([5, 100, 7, -3, 9, 2**40, 11, 12], dtype=np.int64)
+    offsets = np.array([0, 2, 2, 5, 8], dtype=np.int64)
+    ref = eb.checked_eb(T, scale, bias, indices, offsets)
+    assert ref.flags.tolist() == [2, 0, 2, 2]
+    for v in ("batch", "wave"):
+        out = g.run(indices, offsets, None, v)
+        assert same_bits(out["R"], ref.R) and np.array_equal(out["flags"], ref.flags)
+        assert np.all(out["R"][1] == 0.0)
+        nc = g.run(indices, offsets, None, v, check=False)
+        assert nc["flags"].tolist() == [2, 0, 2, 2]
+        # offsets beyond the index array are clamped: the last lookup pools what exists
+        wild = np.array([0, 2, 2, 5, 1000], dtype=np.int64)
+        out = g.run(indices, wild, None, v)
+        assert same_bits(out["R"], ref.R)
+        # no lookups at all
+        empty = g.run(np.zeros(0, dtype=np.int64), np.zeros(1, dtype=np.int64), None, v)
+        assert empty["R"].shape == (0, 32)
+        # only empty lookups
+        out = g.run(np.zeros(0, dtype=np.int64), np.zeros(6, dtype=np.int64), None, v)
+        assert np.all(out["R"] == 0.0) and not out["flags"].any()
+    with pytest.raises(b.AbftError):
+        R = torch.empty((4, 32), dtype=torch.float32, device="cuda")
+        b.abft_eb_u8_checked(g.Tp, dev(indices), dev(offsets), R, None)    # flags are required when checking
+    with pytest.raises(b.AbftError):
+        R = torch.empty((4, 33), dtype=torch.float32, device="cuda")[:, :32]  # ldr not a multiple of 4
+        b.abft_eb_u8_checked(g.Tp, dev(indices), dev(offsets), R, torch.empty(4, dtype=torch.int32, device="cuda"))
+
+
+def test_non_finite_parameters_are_reported(b):
+    rng = w.rng_for(9)
+    T, scale, bias = w.draw_table(rng, 200, 64, "uniform")
+    scale[17] = np.inf
+    bias[23] = np.nan
+    indices, offsets = w.draw_bags(rng, 200, 40, 20, "fixed")
+    indices[5], indices[45] = 17, 23      # lookups 0 and 2
+    g = GpuTable(b, T, scale, bias)
+    ref = eb.checked_eb(T, scale, bias, indices, offsets)
+    assert ref.flags[0] == 1 and ref.flags[2] == 1
+    for v in ("batch", "wave"):
+        out = g.run(indices, offsets, None, v)
+        assert np.array_equal(out["flags"], ref.flags)
+        assert np.array_equal(np.isnan(out["R"]), np.isnan(ref.R))
+        ok = ~np.isnan(ref.R)
+        assert np.array_equal(out["R"][ok], ref.R[ok])
+
+
+def test_zero_bound_and_threshold_on_integer_table(b):
+    """Integer table: RSum and CSum are the same integer, so even bound 0 passes a clean lookup;
+    a planted flip is caught or passed exactly as the closed form says."""
+    rng = w.rng_for(10)
+    T, scale, bias = w.draw_table(rng, 400, 64, "integer")
+    indices, offsets = w.draw_bags(rng, 400, 6, 100, "fixed")
+    g = GpuTable(b, T, scale, bias)
+    C_T = eb.table_rowsums(T)
+    for v in ("batch", "wave"):
+        assert not g.run(indices, offsets, None, v, bound=0.0)["flags"].any()
+    bag0 = indices[offsets[0]:offsets[1]]
+    row, col = int(next(i for i in bag0 if (bag0 == i).sum() == 1)), 5   # pooled exactly once by lookup 0
+    for bit in range(8):
+        b.abft_eb_table_flip_bit(g.Tp, row, col, bit)
+        T2 = T.copy()
+        T2[row, col] ^= np.uint8(1 << bit)
+        ref = eb.checked_eb(T2, scale, bias, indices, offsets, C_T=C_T)
+        for v in ("batch", "wave"):
+            out = g.run(indices, offsets, None, v)
+            assert same_bits(out["R"], ref.R) and np.array_equal(out["flags"], ref.flags)
+            assert out["flags"][0] == int(bit >= 4)     # CSum is about 816000: 1e-5 of it lies between 8 and 16
+        b.abft_eb_table_flip_bit(g.Tp, row, col, bit)
+    assert np.array_equal(g.rowsums(), C_T)
+    assert not g.run(indices, offsets, None, "wave")["flags"].any()
+
+
+@pytest.mark.parametrize("regime", ["uniform", "gauss"])
+def test_table_flip_campaign_matches_oracle(b, regime):
+    """Section VI-B-2 at reduced size: 100 flips in the upper and 100 in the lower four bits of
+    pooled table elements, one per launch, plus clean launches; every flag vector equals the oracle's."""
+    wl = w.EbWorkload("campaign", 20000, 64, 10, 100, False, regime)
+    x = w.make_inputs(wl, tag=20)
+    g = GpuTable(b, x.T, x.scale, x.bias)
+    C_T = eb.table_rowsums(x.T)
+    clean = eb.checked_eb(x.T, x.scale, x.bias, x.indices, x.offsets)
+    assert clean.robust.all()
+    assert np.array_equal(g.run(x.indices, x.offsets, None, "auto")["flags"], clean.flags)
+    rates = {}
+    for bits in ("high", "low"):
+        rng = w.rng_for(20, 0, 1 + (bits == "low"))
+        f_row, f_col, f_bit = w.draw_table_flips(rng, x.indices, 64, 100, bits)
+        want = eb.campaign_table_flips(x.T, x.scale, x.bias, C_T, x.indices, x.offsets, None, f_row, f_col, f_bit)
+        got = np.empty_like(want)
+        for t in range(100):
+            b.abft_eb_table_flip_bit(g.Tp, f_row[t], f_col[t], f_bit[t])
+            got[t] = g.run(x.indices, x.offsets, None, "auto")["flags"]
+            b.abft_eb_table_flip_bit(g.Tp, f_row[t], f_col[t], f_bit[t])
+        assert np.array_equal(got, want)
+        rates[bits] = float((got != 0).any(axis=1).mean())
+    print(f"\n[eb campaign, {regime}] detected: high bits {rates['high']:.0%}, low bits {rates['low']:.0%}, "
+          f"false positives {float((clean.flags != 0).mean()):.0%}")
+    assert rates["high"] >= rates["low"]
+    assert np.array_equal(g.rowsums(), C_T)
+
+
+@pytest.mark.parametrize("d", [64, 256])
+def test_table1_shapes_full_size(b, d):
+    """The benchmark's own configurations: 4,000,000 rows, pooling 100, batch 10 (Table I) and
+    the large batch of 16384 lookups, weighted and not, in the variant the library picks."""
+    x = w.make_inputs(w.TABLE1[d], tag=30 + d)
+    g = GpuTable(b, x.T, x.scale, x.bias)
+    C_T = eb.table_rowsums(x.T)
+    sample = np.concatenate([np.arange(0, 4_000_000, 40_009), x.indices[:200]])
+    assert np.array_equal(g.rowsums()[sample], C_T[sample])
+    ref = eb.checked_eb(x.T, x.scale, x.bias, x.indices, x.offsets, C_T=C_T)
+    compare(g.run(x.indices, x.offsets), ref, x.T, x.scale, x.bias, x.indices, x.offsets, None)
+    rng = w.rng_for(30 + d, 1)
+    indices, offsets = w.draw_bags(rng, 4_000_000, 16384 if d == 64 else 4096, 100, "spread")
+    weights = w.draw_weights(rng, indices.size)
+    for wts in (None, weights):
+        ref = eb.checked_eb(x.T, x.scale, x.bias, indices, offsets, wts, C_T=C_T)
+        compare(g.run(indices, offsets, wts), ref, x.T, x.scale, x.bias, indices, offsets, wts)
