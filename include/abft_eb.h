@@ -19,7 +19,8 @@
  *     in index order; the biases of a lookup are summed apart, in index order, and
  *     added to every column at the end.  With weights, scale and bias are first
  *     multiplied by the weight in binary32.
- *   - RSum and CSum are accumulated in binary64 (RSum over the binary32 values of R).
+ *   - RSum and CSum are accumulated in binary64 (RSum over the binary32 values of R; CSum one
+ *     term scale * C_T + d * bias per pooled row, in index order).
  *   - err <=> not (|RSum - CSum| <= rel_bound * max(|RSum|, |CSum|)), or the difference is
  *     not finite.  The paper's choice is rel_bound = 1e-5 (Section V, round-off bound).
  *   - the row sums travel inside the table: a row is one record
@@ -48,7 +49,7 @@ extern "C" {
 #define ABFT_EB_NOCHECK 1u        /* same kernels with RSum, CSum and the comparison compiled out */
 #define ABFT_EB_VARIANT_MASK 0xF00u /* 0 = choose by batch size */
 #define ABFT_EB_VARIANT_BATCH 0x100u  /* a few lanes per lookup, rows straight into registers: large batches */
-#define ABFT_EB_VARIANT_WAVE 0x200u   /* one wavefront per lookup, rows staged in LDS: small batches */
+#define ABFT_EB_VARIANT_GROUP 0x200u  /* one workgroup per lookup, rows staged in LDS: small batches */
 
 /* bits of bag_flags[b] */
 #define ABFT_EB_ERR 1          /* Algorithm 2's err: RSum and CSum differ by more than the bound */

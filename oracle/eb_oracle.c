@@ -23,6 +23,9 @@
  *    alpha and beta are first multiplied by w in float.
  *  - RSum and CSum of Algorithm 2 are accumulated in double (RSum over the float
  *    values of R); the integer row sums enter CSum unscaled, as Section V states.
+ *    CSum adds one term per pooled row, the parenthesised (alpha * C_T + d * beta)
+ *    of Algorithm 2's third step formed first (both products are exact in double,
+ *    so the term is their sum rounded once).
  *  - "relative bound": err <=> not (|RSum - CSum| <= bound * max(|RSum|, |CSum|)), or
  *    |RSum - CSum| not finite, so that a NaN or an infinity on either side reports an error.
  *  - an index outside [0, rows) is not pooled and sets bit 1 (value 2) of the bag's
@@ -92,8 +95,7 @@ void eb_oracle_check(const float* R, int64_t ldr, int64_t rows, int d, const flo
             }
             const float a = w ? w[p] * alpha[i] : alpha[i];
             const float c = w ? w[p] * beta[i] : beta[i];
-            csum += (double)a * (double)C_T[i];
-            csum += (double)d * (double)c;
+            csum += (double)a * (double)C_T[i] + (double)d * (double)c;
         }
         const double diff = fabs(rsum - csum);
         if (!(diff <= bound * fmax(fabs(rsum), fabs(csum))) || !(diff < INFINITY)) flag |= 1;

@@ -32,7 +32,7 @@ EXPORTS_EB = (
     "abft_eb_table_destroy", "abft_eb_u8_checked",
 )
 ABFT_EB_CHECK, ABFT_EB_NOCHECK = 0, 1
-ABFT_EB_VARIANT_BATCH, ABFT_EB_VARIANT_WAVE = 0x100, 0x200
+ABFT_EB_VARIANT_BATCH, ABFT_EB_VARIANT_GROUP = 0x100, 0x200
 ABFT_EB_ERR, ABFT_EB_BAD_INDEX = 1, 2
 
 

@@ -170,7 +170,7 @@ hipError_t launch_row_checksum(const uint8_t* A, int64_t lda, int M, int K, cons
                                int32_t* row_chk, hipStream_t s);
 
 // EmbeddingBag: lanes (lookups x d/16) from which the batch kernel is chosen over the wave kernel
-constexpr int64_t kEbBatchMinLanes = 65536;
+constexpr int64_t kEbBatchMinLanes = 262144;
 
 // records `code` and a message for abft_last_error(); returns `code`
 int set_error(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));

@@ -10,9 +10,9 @@
 //  * Batch kernel (large batches): d/16 lanes per lookup, every lane owns 16 columns and reads
 //    16 code bytes per pooled row straight into registers, eight rows in flight per lane; the
 //    chip is filled by lookups, and the lanes of a lookup walk its index list in order.
-//  * Wave kernel (small batches): one wavefront per lookup.  All lanes fetch different 16-byte
-//    pieces of the lookup's records into LDS (up to 1024 pieces in flight per wavefront), then
-//    the lanes, now owning columns, walk the staged rows in index order.
+//  * Group kernel (small batches): one workgroup per lookup.  All threads fetch different 16-byte
+//    pieces of the lookup's records into LDS (1024 pieces in flight per workgroup), then the
+//    threads, now owning columns, walk the staged rows in index order.
 //  Both accumulate every output column in the same order (index order, one fused multiply-add
 //  per row, biases summed apart), so they give the same bits; RSum and CSum are taken in
 //  binary64, CSum in index order.
@@ -99,6 +99,10 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
     int flag = 0;
     const uint8_t* const base = p.tab + piece * 16;
 
+    // Every load below is unconditional (clamped position, row 0 in place of a bad index): the
+    // eight index loads go out together, then the sixteen row loads, and only then anything waits.
+    // A row that is not pooled enters the sums with scale, bias and row sum 0, which leaves every
+    // accumulator as it is, bit for bit.
     for (int64_t pos = beg; pos < end; pos += U) {
         int64_t idx[U];
         bool ok[U];
@@ -106,36 +110,34 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
         float wv[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
+            const int64_t pp = pos + u < end ? pos + u : end - 1;
+            idx[u] = p.indices[pp];
+            if (kWeighted) wv[u] = p.weights[pp];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
             const bool in = pos + u < end;
-            idx[u] = in ? p.indices[pos + u] : 0;
-            if (kWeighted) wv[u] = in ? p.weights[pos + u] : 0.0f;
             ok[u] = in && (uint64_t)idx[u] < (uint64_t)p.rows;
             if (in && !ok[u]) flag |= ABFT_EB_BAD_INDEX;
+            const uint8_t* r = base + (ok[u] ? idx[u] : 0) * REC;
+            q[u] = *reinterpret_cast<const v4u*>(r);
+            tl[u] = *reinterpret_cast<const v4u*>(r + (D - piece * 16));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            q[u] = tl[u] = v4u{0, 0, 0, 0};
-            if (ok[u]) {
-                const uint8_t* r = base + idx[u] * REC;
-                q[u] = *reinterpret_cast<const v4u*>(r);
-                tl[u] = *reinterpret_cast<const v4u*>(r + (D - piece * 16));
+            float a = as_f32(tl[u][0]), c = as_f32(tl[u][1]);
+            if (kWeighted) {
+                a = wv[u] * a;
+                c = wv[u] * c;
             }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (ok[u]) {
-                float a = as_f32(tl[u][0]), c = as_f32(tl[u][1]);
-                if (kWeighted) {
-                    a = wv[u] * a;
-                    c = wv[u] * c;
-                }
-                fma16(acc, a, q[u]);
-                beta_sum = beta_sum + c;
-                if (kCheck) {
-                    // Eq. 4, one lookup row: scale * C_T + d * bias (both products are exact in binary64)
-                    cs = fma((double)a, (double)(int32_t)tl[u][2], cs);
-                    cs = fma((double)D, (double)c, cs);
-                }
+            a = ok[u] ? a : 0.0f;
+            c = ok[u] ? c : 0.0f;
+            fma16(acc, a, q[u]);
+            beta_sum = beta_sum + c;
+            if (kCheck) {
+                // Eq. 4, the term of one pooled row: scale * C_T + d * bias, rounded once (both products
+                // are exact in binary64), then added to the running sum
+                cs = cs + fma((double)a, (double)(ok[u] ? (int32_t)tl[u][2] : 0), (double)D * (double)c);
             }
         }
     }
@@ -166,18 +168,31 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Wave kernel: one wavefront per lookup, rows staged through LDS.
+// Group kernel: one workgroup (four wavefronts) per lookup, rows staged through LDS.
+//  1. fetch: every thread loads different 16-byte pieces of the chunk's records (1024 pieces in
+//     flight per workgroup) and they are laid out in LDS record after record;
+//  2. per-row scalars, rows in parallel: the weighted scale and bias of every staged row, and
+//     the two exact binary64 products of its Eq. 4 term;
+//  3. pooling, rows in index order: threads own columns and do one LDS read, one convert and one
+//     fused multiply-add per row; meanwhile the last two wavefronts walk the chains that do not
+//     depend on the column (sum of biases, CSum).
 template <int G, bool kCheck, bool kWeighted>
-__global__ __launch_bounds__(64) void eb_wave_kernel(const EbParams p) {
+__global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
     constexpr int D = 16 * G, REC = D + 16;
-    constexpr int P = G + 1;                 // 16-byte pieces per record
-    constexpr int NL = 16;                   // load instructions per chunk
-    constexpr int ROWS = (NL * 64) / P;      // whole records per chunk
-    constexpr int CPL = D >= 64 ? D / 64 : 1;  // columns per lane in the pooling phase
-    __shared__ v4u s_rec[NL * 64];
-    __shared__ float s_w[ROWS];
+    constexpr int P = G + 1;                   // 16-byte pieces per record
+    constexpr int NL = G >= 16 ? 8 : 4;        // load instructions per thread and chunk
+    constexpr int PIECES = NL * 256;
+    constexpr int ROWS = PIECES / P;           // whole records per chunk
+    constexpr int NW = (ROWS + 255) / 256;     // rows per thread in the per-row pass
+    constexpr int CPL = D > 256 ? D / 256 : 1;  // columns per thread in the pooling phase
+    __shared__ v4u s_rec[PIECES];
+    __shared__ float s_a[ROWS], s_c[ROWS];
+    __shared__ double s_t[kCheck ? ROWS : 1];
+    __shared__ double s_rs[4], s_cs;
+    __shared__ float s_beta;
+    __shared__ int s_flag;
 
-    const int lane = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t bag = blockIdx.x;
     int64_t beg, end;
     bag_range(p, bag, &beg, &end);
@@ -187,95 +202,120 @@ __global__ __launch_bounds__(64) void eb_wave_kernel(const EbParams p) {
     for (int k = 0; k < CPL; ++k) acc[k] = 0.0f;
     float beta_sum = 0.0f;
     double cs = 0.0;
-    int flag = 0;
-    const bool col_lane = lane * CPL < D;
+    const bool col_thread = tid * CPL < D;
+    // the chains that do not depend on the column run on wavefronts that own few or no columns
+    const bool beta_wave = wave == 2, cs_wave = wave == 3;
     const uint8_t* const s_bytes = reinterpret_cast<const uint8_t*>(s_rec);
+    if (tid == 0) s_flag = 0;
 
     for (int64_t pos = beg; pos < end; pos += ROWS) {
         const int n = (int)(end - pos < ROWS ? end - pos : ROWS);
-        // fetch: piece g of the chunk's records, g = l*64 + lane, is piece g % P of row g / P
+        // fetch: piece g = l*256 + tid of the chunk is piece g % P of row g / P.  All loads are
+        // unconditional (clamped row, row 0 in place of a bad index) so that they all go out together.
         int64_t idx[NL];
 #pragma unroll
         for (int l = 0; l < NL; ++l) {
-            const int r = (l * 64 + lane) / P;
-            idx[l] = r < n ? p.indices[pos + r] : -1;
+            const int r = (l * 256 + tid) / P;
+            idx[l] = p.indices[pos + (r < n ? r : n - 1)];
         }
+        float wreg[NW];
+        if (kWeighted)
+#pragma unroll
+            for (int k = 0; k < NW; ++k) wreg[k] = p.weights[pos + (tid + 256 * k < n ? tid + 256 * k : n - 1)];
         v4u v[NL];
 #pragma unroll
         for (int l = 0; l < NL; ++l) {
-            const int g = l * 64 + lane, r = g / P, pc = g - r * P;
-            v[l] = v4u{0, 0, 0, 0};
+            const int g = l * 256 + tid, r = g / P, pc = g - r * P;
             const bool ok = (uint64_t)idx[l] < (uint64_t)p.rows;
-            if (ok) v[l] = *reinterpret_cast<const v4u*>(p.tab + idx[l] * REC + pc * 16);
+            v[l] = *reinterpret_cast<const v4u*>(p.tab + (ok ? idx[l] : 0) * REC + pc * 16);
             // the last word of a record's tail is unused in memory; staged, it marks a row that is not pooled
             if (pc == G) v[l][3] = ok ? 0u : 1u;
         }
-        if (kWeighted)
-            for (int r = lane; r < n; r += 64) s_w[r] = p.weights[pos + r];
         __syncthreads();  // the previous chunk has been pooled
 #pragma unroll
-        for (int l = 0; l < NL; ++l) s_rec[l * 64 + lane] = v[l];
+        for (int l = 0; l < NL; ++l) s_rec[l * 256 + tid] = v[l];
         __syncthreads();
-        // pool: rows in index order, lanes own columns lane*CPL .. +CPL-1
-#pragma unroll 4
-        for (int r = 0; r < n; ++r) {
-            const v4u tl = s_rec[r * P + G];
-            if (tl[3] != 0u) {
-                flag |= ABFT_EB_BAD_INDEX;
-                continue;
-            }
-            float a = as_f32(tl[0]), c = as_f32(tl[1]);
-            if (kWeighted) {
-                const float w = s_w[r];
-                a = w * a;
-                c = w * c;
-            }
-            if (col_lane) {
-                const uint8_t* codes = s_bytes + r * REC + lane * CPL;  // aligned to CPL: REC is a multiple of 16
-                unsigned int cw[(CPL + 3) / 4];
-                if (CPL == 1) cw[0] = *codes;
-                else if (CPL == 2) cw[0] = *reinterpret_cast<const uint16_t*>(codes);
-                else
+        // per-row scalars.  A row that is not pooled gets scale, bias and row sum 0, which leaves every
+        // accumulator as it is, bit for bit.
+        int bad_any = 0;
 #pragma unroll
-                    for (int w = 0; w < CPL / 4; ++w) cw[w] = reinterpret_cast<const unsigned int*>(codes)[w];
+        for (int k = 0; k < NW; ++k) {
+            const int r = tid + 256 * k;
+            if (r < n) {
+                const v4u tl = s_rec[r * P + G];
+                const bool bad = tl[3] != 0u;
+                bad_any |= bad ? ABFT_EB_BAD_INDEX : 0;
+                float a = as_f32(tl[0]), c = as_f32(tl[1]);
+                if (kWeighted) {
+                    a = wreg[k] * a;
+                    c = wreg[k] * c;
+                }
+                a = bad ? 0.0f : a;
+                c = bad ? 0.0f : c;
+                s_a[r] = a;
+                s_c[r] = c;
+                // Eq. 4, the term of one pooled row: scale * C_T + d * bias, rounded once (both products
+                // are exact in binary64)
+                if (kCheck) s_t[r] = fma((double)a, (double)(bad ? 0 : (int32_t)tl[2]), (double)D * (double)c);
+            }
+        }
+        if (bad_any) atomicOr(&s_flag, bad_any);
+        __syncthreads();
+        // pooling, rows in index order
+        if (col_thread) {
+#pragma unroll 8
+            for (int r = 0; r < n; ++r) {
+                const float a = s_a[r];
+                const uint8_t* codes = s_bytes + r * REC + tid * CPL;
+                unsigned int cw = CPL == 1 ? (unsigned int)*codes : (unsigned int)*reinterpret_cast<const uint16_t*>(codes);
 #pragma unroll
-                for (int k = 0; k < CPL; ++k) acc[k] = __builtin_fmaf(a, (float)((cw[k / 4] >> (8 * (k % 4))) & 0xffu), acc[k]);
+                for (int k = 0; k < CPL; ++k) acc[k] = __builtin_fmaf(a, (float)((cw >> (8 * k)) & 0xffu), acc[k]);
             }
-            beta_sum = beta_sum + c;
-            if (kCheck) {
-                cs = fma((double)a, (double)(int32_t)tl[2], cs);
-                cs = fma((double)D, (double)c, cs);
-            }
+        }
+        if (beta_wave) {
+#pragma unroll 8
+            for (int r = 0; r < n; ++r) beta_sum = beta_sum + s_c[r];
+        }
+        if (kCheck && cs_wave) {
+#pragma unroll 8
+            for (int r = 0; r < n; ++r) cs = cs + s_t[r];
         }
     }
 
+    if (beta_wave && lane == 0) s_beta = beta_sum;
+    if (cs_wave && lane == 0) s_cs = cs;
+    __syncthreads();
+    const float beta = s_beta;
     double rs = 0.0;
-    if (col_lane) {
+    if (col_thread) {
 #pragma unroll
         for (int k = 0; k < CPL; ++k) {
-            const float v = acc[k] + beta_sum;
-            p.R[bag * p.ldr + lane * CPL + k] = v;
+            const float v = acc[k] + beta;
+            p.R[bag * p.ldr + tid * CPL + k] = v;
             if (kCheck) rs += (double)v;
         }
     }
     if (kCheck) {
 #pragma unroll
         for (int m = 1; m < 64; m <<= 1) rs += __shfl_xor(rs, m);
-        if (lane == 0) {
-            p.flags[bag] = flag | compare_sums(rs, cs, p.bound);
-            if (p.rsum) p.rsum[bag] = rs;
-            if (p.csum) p.csum[bag] = cs;
+        if (lane == 0) s_rs[wave] = rs;
+        __syncthreads();
+        if (tid == 0) {
+            const double total = (s_rs[0] + s_rs[1]) + (s_rs[2] + s_rs[3]);
+            p.flags[bag] = s_flag | compare_sums(total, s_cs, p.bound);
+            if (p.rsum) p.rsum[bag] = total;
+            if (p.csum) p.csum[bag] = s_cs;
         }
-    } else if (p.flags && lane == 0) {
-        p.flags[bag] = flag;
+    } else if (p.flags && tid == 0) {
+        p.flags[bag] = s_flag;
     }
 }
 
 template <int G>
-hipError_t launch_g(bool wave, bool check, bool weighted, const EbParams& p, hipStream_t s) {
+hipError_t launch_g(bool group, bool check, bool weighted, const EbParams& p, hipStream_t s) {
 #define ABFT_EB_LAUNCH(CK, WT)                                                                         \
     do {                                                                                               \
-        if (wave) eb_wave_kernel<G, CK, WT><<<dim3((unsigned)p.n_bags), dim3(64), 0, s>>>(p);          \
+        if (group) eb_group_kernel<G, CK, WT><<<dim3((unsigned)p.n_bags), dim3(256), 0, s>>>(p);          \
         else eb_batch_kernel<G, CK, WT><<<dim3((unsigned)((p.n_bags * G + 255) / 256)), dim3(256), 0, s>>>(p); \
         return hipGetLastError();                                                                      \
     } while (0)
@@ -286,14 +326,14 @@ hipError_t launch_g(bool wave, bool check, bool weighted, const EbParams& p, hip
 #undef ABFT_EB_LAUNCH
 }
 
-hipError_t launch_eb(int d, bool wave, bool check, bool weighted, const EbParams& p, hipStream_t s) {
+hipError_t launch_eb(int d, bool group, bool check, bool weighted, const EbParams& p, hipStream_t s) {
     switch (d) {
-        case 16: return launch_g<1>(wave, check, weighted, p, s);
-        case 32: return launch_g<2>(wave, check, weighted, p, s);
-        case 64: return launch_g<4>(wave, check, weighted, p, s);
-        case 128: return launch_g<8>(wave, check, weighted, p, s);
-        case 256: return launch_g<16>(wave, check, weighted, p, s);
-        case 512: return launch_g<32>(wave, check, weighted, p, s);
+        case 16: return launch_g<1>(group, check, weighted, p, s);
+        case 32: return launch_g<2>(group, check, weighted, p, s);
+        case 64: return launch_g<4>(group, check, weighted, p, s);
+        case 128: return launch_g<8>(group, check, weighted, p, s);
+        case 256: return launch_g<16>(group, check, weighted, p, s);
+        case 512: return launch_g<32>(group, check, weighted, p, s);
     }
     return hipErrorNotSupported;
 }
@@ -426,16 +466,16 @@ int abft_eb_u8_checked(const abft_eb_table* Tp, const int64_t* indices, int64_t 
     if (ldr < Tp->d || ldr % 4 != 0 || (reinterpret_cast<uintptr_t>(R) & 15) != 0)
         return abft::set_error(ABFT_EINVAL, "%s: R needs ldr >= d, ldr a multiple of 4 and 16-byte alignment", fn);
     const unsigned variant = flags & ABFT_EB_VARIANT_MASK;
-    if (variant != 0 && variant != ABFT_EB_VARIANT_BATCH && variant != ABFT_EB_VARIANT_WAVE)
+    if (variant != 0 && variant != ABFT_EB_VARIANT_BATCH && variant != ABFT_EB_VARIANT_GROUP)
         return abft::set_error(ABFT_EINVAL, "%s: unknown variant %#x", fn, variant);
     const int G = Tp->d / 16;
     if (n_bags > 0x7fffffffll || (n_bags * G + 255) / 256 > 0x7fffffffll)
         return abft::set_error(ABFT_EUNSUPPORTED, "%s: n_bags=%lld too large for one launch", fn, (long long)n_bags);
     // the batch kernel needs enough lookups to fill the chip with lanes; below that one wavefront per lookup
     // keeps more bytes in flight
-    bool wave = n_bags * G < abft::kEbBatchMinLanes;
-    if (variant == ABFT_EB_VARIANT_BATCH) wave = false;
-    if (variant == ABFT_EB_VARIANT_WAVE) wave = true;
+    bool group = n_bags * G < abft::kEbBatchMinLanes;
+    if (variant == ABFT_EB_VARIANT_BATCH) group = false;
+    if (variant == ABFT_EB_VARIANT_GROUP) group = true;
     abft::EbParams p;
     p.tab = Tp->rec;
     p.rows = Tp->rows;
@@ -450,7 +490,7 @@ int abft_eb_u8_checked(const abft_eb_table* Tp, const int64_t* indices, int64_t 
     p.rsum = check ? rsum : nullptr;
     p.csum = check ? csum : nullptr;
     p.bound = rel_bound;
-    HIP_TRY(abft::launch_eb(Tp->d, wave, check, weights != nullptr, p, (hipStream_t)stream));
+    HIP_TRY(abft::launch_eb(Tp->d, group, check, weights != nullptr, p, (hipStream_t)stream));
     return ABFT_OK;
 }
 

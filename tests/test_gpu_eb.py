@@ -15,7 +15,7 @@ from paper_2103_00130_amd import eb_workloads as w
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = {"auto": 0, "batch": 0x100, "wave": 0x200}
+VARIANTS = {"auto": 0, "batch": 0x100, "group": 0x200}
 
 
 @pytest.fixture(scope="module")
@@ -75,13 +75,13 @@ def compare(out, ref, T, scale, bias, indices, offsets, weights, exact_nan=False
 
 
 @pytest.mark.parametrize("d", [16, 32, 64, 128, 256, 512])
-@pytest.mark.parametrize("variant", ["batch", "wave"])
+@pytest.mark.parametrize("variant", ["batch", "group"])
 def test_eb_matches_oracle(b, d, variant):
     for weighted, regime, lengths in ((False, "uniform", "spread"), (True, "gauss", "ragged"), (False, "integer", "ragged")):
         rng = w.rng_for(100 + d, 0, int(weighted))
         T, scale, bias = w.draw_table(rng, 3000, d, regime)
         indices, offsets = w.draw_bags(rng, 3000, 150, 40, lengths)
-        # one lookup long enough to span several staging chunks of the wave kernel at every d
+        # one lookup long enough to span several staging chunks of the group kernel at every d
         extra = rng.integers(0, 3000, size=1300, dtype=np.int64)
         indices = np.concatenate([indices, extra])
         offsets = np.concatenate([offsets, [indices.size]]).astype(np.int64)
@@ -102,7 +102,7 @@ def test_variants_agree_and_nocheck_is_the_same_lookup(b):
     indices, offsets = w.draw_bags(rng, 5000, 700, 30, "ragged")
     weights = w.draw_weights(rng, indices.size)
     g = GpuTable(b, T, scale, bias)
-    outs = [g.run(indices, offsets, weights, v, check=c, ldr=72) for v in ("batch", "wave") for c in (True, False)]
+    outs = [g.run(indices, offsets, weights, v, check=c, ldr=72) for v in ("batch", "group") for c in (True, False)]
     for o in outs[1:]:
         assert same_bits(o["R"], outs[0]["R"])
         assert np.all(o["pad"] == -7.0)          # columns past d are not written
@@ -119,7 +119,7 @@ def test_bad_indices_empty_batches_and_clamped_offsets(b):
     offsets = np.array([0, 2, 2, 5, 8], dtype=np.int64)
     ref = eb.checked_eb(T, scale, bias, indices, offsets)
     assert ref.flags.tolist() == [2, 0, 2, 2]
-    for v in ("batch", "wave"):
+    for v in ("batch", "group"):
         out = g.run(indices, offsets, None, v)
         assert same_bits(out["R"], ref.R) and np.array_equal(out["flags"], ref.flags)
         assert np.all(out["R"][1] == 0.0)
@@ -153,7 +153,7 @@ def test_non_finite_parameters_are_reported(b):
     g = GpuTable(b, T, scale, bias)
     ref = eb.checked_eb(T, scale, bias, indices, offsets)
     assert ref.flags[0] == 1 and ref.flags[2] == 1
-    for v in ("batch", "wave"):
+    for v in ("batch", "group"):
         out = g.run(indices, offsets, None, v)
         assert np.array_equal(out["flags"], ref.flags)
         assert np.array_equal(np.isnan(out["R"]), np.isnan(ref.R))
@@ -169,7 +169,7 @@ def test_zero_bound_and_threshold_on_integer_table(b):
     indices, offsets = w.draw_bags(rng, 400, 6, 100, "fixed")
     g = GpuTable(b, T, scale, bias)
     C_T = eb.table_rowsums(T)
-    for v in ("batch", "wave"):
+    for v in ("batch", "group"):
         assert not g.run(indices, offsets, None, v, bound=0.0)["flags"].any()
     bag0 = indices[offsets[0]:offsets[1]]
     row, col = int(next(i for i in bag0 if (bag0 == i).sum() == 1)), 5   # pooled exactly once by lookup 0
@@ -178,13 +178,13 @@ def test_zero_bound_and_threshold_on_integer_table(b):
         T2 = T.copy()
         T2[row, col] ^= np.uint8(1 << bit)
         ref = eb.checked_eb(T2, scale, bias, indices, offsets, C_T=C_T)
-        for v in ("batch", "wave"):
+        for v in ("batch", "group"):
             out = g.run(indices, offsets, None, v)
             assert same_bits(out["R"], ref.R) and np.array_equal(out["flags"], ref.flags)
             assert out["flags"][0] == int(bit >= 4)     # CSum is about 816000: 1e-5 of it lies between 8 and 16
         b.abft_eb_table_flip_bit(g.Tp, row, col, bit)
     assert np.array_equal(g.rowsums(), C_T)
-    assert not g.run(indices, offsets, None, "wave")["flags"].any()
+    assert not g.run(indices, offsets, None, "group")["flags"].any()
 
 
 @pytest.mark.parametrize("regime", ["uniform", "gauss"])
