@@ -1,5 +1,6 @@
 #!/usr/bin/env python3
-"""Benchmark of the ABFT-checked u8 x s8 -> s32 GEMM on one MI355X.
+"""Benchmark of the ABFT-checked u8 x s8 -> s32 GEMM on one MI355X (and, under "eb", of the
+ABFT-checked EmbeddingBag, the paper's second operator).
 
 A step is one pass of the hot path over one batch of synthetic input already resident
 in HBM: the checked GEMM call (product with the checksum column folded in, row sums,
@@ -202,7 +203,7 @@ def pmc_child(args):
     torch.cuda.synchronize()
 
 
-def measure_traffic(args):
+def measure_traffic(args, child_args=None, tags=None):
     """HBM bytes per checked launch from two counter passes of rocprofv3 (FETCH_SIZE, then
     WRITE_SIZE), each over a child process running pmc_child, each scaled by what the same
     counter reads for the calibration copy.  Runs before this process touches the GPU.
@@ -219,8 +220,9 @@ def measure_traffic(args):
         tmp = tempfile.mkdtemp(prefix="abft_pmc_")
         env = dict(os.environ, TMPDIR=tmp)
         cmd = ["timeout", "-s", "KILL", "170", "rocprofv3", "--pmc", counter, "-d", tmp, "-o", "pmc",
-               "--output-format", "csv", "--", sys.executable, os.path.join(ROOT, "bench.py"), "--pmc-child",
-               "--workload", str(args.workload), "--variant", str(args.variant)] + (["--mod127"] if args.mod127 else [])
+               "--output-format", "csv", "--", sys.executable, os.path.join(ROOT, "bench.py")]
+        cmd += child_args if child_args is not None else (
+            ["--pmc-child", "--workload", str(args.workload), "--variant", str(args.variant)] + (["--mod127"] if args.mod127 else []))
         try:
             r = subprocess.run(cmd, cwd=tmp, env=env, capture_output=True, text=True)
             files = glob.glob(os.path.join(tmp, "**", "*counter_collection.csv"), recursive=True)
@@ -234,7 +236,7 @@ def measure_traffic(args):
                 per_dispatch[k] = per_dispatch.get(k, 0.0) + float(row["Counter_Value"])
             cal = [v for (d, n), v in per_dispatch.items() if "calib_copy_kernel" in n]
             gemm = [v for (d, n), v in sorted(per_dispatch.items(), key=lambda kv: int(kv[0][0]))
-                    if any(t in n for t in GEMM_KERNEL_TAGS)]
+                    if any(t in n for t in (tags or GEMM_KERNEL_TAGS))]
             if len(cal) != 1 or cal[0] <= 0 or len(gemm) < 2:
                 return None, f"{counter} pass: unexpected dispatch list"
             gemm = gemm[1:]           # the first launch also pays for cold instruction and data caches
@@ -244,6 +246,143 @@ def measure_traffic(args):
         finally:
             shutil.rmtree(tmp, ignore_errors=True)
     return out, "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE per checked launch, scaled by a 256 MiB copy kernel"
+
+
+# ------------------------------------------------------------------------------------------------
+# Second operator: the ABFT-checked EmbeddingBag (include/abft_eb.h).  A step is one call of
+# abft_eb_u8_checked over one batch of lookups; the 4,000,000-row tables of Table I are laid end to
+# end in one allocation of at least 2 GiB and every step of a pass uses an index set of its own, so
+# that lookups are not served from cache (the paper flushes its caches for the same reason).
+EB_KERNEL_TAGS = ("eb_batch_kernel", "eb_group_kernel")
+EB_TABLE_MIN_BYTES = 2 << 30
+
+
+class EbJob:
+    def __init__(self, b, torch, wl, max_sets=2048, aligned=False):
+        import numpy as np
+        from paper_2103_00130_amd import eb_workloads as ew
+        self.b, self.torch, self.wl = b, torch, wl
+        rec = wl.d + 16
+        rng = ew.rng_for(900 + wl.d)
+        self.T, self.scale, self.bias = ew.draw_table(rng, wl.rows, wl.d, wl.regime)
+        copies = max(1, -(-EB_TABLE_MIN_BYTES // (wl.rows * rec)))
+        self.rows_big = wl.rows * copies
+        T = torch.from_numpy(self.T).cuda().repeat(copies, 1)
+        scale = torch.from_numpy(self.scale).cuda().repeat(copies)
+        bias = torch.from_numpy(self.bias).cuda().repeat(copies)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.Tp = b.abft_eb_pack_rowsum(T, scale, bias, b.ABFT_EB_PACK_LINE_ALIGNED if aligned else b.ABFT_EB_PACK_COMPACT)
+        torch.cuda.synchronize()
+        self.pack_ms = (time.perf_counter() - t0) * 1e3
+        del T
+        self.table_bytes = self.rows_big * b.abft_eb_table_dims(self.Tp)[2]
+        touched = wl.n_bags * wl.pooling * rec
+        self.n_sets = int(min(max_sets, max(4, (1 << 30) // touched)))
+        self.host_sets, self.sets, n_idx = [], [], 0
+        for s_ in range(self.n_sets):
+            indices, offsets = ew.draw_bags(rng, self.rows_big, wl.n_bags, wl.pooling, "spread")
+            weights = ew.draw_weights(rng, indices.size) if wl.weighted else None
+            if s_ < 64:
+                self.host_sets.append((indices, offsets, weights))
+            self.sets.append((torch.from_numpy(indices).cuda(), torch.from_numpy(offsets).cuda(),
+                              None if weights is None else torch.from_numpy(weights).cuda()))
+            n_idx += indices.size
+        self.mean_indices = n_idx / self.n_sets
+        self.R = torch.empty((wl.n_bags, wl.d), dtype=torch.float32, device="cuda")
+        self.flags = torch.empty(wl.n_bags, dtype=torch.int32, device="cuda")
+        # bytes the method itself must move per call: records and indices (and weights) of the pooled
+        # rows, offsets, the pooled rows written, one flag per lookup
+        self.bytes_per_call = self.mean_indices * (rec + 8 + (4 if wl.weighted else 0)) + wl.n_bags * (4 * wl.d + 8 + 4)
+
+    def call(self, s_, check=True):
+        b = self.b
+        idx, off, wts = self.sets[s_ % self.n_sets]
+        b.abft_eb_u8_checked(self.Tp, idx, off, self.R, self.flags, weights=wts,
+                             flags=b.ABFT_EB_CHECK if check else b.ABFT_EB_NOCHECK)
+
+    def time_calls(self, check=True, reps=3):
+        """Average microseconds per call: one HIP graph holding one call per index set, replayed."""
+        torch = self.torch
+        for s_ in range(min(self.n_sets, 8)):
+            self.call(s_, check)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for s_ in range(self.n_sets):
+                self.call(s_, check)
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * self.n_sets)
+
+    def false_positives(self, n=32):
+        bad = tot = 0
+        for s_ in range(min(n, self.n_sets)):
+            self.call(s_, True)
+            bad += int((self.flags != 0).sum().item())
+            tot += self.wl.n_bags
+        return 100.0 * bad / tot
+
+    def cpu_baseline(self, target_s=4.0):
+        """The CPU oracle on the 4,000,000-row table with the same index sets folded into it."""
+        from oracle import eb_oracle as oracle
+        wl = self.wl
+        C_T = oracle.table_rowsums(self.T)
+        t0 = time.perf_counter()
+        n = 0
+        while True:
+            indices, offsets, weights = self.host_sets[n % len(self.host_sets)]
+            oracle.checked_eb(self.T, self.scale, self.bias, indices % wl.rows, offsets, weights, C_T=C_T)
+            n += 1
+            dt = time.perf_counter() - t0
+            if dt > target_s or n >= 4 * len(self.host_sets):
+                break
+        return {"value": self.bytes_per_call * n / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                "us_per_call": dt / n * 1e6,
+                "sample": f"{n} calls of the oracle (lookup in float, RSum, CSum, comparison; row sums precomputed), {dt:.1f} s wall"}
+
+
+def measure_eb(b, torch, wl, cpu=True, aligned=False):
+    job = EbJob(b, torch, wl, aligned=aligned)
+    us_c = min(job.time_calls(True), job.time_calls(True))
+    us_u = min(job.time_calls(False), job.time_calls(False))
+    res = {
+        "workload": wl.name + ("_line_aligned" if aligned else ""), "rows": wl.rows, "d": wl.d,
+        "record_stride_bytes": job.table_bytes // job.rows_big, "n_bags": wl.n_bags, "pooling": wl.pooling, "weighted": wl.weighted,
+        "us_per_call": us_c, "us_per_call_unchecked": us_u, "abft_overhead_pct": 100.0 * (us_c - us_u) / us_u,
+        "pooled_rows_per_s": job.mean_indices / us_c * 1e6, "table_bytes": job.table_bytes,
+        "index_sets_rotated": job.n_sets, "pack_ms": job.pack_ms, "false_positive_pct": job.false_positives(),
+        "roofline": {"bound": "hbm", "achieved": job.bytes_per_call / us_c / 1e3, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": job.bytes_per_call / us_c / 1e3 / PEAK_HBM_GBS, "traffic": None,
+                     "algorithmic_bytes": job.bytes_per_call},
+    }
+    if cpu:
+        res["cpu_baseline"] = job.cpu_baseline()
+    job.Tp.destroy()
+    return res
+
+
+def pmc_child_eb(spec):
+    """Profiled child for the EmbeddingBag: one calibration copy, then a few checked calls (d:n_bags)."""
+    import torch
+    from paper_2103_00130_amd import binding as b
+    from paper_2103_00130_amd import eb_workloads as ew
+    torch.cuda.set_device(0)
+    d, n_bags = (int(x) for x in spec.split(":"))
+    src = torch.zeros(CALIB_COPY_BYTES // 4, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    job = EbJob(b, torch, ew.EbWorkload("pmc", 4_000_000, d, n_bags, 100, False, "uniform"), max_sets=5)
+    torch.cuda.synchronize()
+    b.abft_calib_copy(src, dst)
+    for s_ in range(5):
+        job.call(s_, True)
+    torch.cuda.synchronize()
 
 
 def main():
@@ -260,6 +399,8 @@ def main():
     ap.add_argument("--mod127", action="store_true", help="check with the paper's printed modulus (8-bit checksum column, "
                     "comparison modulo 127) instead of the exact int32 checksum; tiled kernels only")
     ap.add_argument("--pmc-child", action="store_true", help=argparse.SUPPRESS)
+    ap.add_argument("--pmc-child-eb", type=str, default=None, help=argparse.SUPPRESS)
+    ap.add_argument("--no-eb", action="store_true", help="skip the EmbeddingBag entries (reported under 'eb')")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -267,7 +408,13 @@ def main():
     if args.pmc_child:
         pmc_child(args)
         return
+    if args.pmc_child_eb:
+        pmc_child_eb(args.pmc_child_eb)
+        return
     traffic, traffic_note = (None, "skipped") if args.no_traffic else measure_traffic(args)
+    eb_traffic = None
+    if not args.no_traffic and not args.no_eb:
+        eb_traffic, _ = measure_traffic(args, ["--pmc-child-eb", "64:16384"], EB_KERNEL_TAGS)
 
     import torch
     from paper_2103_00130_amd import binding as b     # fails loudly if the HIP library is missing
@@ -340,6 +487,29 @@ def main():
                 continue
             _, r = measure(cfg, args.steps, args.warmup)
             out["others"].append(r)
+    if not args.no_eb:
+        # second operator (Algorithm 2): Table I at d = 64 and the same table under a large batch; with
+        # --others every width of Table I, regular and weighted sum
+        from paper_2103_00130_amd import eb_workloads as ew
+        import dataclasses
+        del job
+        torch.cuda.empty_cache()
+        eb_list = [ew.TABLE1[64], ew.LARGE_BATCH[64]]
+        if args.others:
+            eb_list = [ew.TABLE1[d] for d in (32, 64, 128, 256)]
+            eb_list += [dataclasses.replace(ew.TABLE1[d], name=ew.TABLE1[d].name + "_weighted", weighted=True) for d in (32, 64, 128, 256)]
+            eb_list += [ew.LARGE_BATCH[d] for d in (32, 64, 128, 256)]
+        out["eb"] = []
+        # (workload, records line-aligned): the large batches of narrow rows are also run on records that
+        # never straddle a 128-byte line
+        eb_runs = [(ewl, False) for ewl in eb_list] + [(ewl, True) for ewl in eb_list if ewl.n_bags > 1000 and ewl.d <= 64]
+        for ewl, aligned in eb_runs:
+            r = measure_eb(b, torch, ewl, cpu=not args.no_cpu_baseline and not aligned, aligned=aligned)
+            if eb_traffic is not None and ewl.name == ew.LARGE_BATCH[64].name and not aligned:
+                r["roofline"]["traffic"] = eb_traffic["read"] + eb_traffic["write"]
+                r["roofline"]["traffic_read"] = eb_traffic["read"]
+                r["roofline"]["traffic_write"] = eb_traffic["write"]
+            out["eb"].append(r)
     print(json.dumps(out))
 
 

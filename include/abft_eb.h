@@ -51,6 +51,12 @@ extern "C" {
 #define ABFT_EB_VARIANT_BATCH 0x100u  /* a few lanes per lookup, rows straight into registers: large batches */
 #define ABFT_EB_VARIANT_GROUP 0x200u  /* one workgroup per lookup, rows staged in LDS: small batches */
 
+/* flags of abft_eb_pack_rowsum */
+#define ABFT_EB_PACK_COMPACT 0u       /* default: records of d + 16 bytes back to back */
+#define ABFT_EB_PACK_LINE_ALIGNED 1u  /* records of up to 128 bytes (d <= 64) get a power-of-two stride
+                                         (32, 64 or 128 bytes), so that no record straddles a 128-byte
+                                         memory line: fewer bytes fetched per lookup, a larger table */
+
 /* bits of bag_flags[b] */
 #define ABFT_EB_ERR 1          /* Algorithm 2's err: RSum and CSum differ by more than the bound */
 #define ABFT_EB_BAD_INDEX 2    /* an index of the lookup lies outside the table; it was not pooled */
@@ -63,12 +69,13 @@ typedef struct abft_eb_table abft_eb_table;
  *   scale, bias   float32 [rows]
  *   d      16, 32, 64, 128, 256 or 512
  *   out    host pointer receiving the handle
- * Allocates rows * (d + 16) bytes with hipMalloc; the packing kernel is enqueued on `stream`
- * and the inputs must stay valid until it has run. */
+ *   flags  ABFT_EB_PACK_COMPACT or ABFT_EB_PACK_LINE_ALIGNED
+ * Allocates rows * stride bytes with hipMalloc (stride = d + 16 unless line-aligned); the packing
+ * kernel is enqueued on `stream` and the inputs must stay valid until it has run. */
 int abft_eb_pack_rowsum(const uint8_t* T, int64_t ldt, const float* scale, const float* bias, int64_t rows, int d,
-                        void* stream, abft_eb_table** out);
+                        unsigned flags, void* stream, abft_eb_table** out);
 
-/* rows, d and the record size in bytes (host out-pointers, any may be NULL). */
+/* rows, d and the record stride in bytes (host out-pointers, any may be NULL). */
 int abft_eb_table_dims(const abft_eb_table* Tp, int64_t* rows, int* d, int* record_bytes);
 
 /* Copy C_T (int32 [rows]; Section V) out of the records. */

@@ -34,6 +34,7 @@ EXPORTS_EB = (
 ABFT_EB_CHECK, ABFT_EB_NOCHECK = 0, 1
 ABFT_EB_VARIANT_BATCH, ABFT_EB_VARIANT_GROUP = 0x100, 0x200
 ABFT_EB_ERR, ABFT_EB_BAD_INDEX = 1, 2
+ABFT_EB_PACK_COMPACT, ABFT_EB_PACK_LINE_ALIGNED = 0, 1
 
 
 class abft_requant_t(ctypes.Structure):
@@ -79,7 +80,7 @@ def _load() -> ctypes.CDLL:
     L.abft_recover_scratch_bytes.restype = sz
     L.abft_recompute_flagged_rows.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64,
                                               i32, vp, sz, vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
-    L.abft_eb_pack_rowsum.argtypes = [vp, i64, vp, vp, i64, i32, vp, ctypes.POINTER(vp)]
+    L.abft_eb_pack_rowsum.argtypes = [vp, i64, vp, vp, i64, i32, u32, vp, ctypes.POINTER(vp)]
     L.abft_eb_table_dims.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.abft_eb_table_get_rowsums.argtypes = [vp, vp, vp]
     L.abft_eb_table_flip_bit.argtypes = [vp, i64, i32, i32, vp]
@@ -298,7 +299,7 @@ class EbTable:
             pass
 
 
-def abft_eb_pack_rowsum(T: torch.Tensor, scale: torch.Tensor, bias: torch.Tensor, stream=None) -> EbTable:
+def abft_eb_pack_rowsum(T: torch.Tensor, scale: torch.Tensor, bias: torch.Tensor, flags: int = 0, stream=None) -> EbTable:
     """T: uint8 device tensor rows x d; scale, bias: float32 [rows]."""
     ptr = _ptr(T, torch.uint8, "T")
     ldt = _ld(T, "T")
@@ -307,7 +308,7 @@ def abft_eb_pack_rowsum(T: torch.Tensor, scale: torch.Tensor, bias: torch.Tensor
         raise ValueError("scale and bias must be contiguous with one entry per table row")
     out = ctypes.c_void_p()
     _check(lib.abft_eb_pack_rowsum(ptr, ldt, _ptr(scale, torch.float32, "scale"), _ptr(bias, torch.float32, "bias"),
-                                   rows, d, _stream(stream), ctypes.byref(out)))
+                                   rows, d, int(flags), _stream(stream), ctypes.byref(out)))
     return EbTable(out.value, rows, d)
 
 

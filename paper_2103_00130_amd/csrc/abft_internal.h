@@ -169,7 +169,7 @@ hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream
 hipError_t launch_row_checksum(const uint8_t* A, int64_t lda, int M, int K, const int32_t* S_B,
                                int32_t* row_chk, hipStream_t s);
 
-// EmbeddingBag: lanes (lookups x d/16) from which the batch kernel is chosen over the wave kernel
+// EmbeddingBag: lanes (lookups x max(d/16, 4)) from which the batch kernel is chosen over the group kernel
 constexpr int64_t kEbBatchMinLanes = 262144;
 
 // records `code` and a message for abft_last_error(); returns `code`

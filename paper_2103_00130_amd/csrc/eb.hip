@@ -24,8 +24,9 @@
 #include "abft_internal.h"
 
 struct abft_eb_table {
-    uint8_t* rec;   // rows * (d + 16) bytes
+    uint8_t* rec;    // rows * stride bytes
     int64_t rows;
+    int64_t stride;  // d + 16, or the next power of two when the records are line-aligned
     int d;
     int device;
 };
@@ -38,6 +39,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 struct EbParams {
     const uint8_t* tab;
+    int64_t stride;  // bytes from one record to the next
     int64_t rows;
     const int64_t* indices;
     int64_t n_indices;
@@ -83,7 +85,7 @@ __device__ inline void fma16(float (&acc)[16], float a, v4u q) {
 // Batch kernel: G = d/16 lanes per lookup.
 template <int G, bool kCheck, bool kWeighted>
 __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
-    constexpr int D = 16 * G, REC = D + 16, U = 8;
+    constexpr int D = 16 * G, U = 8;
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t bag = t / G;
     const int piece = (int)(t % G);
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
             const bool in = pos + u < end;
             ok[u] = in && (uint64_t)idx[u] < (uint64_t)p.rows;
             if (in && !ok[u]) flag |= ABFT_EB_BAD_INDEX;
-            const uint8_t* r = base + (ok[u] ? idx[u] : 0) * REC;
+            const uint8_t* r = base + (ok[u] ? idx[u] : 0) * p.stride;
             q[u] = *reinterpret_cast<const v4u*>(r);
             tl[u] = *reinterpret_cast<const v4u*>(r + (D - piece * 16));
         }
@@ -178,7 +180,7 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
 //     depend on the column (sum of biases, CSum).
 template <int G, bool kCheck, bool kWeighted>
 __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
-    constexpr int D = 16 * G, REC = D + 16;
+    constexpr int D = 16 * G, REC = D + 16;   // REC: a record as staged in LDS (no padding there)
     constexpr int P = G + 1;                   // 16-byte pieces per record
     constexpr int NL = G >= 16 ? 8 : 4;        // load instructions per thread and chunk
     constexpr int PIECES = NL * 256;
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
         for (int l = 0; l < NL; ++l) {
             const int g = l * 256 + tid, r = g / P, pc = g - r * P;
             const bool ok = (uint64_t)idx[l] < (uint64_t)p.rows;
-            v[l] = *reinterpret_cast<const v4u*>(p.tab + (ok ? idx[l] : 0) * REC + pc * 16);
+            v[l] = *reinterpret_cast<const v4u*>(p.tab + (ok ? idx[l] : 0) * p.stride + pc * 16);
             // the last word of a record's tail is unused in memory; staged, it marks a row that is not pooled
             if (pc == G) v[l][3] = ok ? 0u : 1u;
         }
@@ -342,7 +344,7 @@ hipError_t launch_eb(int d, bool group, bool check, bool weighted, const EbParam
 // Table build (Section V: row sums computed once), and the small helpers.
 // One thread per 16-byte piece of a record; the thread of the tail piece sums the row's codes.
 __global__ __launch_bounds__(256) void eb_pack_kernel(const uint8_t* T, int64_t ldt, const float* scale, const float* bias,
-                                                      int64_t rows, int d, uint8_t* rec) {
+                                                      int64_t rows, int d, uint8_t* rec, int64_t stride) {
     const int P = d / 16 + 1;
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t row = t / P;
@@ -366,12 +368,12 @@ __global__ __launch_bounds__(256) void eb_pack_kernel(const uint8_t* T, int64_t 
         out[2] = (unsigned int)sum;
         out[3] = 0u;
     }
-    *reinterpret_cast<v4u*>(rec + row * (int64_t)(d + 16) + pc * 16) = out;
+    *reinterpret_cast<v4u*>(rec + row * stride + pc * 16) = out;
 }
 
-__global__ __launch_bounds__(256) void eb_get_rowsums_kernel(const uint8_t* rec, int64_t rows, int d, int32_t* C_T) {
+__global__ __launch_bounds__(256) void eb_get_rowsums_kernel(const uint8_t* rec, int64_t stride, int64_t rows, int d, int32_t* C_T) {
     const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (row < rows) C_T[row] = *reinterpret_cast<const int32_t*>(rec + row * (int64_t)(d + 16) + d + 8);
+    if (row < rows) C_T[row] = *reinterpret_cast<const int32_t*>(rec + row * stride + d + 8);
 }
 
 __global__ void eb_flip_kernel(uint8_t* rec, int64_t off, int bit) {
@@ -390,12 +392,16 @@ __global__ void eb_flip_kernel(uint8_t* rec, int64_t off, int bit) {
 extern "C" {
 
 int abft_eb_pack_rowsum(const uint8_t* T, int64_t ldt, const float* scale, const float* bias, int64_t rows, int d,
-                        void* stream, abft_eb_table** out) {
+                        unsigned flags, void* stream, abft_eb_table** out) {
     if (!T || !scale || !bias || !out) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: null pointer");
     if (rows < 1) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: rows=%lld must be >= 1", (long long)rows);
     if (d != 16 && d != 32 && d != 64 && d != 128 && d != 256 && d != 512)
         return abft::set_error(ABFT_EUNSUPPORTED, "abft_eb_pack_rowsum: d=%d (supported: 16, 32, 64, 128, 256, 512)", d);
     if (ldt < d) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: ldt=%lld smaller than d=%d", (long long)ldt, d);
+    if (flags & ~ABFT_EB_PACK_LINE_ALIGNED) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: unknown flag bits %#x", flags);
+    // line-aligned: records of up to 128 bytes get a power-of-two stride, so none of them straddles a 128-byte line
+    int64_t stride = d + 16;
+    if ((flags & ABFT_EB_PACK_LINE_ALIGNED) && stride <= 128) stride = stride <= 32 ? 32 : (stride <= 64 ? 64 : 128);
     const int64_t pieces = rows * (d / 16 + 1);
     if ((pieces + 255) / 256 > 0x7fffffffll) return abft::set_error(ABFT_EUNSUPPORTED, "abft_eb_pack_rowsum: table too large");
     abft_eb_table* h = new (std::nothrow) abft_eb_table();
@@ -403,11 +409,12 @@ int abft_eb_pack_rowsum(const uint8_t* T, int64_t ldt, const float* scale, const
     std::memset(h, 0, sizeof *h);
     h->rows = rows;
     h->d = d;
+    h->stride = stride;
     hipError_t e = hipGetDevice(&h->device);
-    if (e == hipSuccess) e = hipMalloc(&h->rec, (size_t)rows * (size_t)(d + 16));
+    if (e == hipSuccess) e = hipMalloc(&h->rec, (size_t)rows * (size_t)stride);
     if (e == hipSuccess) {
         abft::eb_pack_kernel<<<dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
-            T, ldt, scale, bias, rows, d, h->rec);
+            T, ldt, scale, bias, rows, d, h->rec, stride);
         e = hipGetLastError();
     }
     if (e != hipSuccess) {
@@ -423,14 +430,14 @@ int abft_eb_table_dims(const abft_eb_table* Tp, int64_t* rows, int* d, int* reco
     if (!Tp) return abft::set_error(ABFT_EINVAL, "abft_eb_table_dims: null handle");
     if (rows) *rows = Tp->rows;
     if (d) *d = Tp->d;
-    if (record_bytes) *record_bytes = Tp->d + 16;
+    if (record_bytes) *record_bytes = (int)Tp->stride;
     return ABFT_OK;
 }
 
 int abft_eb_table_get_rowsums(const abft_eb_table* Tp, int32_t* C_T, void* stream) {
     if (!Tp || !C_T) return abft::set_error(ABFT_EINVAL, "abft_eb_table_get_rowsums: null pointer");
     abft::eb_get_rowsums_kernel<<<dim3((unsigned)((Tp->rows + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
-        Tp->rec, Tp->rows, Tp->d, C_T);
+        Tp->rec, Tp->stride, Tp->rows, Tp->d, C_T);
     HIP_TRY(hipGetLastError());
     return ABFT_OK;
 }
@@ -439,7 +446,7 @@ int abft_eb_table_flip_bit(abft_eb_table* Tp, int64_t row, int col, int bit, voi
     if (!Tp) return abft::set_error(ABFT_EINVAL, "abft_eb_table_flip_bit: null handle");
     if (row < 0 || row >= Tp->rows || col < 0 || col >= Tp->d || bit < 0 || bit > 7)
         return abft::set_error(ABFT_EINVAL, "abft_eb_table_flip_bit: row=%lld col=%d bit=%d outside the table", (long long)row, col, bit);
-    abft::eb_flip_kernel<<<dim3(1), dim3(64), 0, (hipStream_t)stream>>>(Tp->rec, row * (int64_t)(Tp->d + 16) + col, bit);
+    abft::eb_flip_kernel<<<dim3(1), dim3(64), 0, (hipStream_t)stream>>>(Tp->rec, row * Tp->stride + col, bit);
     HIP_TRY(hipGetLastError());
     return ABFT_OK;
 }
@@ -471,13 +478,14 @@ int abft_eb_u8_checked(const abft_eb_table* Tp, const int64_t* indices, int64_t 
     const int G = Tp->d / 16;
     if (n_bags > 0x7fffffffll || (n_bags * G + 255) / 256 > 0x7fffffffll)
         return abft::set_error(ABFT_EUNSUPPORTED, "%s: n_bags=%lld too large for one launch", fn, (long long)n_bags);
-    // the batch kernel needs enough lookups to fill the chip with lanes; below that one wavefront per lookup
-    // keeps more bytes in flight
-    bool group = n_bags * G < abft::kEbBatchMinLanes;
+    // the batch kernel needs enough lookups to fill the chip with lanes; below that one workgroup per lookup
+    // keeps more bytes in flight (measured crossover: 65536 lookups at d <= 64, 16384 at d = 256)
+    bool group = n_bags * (G < 4 ? 4 : G) < abft::kEbBatchMinLanes;
     if (variant == ABFT_EB_VARIANT_BATCH) group = false;
     if (variant == ABFT_EB_VARIANT_GROUP) group = true;
     abft::EbParams p;
     p.tab = Tp->rec;
+    p.stride = Tp->stride;
     p.rows = Tp->rows;
     p.indices = indices;
     p.n_indices = n_indices;

@@ -65,11 +65,12 @@ def test_eb_bad_arguments_are_rejected_on_the_host(binding):
     L = binding.lib
     out = ctypes.c_void_p()
     dummy = ctypes.c_void_p(0x1000)
-    assert L.abft_eb_pack_rowsum(None, 64, dummy, dummy, 10, 64, None, ctypes.byref(out)) == binding.ABFT_EINVAL
-    assert L.abft_eb_pack_rowsum(dummy, 64, dummy, dummy, 0, 64, None, ctypes.byref(out)) == binding.ABFT_EINVAL
-    assert L.abft_eb_pack_rowsum(dummy, 32, dummy, dummy, 10, 64, None, ctypes.byref(out)) == binding.ABFT_EINVAL  # ldt < d
-    assert L.abft_eb_pack_rowsum(dummy, 100, dummy, dummy, 10, 100, None, ctypes.byref(out)) == binding.ABFT_EUNSUPPORTED
+    assert L.abft_eb_pack_rowsum(None, 64, dummy, dummy, 10, 64, 0, None, ctypes.byref(out)) == binding.ABFT_EINVAL
+    assert L.abft_eb_pack_rowsum(dummy, 64, dummy, dummy, 0, 64, 0, None, ctypes.byref(out)) == binding.ABFT_EINVAL
+    assert L.abft_eb_pack_rowsum(dummy, 32, dummy, dummy, 10, 64, 0, None, ctypes.byref(out)) == binding.ABFT_EINVAL  # ldt < d
+    assert L.abft_eb_pack_rowsum(dummy, 100, dummy, dummy, 10, 100, 0, None, ctypes.byref(out)) == binding.ABFT_EUNSUPPORTED
     assert b"d=100" in L.abft_last_error()
+    assert L.abft_eb_pack_rowsum(dummy, 64, dummy, dummy, 10, 64, 6, None, ctypes.byref(out)) == binding.ABFT_EINVAL  # unknown flag
     assert L.abft_eb_table_dims(None, None, None, None) == binding.ABFT_EINVAL
     assert L.abft_eb_table_get_rowsums(None, dummy, None) == binding.ABFT_EINVAL
     assert L.abft_eb_table_flip_bit(None, 0, 0, 0, None) == binding.ABFT_EINVAL

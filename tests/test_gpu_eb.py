@@ -30,9 +30,9 @@ def dev(a):
 
 
 class GpuTable:
-    def __init__(self, b, T, scale, bias):
+    def __init__(self, b, T, scale, bias, aligned=False):
         self.b = b
-        self.Tp = b.abft_eb_pack_rowsum(dev(T), dev(scale), dev(bias))
+        self.Tp = b.abft_eb_pack_rowsum(dev(T), dev(scale), dev(bias), b.ABFT_EB_PACK_LINE_ALIGNED if aligned else 0)
         torch.cuda.synchronize()
 
     def rowsums(self):
@@ -86,8 +86,10 @@ def test_eb_matches_oracle(b, d, variant):
         indices = np.concatenate([indices, extra])
         offsets = np.concatenate([offsets, [indices.size]]).astype(np.int64)
         weights = w.draw_weights(rng, indices.size) if weighted else None
-        g = GpuTable(b, T, scale, bias)
-        assert b.abft_eb_table_dims(g.Tp) == (3000, d, d + 16)
+        aligned = regime == "gauss"     # one of the three passes runs on line-aligned records
+        g = GpuTable(b, T, scale, bias, aligned)
+        stride = {16: 32, 32: 64, 64: 128}.get(d, d + 16) if aligned else d + 16
+        assert b.abft_eb_table_dims(g.Tp) == (3000, d, stride)
         assert np.array_equal(g.rowsums(), eb.table_rowsums(T))
         ref = eb.checked_eb(T, scale, bias, indices, offsets, weights)
         out = g.run(indices, offsets, weights, variant)
@@ -193,7 +195,7 @@ def test_table_flip_campaign_matches_oracle(b, regime):
     pooled table elements, one per launch, plus clean launches; every flag vector equals the oracle's."""
     wl = w.EbWorkload("campaign", 20000, 64, 10, 100, False, regime)
     x = w.make_inputs(wl, tag=20)
-    g = GpuTable(b, x.T, x.scale, x.bias)
+    g = GpuTable(b, x.T, x.scale, x.bias, aligned=(regime == "gauss"))
     C_T = eb.table_rowsums(x.T)
     clean = eb.checked_eb(x.T, x.scale, x.bias, x.indices, x.offsets)
     assert clean.robust.all()
