@@ -401,6 +401,8 @@ def main():
     ap.add_argument("--pmc-child", action="store_true", help=argparse.SUPPRESS)
     ap.add_argument("--pmc-child-eb", type=str, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--no-eb", action="store_true", help="skip the EmbeddingBag entries (reported under 'eb')")
+    ap.add_argument("--eb-only", type=str, default=None, metavar="D:N_BAGS",
+                    help="time only the EmbeddingBag at row width D and batch N_BAGS (Table I table, pooling 100) and print its entry")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -410,6 +412,15 @@ def main():
         return
     if args.pmc_child_eb:
         pmc_child_eb(args.pmc_child_eb)
+        return
+    if args.eb_only:
+        import torch
+        from paper_2103_00130_amd import binding as b
+        from paper_2103_00130_amd import eb_workloads as ew
+        torch.cuda.set_device(0)
+        d, n_bags = (int(x) for x in args.eb_only.split(":"))
+        ewl = ew.EbWorkload(f"rows4000000_d{d}_pool100_batch{n_bags}", 4_000_000, d, n_bags, 100, False, "uniform")
+        print(json.dumps({"eb": [measure_eb(b, torch, ewl, cpu=False)]}))
         return
     traffic, traffic_note = (None, "skipped") if args.no_traffic else measure_traffic(args)
     eb_traffic = None
