@@ -7,6 +7,10 @@
  * benchmark may call it.  It shares no code with the HIP path and knows nothing
  * about fused row records, lanes or wavefronts.
  *
+ * Tables hold 8-bit codes (one per byte) or 4-bit codes (Section V, overhead analysis: p = 4 or 8
+ * bits; two codes per byte, the even column in the low half): `bits` says which, and a row of
+ * the table is d * bits / 8 bytes.
+ *
  * Notation of the paper: T the table of 8-bit codes, d its row length, alpha[i] and
  * beta[i] the scale and bias of row i, I the index set of one lookup ("bag"), R the
  * pooled row, C_T[i] = sum_j T[i][j] the precomputed 32-bit integer row sums.
@@ -36,17 +40,23 @@
 #include <stdlib.h>
 #include <string.h>
 
+static inline int code_at(const uint8_t* T, int64_t i, int j, int d, int bits) {
+    if (bits == 8) return T[i * d + j];
+    const uint8_t b = T[i * (d / 2) + (j >> 1)];
+    return (j & 1) ? (b >> 4) : (b & 15);
+}
+
 /* Section V: the column vector C_T of row sums of the table, 32-bit integers. */
-void eb_oracle_rowsums(const uint8_t* T, int64_t rows, int d, int32_t* C_T) {
+void eb_oracle_rowsums(const uint8_t* T, int64_t rows, int d, int bits, int32_t* C_T) {
     for (int64_t i = 0; i < rows; ++i) {
         int32_t s = 0;
-        for (int j = 0; j < d; ++j) s += T[i * d + j];
+        for (int j = 0; j < d; ++j) s += code_at(T, i, j, d, bits);
         C_T[i] = s;
     }
 }
 
 /* Section III-C: R = sum_{i in I} alpha_i eb_i + beta_i e_d (times w_i when weighted), in double. */
-void eb_oracle_forward_f64(const uint8_t* T, int64_t rows, int d, const float* alpha, const float* beta,
+void eb_oracle_forward_f64(const uint8_t* T, int64_t rows, int d, int bits, const float* alpha, const float* beta,
                            const int64_t* indices, const int64_t* offsets, int64_t n_bags, const float* w, double* R) {
     for (int64_t b = 0; b < n_bags; ++b) {
         for (int j = 0; j < d; ++j) R[b * d + j] = 0.0;
@@ -55,13 +65,13 @@ void eb_oracle_forward_f64(const uint8_t* T, int64_t rows, int d, const float* a
             if (i < 0 || i >= rows) continue;
             const double wi = w ? (double)w[p] : 1.0;
             for (int j = 0; j < d; ++j)
-                R[b * d + j] += wi * ((double)alpha[i] * (double)T[i * d + j] + (double)beta[i]);
+                R[b * d + j] += wi * ((double)alpha[i] * (double)code_at(T, i, j, d, bits) + (double)beta[i]);
         }
     }
 }
 
 /* The same in float, in the order stated in the header. */
-void eb_oracle_forward_f32(const uint8_t* T, int64_t rows, int d, const float* alpha, const float* beta,
+void eb_oracle_forward_f32(const uint8_t* T, int64_t rows, int d, int bits, const float* alpha, const float* beta,
                            const int64_t* indices, const int64_t* offsets, int64_t n_bags, const float* w, float* R) {
     for (int64_t b = 0; b < n_bags; ++b) {
         for (int j = 0; j < d; ++j) R[b * d + j] = 0.0f;
@@ -71,7 +81,7 @@ void eb_oracle_forward_f32(const uint8_t* T, int64_t rows, int d, const float* a
             if (i < 0 || i >= rows) continue;
             const float a = w ? w[p] * alpha[i] : alpha[i];
             const float c = w ? w[p] * beta[i] : beta[i];
-            for (int j = 0; j < d; ++j) R[b * d + j] = fmaf(a, (float)T[i * d + j], R[b * d + j]);
+            for (int j = 0; j < d; ++j) R[b * d + j] = fmaf(a, (float)code_at(T, i, j, d, bits), R[b * d + j]);
             beta_sum = beta_sum + c;
         }
         for (int j = 0; j < d; ++j) R[b * d + j] = R[b * d + j] + beta_sum;
@@ -106,18 +116,21 @@ void eb_oracle_check(const float* R, int64_t ldr, int64_t rows, int d, const flo
 }
 
 /* Section VI-B-2: one bit of one table element is flipped after C_T was computed, the batch is
- * looked up and checked (in float), the element is restored.  flags_out[n][n_bags]. */
-void eb_oracle_campaign_table_flips(uint8_t* T, int64_t rows, int d, const float* alpha, const float* beta,
+ * looked up and checked (in float), the element is restored.  f_bit counts inside the element
+ * (0..bits-1).  flags_out[n][n_bags]. */
+void eb_oracle_campaign_table_flips(uint8_t* T, int64_t rows, int d, int bits, const float* alpha, const float* beta,
                                     const int32_t* C_T, const int64_t* indices, const int64_t* offsets, int64_t n_bags,
                                     const float* w, double bound, const int64_t* f_row, const int32_t* f_col,
                                     const int32_t* f_bit, int64_t n, int32_t* flags_out) {
     float* R = (float*)malloc(sizeof(float) * (size_t)n_bags * (size_t)d);
     for (int64_t t = 0; t < n; ++t) {
-        uint8_t* e = &T[f_row[t] * d + f_col[t]];
-        *e ^= (uint8_t)(1u << f_bit[t]);
-        eb_oracle_forward_f32(T, rows, d, alpha, beta, indices, offsets, n_bags, w, R);
+        /* the element's bit inside its byte: a 4-bit code of an odd column sits in the high half */
+        uint8_t* e = bits == 8 ? &T[f_row[t] * d + f_col[t]] : &T[f_row[t] * (d / 2) + (f_col[t] >> 1)];
+        const uint8_t mask = (uint8_t)(1u << (f_bit[t] + (bits == 4 && (f_col[t] & 1) ? 4 : 0)));
+        *e ^= mask;
+        eb_oracle_forward_f32(T, rows, d, bits, alpha, beta, indices, offsets, n_bags, w, R);
         eb_oracle_check(R, d, rows, d, alpha, beta, C_T, indices, offsets, n_bags, w, bound, flags_out + t * n_bags, 0, 0);
-        *e ^= (uint8_t)(1u << f_bit[t]);
+        *e ^= mask;
     }
     free(R);
 }

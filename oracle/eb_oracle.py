@@ -48,13 +48,13 @@ def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
         L = ctypes.CDLL(build())
-        L.eb_oracle_rowsums.argtypes = [_u8p, _i64, _int, _i32p]
-        fwd = [_u8p, _i64, _int, _f32p, _f32p, _i64p, _i64p, _i64, _f32p]
+        L.eb_oracle_rowsums.argtypes = [_u8p, _i64, _int, _int, _i32p]
+        fwd = [_u8p, _i64, _int, _int, _f32p, _f32p, _i64p, _i64p, _i64, _f32p]
         L.eb_oracle_forward_f64.argtypes = fwd + [_f64p]
         L.eb_oracle_forward_f32.argtypes = fwd + [_f32p]
         L.eb_oracle_check.argtypes = [_f32p, _i64, _i64, _int, _f32p, _f32p, _i32p, _i64p, _i64p, _i64, _f32p, _dbl,
                                       _i32p, _f64p, _f64p]
-        L.eb_oracle_campaign_table_flips.argtypes = [_u8p, _i64, _int, _f32p, _f32p, _i32p, _i64p, _i64p, _i64, _f32p,
+        L.eb_oracle_campaign_table_flips.argtypes = [_u8p, _i64, _int, _int, _f32p, _f32p, _i32p, _i64p, _i64p, _i64, _f32p,
                                                      _dbl, _i64p, _i32p, _i32p, _i64, _i32p]
         for f in (L.eb_oracle_rowsums, L.eb_oracle_forward_f64, L.eb_oracle_forward_f32, L.eb_oracle_check,
                   L.eb_oracle_campaign_table_flips):
@@ -67,10 +67,11 @@ def _p(a, t):
     return a.ctypes.data_as(t) if a is not None else None
 
 
-def _table(T):
+def _table(T, bits=8):
+    """The code table as bytes, and its number of columns d (4-bit codes lie two per byte)."""
     T = np.ascontiguousarray(T, dtype=np.uint8)
-    assert T.ndim == 2
-    return T
+    assert T.ndim == 2 and bits in (4, 8)
+    return T, T.shape[1] * 8 // bits
 
 
 def _bags(indices, offsets):
@@ -85,28 +86,28 @@ def _f32(a):
     return None if a is None else np.ascontiguousarray(a, dtype=np.float32)
 
 
-def table_rowsums(T) -> np.ndarray:
+def table_rowsums(T, bits: int = 8) -> np.ndarray:
     """C_T of Section V: 32-bit integer row sums of the code table."""
-    T = _table(T)
+    T, d = _table(T, bits)
     out = np.empty(T.shape[0], dtype=np.int32)
-    lib().eb_oracle_rowsums(_p(T, _u8p), T.shape[0], T.shape[1], _p(out, _i32p))
+    lib().eb_oracle_rowsums(_p(T, _u8p), T.shape[0], d, bits, _p(out, _i32p))
     return out
 
 
-def forward(T, scale, bias, indices, offsets, weights=None, precision: str = "f32") -> np.ndarray:
+def forward(T, scale, bias, indices, offsets, weights=None, precision: str = "f32", bits: int = 8) -> np.ndarray:
     """The EmbeddingBag of Section III-C for a batch, in double ("f64", the definition) or in
     float in index order ("f32", the paper's precision)."""
-    T = _table(T)
+    T, d = _table(T, bits)
     scale, bias, weights = _f32(scale), _f32(bias), _f32(weights)
     indices, offsets = _bags(indices, offsets)
     n_bags = offsets.size - 1
     if precision == "f64":
-        R = np.empty((n_bags, T.shape[1]), dtype=np.float64)
-        lib().eb_oracle_forward_f64(_p(T, _u8p), T.shape[0], T.shape[1], _p(scale, _f32p), _p(bias, _f32p),
+        R = np.empty((n_bags, d), dtype=np.float64)
+        lib().eb_oracle_forward_f64(_p(T, _u8p), T.shape[0], d, bits, _p(scale, _f32p), _p(bias, _f32p),
                                     _p(indices, _i64p), _p(offsets, _i64p), n_bags, _p(weights, _f32p), _p(R, _f64p))
     elif precision == "f32":
-        R = np.empty((n_bags, T.shape[1]), dtype=np.float32)
-        lib().eb_oracle_forward_f32(_p(T, _u8p), T.shape[0], T.shape[1], _p(scale, _f32p), _p(bias, _f32p),
+        R = np.empty((n_bags, d), dtype=np.float32)
+        lib().eb_oracle_forward_f32(_p(T, _u8p), T.shape[0], d, bits, _p(scale, _f32p), _p(bias, _f32p),
                                     _p(indices, _i64p), _p(offsets, _i64p), n_bags, _p(weights, _f32p), _p(R, _f32p))
     else:
         raise ValueError(precision)
@@ -162,22 +163,24 @@ class CheckedEb:
     robust: np.ndarray
 
 
-def checked_eb(T, scale, bias, indices, offsets, weights=None, bound: float = REL_BOUND, C_T=None) -> CheckedEb:
+def checked_eb(T, scale, bias, indices, offsets, weights=None, bound: float = REL_BOUND, C_T=None,
+               bits: int = 8) -> CheckedEb:
     """Algorithm 2 end to end: lookup in float, RSum, CSum, comparison.  C_T may be given
     (row sums taken before a fault was planted in T); otherwise it is computed from T."""
-    T = _table(T)
+    T, _ = _table(T, bits)
     if C_T is None:
-        C_T = table_rowsums(T)
-    R = forward(T, scale, bias, indices, offsets, weights, "f32")
+        C_T = table_rowsums(T, bits)
+    R = forward(T, scale, bias, indices, offsets, weights, "f32", bits)
     c = check(R, T.shape[0], scale, bias, C_T, indices, offsets, weights, bound)
     return CheckedEb(R, C_T, c.flags, c.rsum, c.csum, c.robust)
 
 
 def campaign_table_flips(T, scale, bias, C_T, indices, offsets, weights, f_row, f_col, f_bit,
-                         bound: float = REL_BOUND) -> np.ndarray:
+                         bound: float = REL_BOUND, bits: int = 8) -> np.ndarray:
     """Section VI-B-2: per planted single-bit flip in the table (after C_T), the flags of the
     whole batch.  Returns int32 [n_flips, n_bags]."""
-    T = _table(T).copy()
+    T, d = _table(T, bits)
+    T = T.copy()
     scale, bias, weights = _f32(scale), _f32(bias), _f32(weights)
     C_T = np.ascontiguousarray(C_T, dtype=np.int32)
     indices, offsets = _bags(indices, offsets)
@@ -186,16 +189,16 @@ def campaign_table_flips(T, scale, bias, C_T, indices, offsets, weights, f_row, 
     f_bit = np.ascontiguousarray(f_bit, dtype=np.int32)
     n, n_bags = f_row.size, offsets.size - 1
     out = np.empty((n, n_bags), dtype=np.int32)
-    lib().eb_oracle_campaign_table_flips(_p(T, _u8p), T.shape[0], T.shape[1], _p(scale, _f32p), _p(bias, _f32p),
+    lib().eb_oracle_campaign_table_flips(_p(T, _u8p), T.shape[0], d, bits, _p(scale, _f32p), _p(bias, _f32p),
                                          _p(C_T, _i32p), _p(indices, _i64p), _p(offsets, _i64p), n_bags,
                                          _p(weights, _f32p), float(bound), _p(f_row, _i64p), _p(f_col, _i32p),
                                          _p(f_bit, _i32p), n, _p(out, _i32p))
     return out
 
 
-def roundoff_tolerance(T, scale, bias, indices, offsets, weights=None) -> np.ndarray:
+def roundoff_tolerance(T, scale, bias, indices, offsets, weights=None, bits: int = 8) -> np.ndarray:
     """Per bag, a bound on |R_f32[j] - R_f64[j]| for any column j and any order of summation:
-    (m + 3) * 2^-24 * sum_i (|a_i| * 255 + |b_i|), m the bag's length (standard forward error
+    (m + 3) * 2^-24 * sum_i (|a_i| * (2^bits - 1) + |b_i|), m the bag's length (standard forward error
     bound of a length-m float sum, plus the roundings of w*alpha, w*beta and the final add)."""
     scale, bias, weights = _f32(scale), _f32(bias), _f32(weights)
     indices, offsets = _bags(indices, offsets)
@@ -206,6 +209,6 @@ def roundoff_tolerance(T, scale, bias, indices, offsets, weights=None) -> np.nda
         ok = (idx >= 0) & (idx < len(scale))
         idx = idx[ok]
         w = np.ones(idx.size) if weights is None else weights[offsets[b]:offsets[b + 1]][ok].astype(np.float64)
-        mag = float(np.sum(np.abs(w * scale[idx].astype(np.float64)) * 255.0 + np.abs(w * bias[idx].astype(np.float64))))
+        mag = float(np.sum(np.abs(w * scale[idx].astype(np.float64)) * float(2 ** bits - 1) + np.abs(w * bias[idx].astype(np.float64))))
         tol[b] = (idx.size + 3) * 2.0 ** -24 * mag
     return tol

@@ -40,9 +40,16 @@ def rng_for(tag: int, rep: int = 0, stream: int = 0) -> np.random.Generator:
     return np.random.Generator(np.random.PCG64(EB_SEED_BASE + 1000 * tag + rep + 7919 * stream))
 
 
-def draw_table(rng: np.random.Generator, rows: int, d: int, regime: str):
-    """Row-wise quantized table: uint8 codes T[rows, d], float32 scale[rows], float32 bias[rows];
-    row i stands for the real vector scale[i] * T[i, :] + bias[i].
+def pack_nibbles(codes: np.ndarray) -> np.ndarray:
+    """4-bit codes [rows, d] (values 0..15) as bytes [rows, d/2]: the even column in the low half."""
+    return (codes[:, 0::2] | (codes[:, 1::2] << 4)).astype(np.uint8)
+
+
+def draw_table(rng: np.random.Generator, rows: int, d: int, regime: str, bits: int = 8):
+    """Row-wise quantized table: codes T, float32 scale[rows], float32 bias[rows]; row i stands for
+    the real vector scale[i] * code[i, :] + bias[i].  bits = 8: T is uint8 [rows, d]; bits = 4: codes
+    0..15 packed two per byte, T is uint8 [rows, d/2] (see pack_nibbles) and scales are 17 times larger
+    so that the values cover the same range.
 
     regime "uniform": codes uniform on [0, 255], scale uniform on [0.005, 0.02), bias uniform on
         [-0.5, 0): values of mostly one sign, as after a ReLU-like training range.
@@ -50,24 +57,25 @@ def draw_table(rng: np.random.Generator, rows: int, d: int, regime: str):
         (max - min) / 255, bias = min): values centred on zero.
     regime "integer": scale 1, bias 0 (the operator is then exact integer arithmetic).
     """
+    top = (1 << bits) - 1
     if regime == "uniform":
-        T = rng.integers(0, 256, size=(rows, d), dtype=np.uint8)
-        scale = rng.uniform(0.005, 0.02, size=rows).astype(np.float32)
+        T = rng.integers(0, top + 1, size=(rows, d), dtype=np.uint8)
+        scale = (rng.uniform(0.005, 0.02, size=rows) * (255 // top)).astype(np.float32)
         bias = rng.uniform(-0.5, 0.0, size=rows).astype(np.float32)
     elif regime == "gauss":
         x = rng.standard_normal(size=(rows, d)).astype(np.float32)
         lo, hi = x.min(axis=1), x.max(axis=1)
-        scale = ((hi - lo) / np.float32(255)).astype(np.float32)
+        scale = ((hi - lo) / np.float32(top)).astype(np.float32)
         scale[scale == 0] = np.float32(1)
         bias = lo.astype(np.float32)
-        T = np.clip(np.rint((x - bias[:, None]) / scale[:, None]), 0, 255).astype(np.uint8)
+        T = np.clip(np.rint((x - bias[:, None]) / scale[:, None]), 0, top).astype(np.uint8)
     elif regime == "integer":
-        T = rng.integers(0, 256, size=(rows, d), dtype=np.uint8)
+        T = rng.integers(0, top + 1, size=(rows, d), dtype=np.uint8)
         scale = np.ones(rows, dtype=np.float32)
         bias = np.zeros(rows, dtype=np.float32)
     else:
         raise ValueError(regime)
-    return T, scale, bias
+    return (T if bits == 8 else pack_nibbles(T)), scale, bias
 
 
 def draw_bags(rng: np.random.Generator, rows: int, n_bags: int, pooling: int, lengths: str = "spread"):
@@ -117,11 +125,13 @@ def make_inputs(wl: EbWorkload, tag: int = 0, rep: int = 0, lengths: str = "spre
     return EbInputs(wl, T, scale, bias, indices, offsets, weights)
 
 
-def draw_table_flips(rng: np.random.Generator, indices: np.ndarray, d: int, n: int, bits: str):
+def draw_table_flips(rng: np.random.Generator, indices: np.ndarray, d: int, n: int, bits: str, code_bits: int = 8):
     """Fault list of Section VI-B-2: single bit flips in table elements that the batch reads.
     Returns arrays (row, col, bit); the row is one of `indices` (uniform over positions), the
-    column uniform, the bit uniform over the upper ("high": 4..7) or lower ("low": 0..3) half."""
-    lo = {"high": 4, "low": 0}[bits]
+    column uniform, the bit uniform over the upper ("high") or lower ("low") half of the element's
+    code_bits bits (8-bit codes: 4..7 and 0..3)."""
+    half = code_bits // 2
+    lo = {"high": half, "low": 0}[bits]
     pos = rng.integers(0, indices.size, size=n)
     return indices[pos].astype(np.int64), rng.integers(0, d, size=n, dtype=np.int32), \
-        rng.integers(lo, lo + 4, size=n, dtype=np.int32)
+        rng.integers(lo, lo + half, size=n, dtype=np.int32)

@@ -187,3 +187,58 @@ def test_clean_runs_and_robust_band():
     out = eb.checked_eb(x.T, x.scale, x.bias, x.indices, x.offsets, x.weights)
     assert not out.flags.any() and out.robust.all()
     assert np.all(np.abs(out.rsum - out.csum) < 1e-6 * np.abs(out.csum))
+
+
+# ---- 4-bit tables (two codes per byte) ---------------------------------------------------------
+
+def unpack(Tp):
+    out = np.empty((Tp.shape[0], Tp.shape[1] * 2), dtype=np.uint8)
+    out[:, 0::2] = Tp & 15
+    out[:, 1::2] = Tp >> 4
+    return out
+
+
+def test_int4_equals_the_8bit_oracle_on_unpacked_codes():
+    """A 4-bit table is the 8-bit table of its unpacked codes: row sums, both precisions of the
+    lookup, Algorithm 2 and the flip campaign must agree (the 8-bit path is pinned above), and the
+    unpacking itself is pinned by hand-written bytes."""
+    Tp = np.array([[0x21, 0xF0], [0x0A, 0x37]], dtype=np.uint8)
+    assert unpack(Tp).tolist() == [[1, 2, 0, 15], [10, 0, 7, 3]]
+    assert eb.table_rowsums(Tp, bits=4).tolist() == [18, 20]
+    for seed, weighted in ((1, False), (2, True)):
+        rng = np.random.default_rng(seed)
+        Tp, scale, bias = w.draw_table(rng, 300, 64, "uniform", bits=4)
+        assert Tp.shape == (300, 32)
+        T8 = unpack(Tp)
+        assert T8.max() == 15
+        indices, offsets = w.draw_bags(rng, 300, 30, 20, "ragged")
+        weights = w.draw_weights(rng, indices.size) if weighted else None
+        assert np.array_equal(eb.table_rowsums(Tp, bits=4), eb.table_rowsums(T8))
+        for prec in ("f32", "f64"):
+            assert np.array_equal(eb.forward(Tp, scale, bias, indices, offsets, weights, prec, bits=4),
+                                  eb.forward(T8, scale, bias, indices, offsets, weights, prec))
+        a, c = eb.checked_eb(Tp, scale, bias, indices, offsets, weights, bits=4), eb.checked_eb(T8, scale, bias, indices, offsets, weights)
+        assert np.array_equal(a.flags, c.flags) and np.array_equal(a.csum, c.csum) and np.array_equal(a.rsum, c.rsum)
+        f_row, f_col, f_bit = w.draw_table_flips(rng, indices, 64, 30, "high", code_bits=4)
+        assert f_bit.min() >= 2 and f_bit.max() <= 3
+        C_T = eb.table_rowsums(T8)
+        assert np.array_equal(eb.campaign_table_flips(Tp, scale, bias, C_T, indices, offsets, weights, f_row, f_col, f_bit, bits=4),
+                              eb.campaign_table_flips(T8, scale, bias, C_T, indices, offsets, weights, f_row, f_col, f_bit))
+
+
+def test_int4_flip_changes_the_named_element_only():
+    rng = np.random.default_rng(4)
+    Tp, scale, bias = w.draw_table(rng, 50, 32, "integer", bits=4)
+    indices = np.arange(50, dtype=np.int64)
+    offsets = np.array([0, 50], dtype=np.int64)
+    C_T = eb.table_rowsums(Tp, bits=4)
+    base = eb.forward(Tp, scale, bias, indices, offsets, None, "f32", bits=4)[0]
+    for row, col, bit in ((3, 0, 0), (3, 1, 3), (49, 31, 2), (10, 16, 1)):
+        T2 = Tp.copy()
+        T2[row, col // 2] ^= np.uint8(1 << (bit + 4 * (col & 1)))
+        got = eb.forward(T2, scale, bias, indices, offsets, None, "f32", bits=4)[0]
+        diff = got - base
+        assert abs(diff[col]) == (1 << bit) and np.count_nonzero(diff) == 1
+        flags = eb.campaign_table_flips(Tp, scale, bias, C_T, indices, offsets, None, [row], [col], [bit], bits=4)
+        # RSum is about 50*32*7.5 = 12000: the bound 1e-5 is 0.12, every flip is caught
+        assert flags[0, 0] == 1
