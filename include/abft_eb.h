@@ -4,7 +4,7 @@
  *
  * The operation is Algorithm 2 of arXiv 2103.00130 ("ABFT for low-precision EB",
  * Section V) on the row-wise quantized EmbeddingBag of Section III-C: a table T of
- * 8-bit codes with one (scale, bias) pair per row; one lookup pools the rows named by
+ * 8-bit (or 4-bit) codes with one (scale, bias) pair per row; one lookup pools the rows named by
  * an index set I,
  *     R = sum_{i in I} scale[i] * T[i, :] + bias[i] * e_d          (optionally times a
  *     per-sample weight: the "weighted sum" of Section VI-A-2),
@@ -24,8 +24,8 @@
  *   - err <=> not (|RSum - CSum| <= rel_bound * max(|RSum|, |CSum|)), or the difference is
  *     not finite.  The paper's choice is rel_bound = 1e-5 (Section V, round-off bound).
  *   - the row sums travel inside the table: a row is one record
- *     [d codes][scale f32][bias f32][C_T i32][4 bytes unused], d + 16 bytes, so the check
- *     reads no memory the lookup does not already touch.
+ *     [d codes][scale f32][bias f32][C_T i32][4 bytes unused], d + 16 bytes for 8-bit codes, so
+ *     the check reads no memory the lookup does not already touch.
  *
  * Conventions are those of abft_gemm.h: device pointers unless a comment says "host",
  * `stream` a hipStream_t passed as void*, calls enqueue and return, error codes and
@@ -53,9 +53,11 @@ extern "C" {
 
 /* flags of abft_eb_pack_rowsum */
 #define ABFT_EB_PACK_COMPACT 0u       /* default: records of d + 16 bytes back to back */
-#define ABFT_EB_PACK_LINE_ALIGNED 1u  /* records of up to 128 bytes (d <= 64) get a power-of-two stride
-                                         (32, 64 or 128 bytes), so that no record straddles a 128-byte
-                                         memory line: fewer bytes fetched per lookup, a larger table */
+#define ABFT_EB_PACK_LINE_ALIGNED 1u  /* records of up to 128 bytes get a power-of-two stride (32, 64 or
+                                         128 bytes), so that no record straddles a 128-byte memory
+                                         line: fewer bytes fetched per lookup, a larger table */
+#define ABFT_EB_PACK_INT4 2u          /* T holds 4-bit codes, two per byte, the even column in the low
+                                         half (Section V, overhead analysis: p = 4 or 8 bits) */
 
 /* bits of bag_flags[b] */
 #define ABFT_EB_ERR 1          /* Algorithm 2's err: RSum and CSum differ by more than the bound */
@@ -65,24 +67,25 @@ extern "C" {
 typedef struct abft_eb_table abft_eb_table;
 
 /* Section V, "pre-computed row sums of T": build the table once.
- *   T      uint8 codes, rows x d row-major with ldt >= d
+ *   T      the codes, rows x (d * bits / 8) bytes row-major with ldt (bytes) at least that
  *   scale, bias   float32 [rows]
- *   d      16, 32, 64, 128, 256 or 512
+ *   d      columns; a row of codes must be 16, 32, 64, 128, 256 or 512 bytes
+ *          (d = 16 .. 512 for 8-bit codes, 32 .. 1024 for 4-bit codes, powers of two)
  *   out    host pointer receiving the handle
- *   flags  ABFT_EB_PACK_COMPACT or ABFT_EB_PACK_LINE_ALIGNED
- * Allocates rows * stride bytes with hipMalloc (stride = d + 16 unless line-aligned); the packing
+ *   flags  ABFT_EB_PACK_COMPACT, or ABFT_EB_PACK_LINE_ALIGNED and ABFT_EB_PACK_INT4 in any combination
+ * Allocates rows * stride bytes with hipMalloc (stride = code bytes + 16 unless line-aligned); the packing
  * kernel is enqueued on `stream` and the inputs must stay valid until it has run. */
 int abft_eb_pack_rowsum(const uint8_t* T, int64_t ldt, const float* scale, const float* bias, int64_t rows, int d,
                         unsigned flags, void* stream, abft_eb_table** out);
 
-/* rows, d and the record stride in bytes (host out-pointers, any may be NULL). */
-int abft_eb_table_dims(const abft_eb_table* Tp, int64_t* rows, int* d, int* record_bytes);
+/* rows, d, the record stride in bytes and the code width in bits (host out-pointers, any may be NULL). */
+int abft_eb_table_dims(const abft_eb_table* Tp, int64_t* rows, int* d, int* record_bytes, int* bits);
 
 /* Copy C_T (int32 [rows]; Section V) out of the records. */
 int abft_eb_table_get_rowsums(const abft_eb_table* Tp, int32_t* C_T, void* stream);
 
 /* Fault-injection hook (Section VI-B-2: a random bit of a random element is flipped): inverts
- * bit `bit` (0..7) of code T[row][col] inside the table and leaves C_T stale.  Calling it twice
+ * bit `bit` (0..7, or 0..3 for 4-bit codes) of code T[row][col] inside the table and leaves C_T stale.  Calling it twice
  * with the same arguments restores the table. */
 int abft_eb_table_flip_bit(abft_eb_table* Tp, int64_t row, int col, int bit, void* stream);
 

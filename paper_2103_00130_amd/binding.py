@@ -34,7 +34,7 @@ EXPORTS_EB = (
 ABFT_EB_CHECK, ABFT_EB_NOCHECK = 0, 1
 ABFT_EB_VARIANT_BATCH, ABFT_EB_VARIANT_GROUP = 0x100, 0x200
 ABFT_EB_ERR, ABFT_EB_BAD_INDEX = 1, 2
-ABFT_EB_PACK_COMPACT, ABFT_EB_PACK_LINE_ALIGNED = 0, 1
+ABFT_EB_PACK_COMPACT, ABFT_EB_PACK_LINE_ALIGNED, ABFT_EB_PACK_INT4 = 0, 1, 2
 
 
 class abft_requant_t(ctypes.Structure):
@@ -81,7 +81,7 @@ def _load() -> ctypes.CDLL:
     L.abft_recompute_flagged_rows.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64,
                                               i32, vp, sz, vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.abft_eb_pack_rowsum.argtypes = [vp, i64, vp, vp, i64, i32, u32, vp, ctypes.POINTER(vp)]
-    L.abft_eb_table_dims.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.abft_eb_table_dims.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.abft_eb_table_get_rowsums.argtypes = [vp, vp, vp]
     L.abft_eb_table_flip_bit.argtypes = [vp, i64, i32, i32, vp]
     L.abft_eb_table_destroy.argtypes = [vp]
@@ -300,10 +300,12 @@ class EbTable:
 
 
 def abft_eb_pack_rowsum(T: torch.Tensor, scale: torch.Tensor, bias: torch.Tensor, flags: int = 0, stream=None) -> EbTable:
-    """T: uint8 device tensor rows x d; scale, bias: float32 [rows]."""
+    """T: uint8 device tensor, rows x d codes (rows x d/2 bytes with ABFT_EB_PACK_INT4); scale, bias: float32 [rows]."""
     ptr = _ptr(T, torch.uint8, "T")
     ldt = _ld(T, "T")
     rows, d = T.shape
+    if flags & ABFT_EB_PACK_INT4:
+        d *= 2
     if scale.numel() != rows or bias.numel() != rows or not scale.is_contiguous() or not bias.is_contiguous():
         raise ValueError("scale and bias must be contiguous with one entry per table row")
     out = ctypes.c_void_p()
@@ -313,9 +315,9 @@ def abft_eb_pack_rowsum(T: torch.Tensor, scale: torch.Tensor, bias: torch.Tensor
 
 
 def abft_eb_table_dims(Tp: EbTable):
-    rows, d, rec = ctypes.c_int64(), ctypes.c_int(), ctypes.c_int()
-    _check(lib.abft_eb_table_dims(Tp.handle, ctypes.byref(rows), ctypes.byref(d), ctypes.byref(rec)))
-    return rows.value, d.value, rec.value
+    rows, d, rec, bits = ctypes.c_int64(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(lib.abft_eb_table_dims(Tp.handle, ctypes.byref(rows), ctypes.byref(d), ctypes.byref(rec), ctypes.byref(bits)))
+    return rows.value, d.value, rec.value, bits.value
 
 
 def abft_eb_table_get_rowsums(Tp: EbTable, C_T: torch.Tensor, stream=None):

@@ -4,11 +4,13 @@
 // The work is a gather: every pooled row is read once from a table far larger than any
 // cache, so the kernels are built around bytes in flight, not arithmetic.
 //
-//  * The table is kept as fused records [d codes][scale][bias][C_T][unused]: the row sum that
+//  * Codes are 8 bits wide, or 4 bits wide and packed two per byte (Section V: p = 4 or 8); the
+//    kernels are templated on the width and differ only in how a code is cut out of its word.
+//  * The table is kept as fused records [codes][scale][bias][C_T][unused]: the row sum that
 //    Eq. 4 needs arrives in the same memory transaction as the scale and bias the lookup needs
 //    anyway, so the check adds no memory traffic at all.
-//  * Batch kernel (large batches): d/16 lanes per lookup, every lane owns 16 columns and reads
-//    16 code bytes per pooled row straight into registers, eight rows in flight per lane; the
+//  * Batch kernel (large batches): one lane per 16 code bytes of a row; every lane owns their columns and reads
+//    those 16 code bytes per pooled row straight into registers, eight rows in flight per lane; the
 //    chip is filled by lookups, and the lanes of a lookup walk its index list in order.
 //  * Group kernel (small batches): one workgroup per lookup.  All threads fetch different 16-byte
 //    pieces of the lookup's records into LDS (1024 pieces in flight per workgroup), then the
@@ -24,10 +26,12 @@
 #include "abft_internal.h"
 
 struct abft_eb_table {
-    uint8_t* rec;    // rows * stride bytes
+    uint8_t* rec;    // rows * stride bytes: [codes][scale f32][bias f32][C_T i32][unused]
     int64_t rows;
-    int64_t stride;  // d + 16, or the next power of two when the records are line-aligned
-    int d;
+    int64_t stride;  // code bytes + 16, or the next power of two when the records are line-aligned
+    int d;           // columns
+    int bits;        // 8 or 4 bits per code
+    int code_bytes;  // d * bits / 8
     int device;
 };
 
@@ -70,22 +74,25 @@ __device__ inline int compare_sums(double rs, double cs, double bound) {
     return (!(diff <= bound * fmax(fabs(rs), fabs(cs))) || !(diff < (double)INFINITY)) ? ABFT_EB_ERR : 0;
 }
 
-// 16 columns of one pooled row: acc[k] = a * code[k] + acc[k]
-__device__ inline void fma16(float (&acc)[16], float a, v4u q) {
+// the columns held by 16 code bytes of one pooled row: acc[k] = a * code[k] + acc[k].
+// 8-bit codes: 16 columns; 4-bit codes: 32 columns, the even column in the low half of its byte.
+template <int BITS>
+__device__ inline void fma_codes(float (&acc)[128 / BITS], float a, v4u q) {
+    constexpr int PER_WORD = 32 / BITS;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        acc[4 * w + 0] = __builtin_fmaf(a, (float)(q[w] & 0xffu), acc[4 * w + 0]);
-        acc[4 * w + 1] = __builtin_fmaf(a, (float)((q[w] >> 8) & 0xffu), acc[4 * w + 1]);
-        acc[4 * w + 2] = __builtin_fmaf(a, (float)((q[w] >> 16) & 0xffu), acc[4 * w + 2]);
-        acc[4 * w + 3] = __builtin_fmaf(a, (float)(q[w] >> 24), acc[4 * w + 3]);
-    }
+    for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int n = 0; n < PER_WORD; ++n)
+            acc[PER_WORD * w + n] = __builtin_fmaf(a, (float)((q[w] >> (BITS * n)) & ((1u << BITS) - 1u)), acc[PER_WORD * w + n]);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Batch kernel: G = d/16 lanes per lookup.
-template <int G, bool kCheck, bool kWeighted>
+// Batch kernel: G lanes per lookup, one per 16 code bytes of a row.
+template <int G, int BITS, bool kCheck, bool kWeighted>
 __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
-    constexpr int D = 16 * G, U = 8;
+    constexpr int CB = 16 * G;            // code bytes per row
+    constexpr int CPP = 128 / BITS;       // columns per 16-byte piece
+    constexpr int D = G * CPP, U = 8;
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t bag = t / G;
     const int piece = (int)(t % G);
@@ -93,9 +100,9 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
     int64_t beg, end;
     bag_range(p, bag, &beg, &end);
 
-    float acc[16];
+    float acc[CPP];
 #pragma unroll
-    for (int k = 0; k < 16; ++k) acc[k] = 0.0f;
+    for (int k = 0; k < CPP; ++k) acc[k] = 0.0f;
     float beta_sum = 0.0f;
     double cs = 0.0;
     int flag = 0;
@@ -123,7 +130,7 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
             if (in && !ok[u]) flag |= ABFT_EB_BAD_INDEX;
             const uint8_t* r = base + (ok[u] ? idx[u] : 0) * p.stride;
             q[u] = *reinterpret_cast<const v4u*>(r);
-            tl[u] = *reinterpret_cast<const v4u*>(r + (D - piece * 16));
+            tl[u] = *reinterpret_cast<const v4u*>(r + (CB - piece * 16));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -134,7 +141,7 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
             }
             a = ok[u] ? a : 0.0f;
             c = ok[u] ? c : 0.0f;
-            fma16(acc, a, q[u]);
+            fma_codes<BITS>(acc, a, q[u]);
             beta_sum = beta_sum + c;
             if (kCheck) {
                 // Eq. 4, the term of one pooled row: scale * C_T + d * bias, rounded once (both products
@@ -144,10 +151,10 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
         }
     }
 
-    float* const out = p.R + bag * p.ldr + piece * 16;
+    float* const out = p.R + bag * p.ldr + piece * CPP;
     double rs = 0.0;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < CPP / 4; ++w) {
         v4f v;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -178,15 +185,17 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
 //  3. pooling, rows in index order: threads own columns and do one LDS read, one convert and one
 //     fused multiply-add per row; meanwhile the last two wavefronts walk the chains that do not
 //     depend on the column (sum of biases, CSum).
-template <int G, bool kCheck, bool kWeighted>
+template <int G, int BITS, bool kCheck, bool kWeighted>
 __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
-    constexpr int D = 16 * G, REC = D + 16;   // REC: a record as staged in LDS (no padding there)
+    constexpr int CB = 16 * G;                 // code bytes per row
+    constexpr int D = CB * 8 / BITS, REC = CB + 16;   // REC: a record as staged in LDS (no padding there)
     constexpr int P = G + 1;                   // 16-byte pieces per record
     constexpr int NL = G >= 16 ? 8 : 4;        // load instructions per thread and chunk
     constexpr int PIECES = NL * 256;
     constexpr int ROWS = PIECES / P;           // whole records per chunk
     constexpr int NW = (ROWS + 255) / 256;     // rows per thread in the per-row pass
-    constexpr int CPL = D > 256 ? D / 256 : 1;  // columns per thread in the pooling phase
+    constexpr int BPT = CB > 256 ? CB / 256 : 1;  // code bytes per thread in the pooling phase
+    constexpr int CPL = BPT * 8 / BITS;           // columns per thread
     __shared__ v4u s_rec[PIECES];
     __shared__ float s_a[ROWS], s_c[ROWS];
     __shared__ double s_t[kCheck ? ROWS : 1];
@@ -204,7 +213,7 @@ __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
     for (int k = 0; k < CPL; ++k) acc[k] = 0.0f;
     float beta_sum = 0.0f;
     double cs = 0.0;
-    const bool col_thread = tid * CPL < D;
+    const bool col_thread = tid * BPT < CB;
     // the chains that do not depend on the column run on wavefronts that own few or no columns
     const bool beta_wave = wave == 2, cs_wave = wave == 3;
     const uint8_t* const s_bytes = reinterpret_cast<const uint8_t*>(s_rec);
@@ -268,10 +277,10 @@ __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
 #pragma unroll 8
             for (int r = 0; r < n; ++r) {
                 const float a = s_a[r];
-                const uint8_t* codes = s_bytes + r * REC + tid * CPL;
-                unsigned int cw = CPL == 1 ? (unsigned int)*codes : (unsigned int)*reinterpret_cast<const uint16_t*>(codes);
+                const uint8_t* codes = s_bytes + r * REC + tid * BPT;
+                unsigned int cw = BPT == 1 ? (unsigned int)*codes : (unsigned int)*reinterpret_cast<const uint16_t*>(codes);
 #pragma unroll
-                for (int k = 0; k < CPL; ++k) acc[k] = __builtin_fmaf(a, (float)((cw >> (8 * k)) & 0xffu), acc[k]);
+                for (int k = 0; k < CPL; ++k) acc[k] = __builtin_fmaf(a, (float)((cw >> (BITS * k)) & ((1u << BITS) - 1u)), acc[k]);
             }
         }
         if (beta_wave) {
@@ -313,13 +322,13 @@ __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
     }
 }
 
-template <int G>
+template <int G, int BITS>
 hipError_t launch_g(bool group, bool check, bool weighted, const EbParams& p, hipStream_t s) {
-#define ABFT_EB_LAUNCH(CK, WT)                                                                         \
-    do {                                                                                               \
-        if (group) eb_group_kernel<G, CK, WT><<<dim3((unsigned)p.n_bags), dim3(256), 0, s>>>(p);          \
-        else eb_batch_kernel<G, CK, WT><<<dim3((unsigned)((p.n_bags * G + 255) / 256)), dim3(256), 0, s>>>(p); \
-        return hipGetLastError();                                                                      \
+#define ABFT_EB_LAUNCH(CK, WT)                                                                                     \
+    do {                                                                                                           \
+        if (group) eb_group_kernel<G, BITS, CK, WT><<<dim3((unsigned)p.n_bags), dim3(256), 0, s>>>(p);             \
+        else eb_batch_kernel<G, BITS, CK, WT><<<dim3((unsigned)((p.n_bags * G + 255) / 256)), dim3(256), 0, s>>>(p); \
+        return hipGetLastError();                                                                                  \
     } while (0)
     if (check && weighted) ABFT_EB_LAUNCH(true, true);
     if (check) ABFT_EB_LAUNCH(true, false);
@@ -328,24 +337,30 @@ hipError_t launch_g(bool group, bool check, bool weighted, const EbParams& p, hi
 #undef ABFT_EB_LAUNCH
 }
 
-hipError_t launch_eb(int d, bool group, bool check, bool weighted, const EbParams& p, hipStream_t s) {
-    switch (d) {
-        case 16: return launch_g<1>(group, check, weighted, p, s);
-        case 32: return launch_g<2>(group, check, weighted, p, s);
-        case 64: return launch_g<4>(group, check, weighted, p, s);
-        case 128: return launch_g<8>(group, check, weighted, p, s);
-        case 256: return launch_g<16>(group, check, weighted, p, s);
-        case 512: return launch_g<32>(group, check, weighted, p, s);
+template <int BITS>
+hipError_t launch_bits(int code_bytes, bool group, bool check, bool weighted, const EbParams& p, hipStream_t s) {
+    switch (code_bytes) {
+        case 16: return launch_g<1, BITS>(group, check, weighted, p, s);
+        case 32: return launch_g<2, BITS>(group, check, weighted, p, s);
+        case 64: return launch_g<4, BITS>(group, check, weighted, p, s);
+        case 128: return launch_g<8, BITS>(group, check, weighted, p, s);
+        case 256: return launch_g<16, BITS>(group, check, weighted, p, s);
+        case 512: return launch_g<32, BITS>(group, check, weighted, p, s);
     }
     return hipErrorNotSupported;
+}
+
+hipError_t launch_eb(int code_bytes, int bits, bool group, bool check, bool weighted, const EbParams& p, hipStream_t s) {
+    return bits == 4 ? launch_bits<4>(code_bytes, group, check, weighted, p, s)
+                     : launch_bits<8>(code_bytes, group, check, weighted, p, s);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Table build (Section V: row sums computed once), and the small helpers.
 // One thread per 16-byte piece of a record; the thread of the tail piece sums the row's codes.
 __global__ __launch_bounds__(256) void eb_pack_kernel(const uint8_t* T, int64_t ldt, const float* scale, const float* bias,
-                                                      int64_t rows, int d, uint8_t* rec, int64_t stride) {
-    const int P = d / 16 + 1;
+                                                      int64_t rows, int code_bytes, int bits, uint8_t* rec, int64_t stride) {
+    const int P = code_bytes / 16 + 1;
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t row = t / P;
     const int pc = (int)(t - row * P);
@@ -362,7 +377,7 @@ __global__ __launch_bounds__(256) void eb_pack_kernel(const uint8_t* T, int64_t 
         }
     } else {
         int32_t sum = 0;
-        for (int j = 0; j < d; ++j) sum += src[j];
+        for (int j = 0; j < code_bytes; ++j) sum += bits == 8 ? (int)src[j] : (int)(src[j] & 15) + (int)(src[j] >> 4);
         out[0] = __builtin_bit_cast(unsigned int, scale[row]);
         out[1] = __builtin_bit_cast(unsigned int, bias[row]);
         out[2] = (unsigned int)sum;
@@ -371,9 +386,9 @@ __global__ __launch_bounds__(256) void eb_pack_kernel(const uint8_t* T, int64_t 
     *reinterpret_cast<v4u*>(rec + row * stride + pc * 16) = out;
 }
 
-__global__ __launch_bounds__(256) void eb_get_rowsums_kernel(const uint8_t* rec, int64_t stride, int64_t rows, int d, int32_t* C_T) {
+__global__ __launch_bounds__(256) void eb_get_rowsums_kernel(const uint8_t* rec, int64_t stride, int64_t rows, int code_bytes, int32_t* C_T) {
     const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (row < rows) C_T[row] = *reinterpret_cast<const int32_t*>(rec + row * stride + d + 8);
+    if (row < rows) C_T[row] = *reinterpret_cast<const int32_t*>(rec + row * stride + code_bytes + 8);
 }
 
 __global__ void eb_flip_kernel(uint8_t* rec, int64_t off, int bit) {
@@ -395,26 +410,30 @@ int abft_eb_pack_rowsum(const uint8_t* T, int64_t ldt, const float* scale, const
                         unsigned flags, void* stream, abft_eb_table** out) {
     if (!T || !scale || !bias || !out) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: null pointer");
     if (rows < 1) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: rows=%lld must be >= 1", (long long)rows);
-    if (d != 16 && d != 32 && d != 64 && d != 128 && d != 256 && d != 512)
-        return abft::set_error(ABFT_EUNSUPPORTED, "abft_eb_pack_rowsum: d=%d (supported: 16, 32, 64, 128, 256, 512)", d);
-    if (ldt < d) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: ldt=%lld smaller than d=%d", (long long)ldt, d);
-    if (flags & ~ABFT_EB_PACK_LINE_ALIGNED) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: unknown flag bits %#x", flags);
+    if (flags & ~(ABFT_EB_PACK_LINE_ALIGNED | ABFT_EB_PACK_INT4)) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: unknown flag bits %#x", flags);
+    const int bits = (flags & ABFT_EB_PACK_INT4) ? 4 : 8;
+    const int code_bytes = d > 0 && d <= 4096 && (d * bits) % 8 == 0 ? d * bits / 8 : 0;
+    if (code_bytes != 16 && code_bytes != 32 && code_bytes != 64 && code_bytes != 128 && code_bytes != 256 && code_bytes != 512)
+        return abft::set_error(ABFT_EUNSUPPORTED, "abft_eb_pack_rowsum: d=%d with %d-bit codes (supported: rows of 16, 32, 64, 128, 256 or 512 bytes)", d, bits);
+    if (ldt < code_bytes) return abft::set_error(ABFT_EINVAL, "abft_eb_pack_rowsum: ldt=%lld smaller than a row of %d bytes", (long long)ldt, code_bytes);
     // line-aligned: records of up to 128 bytes get a power-of-two stride, so none of them straddles a 128-byte line
-    int64_t stride = d + 16;
+    int64_t stride = code_bytes + 16;
     if ((flags & ABFT_EB_PACK_LINE_ALIGNED) && stride <= 128) stride = stride <= 32 ? 32 : (stride <= 64 ? 64 : 128);
-    const int64_t pieces = rows * (d / 16 + 1);
+    const int64_t pieces = rows * (code_bytes / 16 + 1);
     if ((pieces + 255) / 256 > 0x7fffffffll) return abft::set_error(ABFT_EUNSUPPORTED, "abft_eb_pack_rowsum: table too large");
     abft_eb_table* h = new (std::nothrow) abft_eb_table();
     if (!h) return abft::set_error(ABFT_EHIP, "abft_eb_pack_rowsum: out of host memory");
     std::memset(h, 0, sizeof *h);
     h->rows = rows;
     h->d = d;
+    h->bits = bits;
+    h->code_bytes = code_bytes;
     h->stride = stride;
     hipError_t e = hipGetDevice(&h->device);
     if (e == hipSuccess) e = hipMalloc(&h->rec, (size_t)rows * (size_t)stride);
     if (e == hipSuccess) {
         abft::eb_pack_kernel<<<dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
-            T, ldt, scale, bias, rows, d, h->rec, stride);
+            T, ldt, scale, bias, rows, code_bytes, bits, h->rec, stride);
         e = hipGetLastError();
     }
     if (e != hipSuccess) {
@@ -426,27 +445,31 @@ int abft_eb_pack_rowsum(const uint8_t* T, int64_t ldt, const float* scale, const
     return ABFT_OK;
 }
 
-int abft_eb_table_dims(const abft_eb_table* Tp, int64_t* rows, int* d, int* record_bytes) {
+int abft_eb_table_dims(const abft_eb_table* Tp, int64_t* rows, int* d, int* record_bytes, int* bits) {
     if (!Tp) return abft::set_error(ABFT_EINVAL, "abft_eb_table_dims: null handle");
     if (rows) *rows = Tp->rows;
     if (d) *d = Tp->d;
     if (record_bytes) *record_bytes = (int)Tp->stride;
+    if (bits) *bits = Tp->bits;
     return ABFT_OK;
 }
 
 int abft_eb_table_get_rowsums(const abft_eb_table* Tp, int32_t* C_T, void* stream) {
     if (!Tp || !C_T) return abft::set_error(ABFT_EINVAL, "abft_eb_table_get_rowsums: null pointer");
     abft::eb_get_rowsums_kernel<<<dim3((unsigned)((Tp->rows + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
-        Tp->rec, Tp->stride, Tp->rows, Tp->d, C_T);
+        Tp->rec, Tp->stride, Tp->rows, Tp->code_bytes, C_T);
     HIP_TRY(hipGetLastError());
     return ABFT_OK;
 }
 
 int abft_eb_table_flip_bit(abft_eb_table* Tp, int64_t row, int col, int bit, void* stream) {
     if (!Tp) return abft::set_error(ABFT_EINVAL, "abft_eb_table_flip_bit: null handle");
-    if (row < 0 || row >= Tp->rows || col < 0 || col >= Tp->d || bit < 0 || bit > 7)
+    if (row < 0 || row >= Tp->rows || col < 0 || col >= Tp->d || bit < 0 || bit >= Tp->bits)
         return abft::set_error(ABFT_EINVAL, "abft_eb_table_flip_bit: row=%lld col=%d bit=%d outside the table", (long long)row, col, bit);
-    abft::eb_flip_kernel<<<dim3(1), dim3(64), 0, (hipStream_t)stream>>>(Tp->rec, row * Tp->stride + col, bit);
+    // a 4-bit code of an odd column sits in the high half of its byte
+    const int64_t off = row * Tp->stride + (Tp->bits == 8 ? col : col / 2);
+    const int pos = Tp->bits == 8 ? bit : bit + 4 * (col & 1);
+    abft::eb_flip_kernel<<<dim3(1), dim3(64), 0, (hipStream_t)stream>>>(Tp->rec, off, pos);
     HIP_TRY(hipGetLastError());
     return ABFT_OK;
 }
@@ -475,7 +498,7 @@ int abft_eb_u8_checked(const abft_eb_table* Tp, const int64_t* indices, int64_t 
     const unsigned variant = flags & ABFT_EB_VARIANT_MASK;
     if (variant != 0 && variant != ABFT_EB_VARIANT_BATCH && variant != ABFT_EB_VARIANT_GROUP)
         return abft::set_error(ABFT_EINVAL, "%s: unknown variant %#x", fn, variant);
-    const int G = Tp->d / 16;
+    const int G = Tp->code_bytes / 16;
     if (n_bags > 0x7fffffffll || (n_bags * G + 255) / 256 > 0x7fffffffll)
         return abft::set_error(ABFT_EUNSUPPORTED, "%s: n_bags=%lld too large for one launch", fn, (long long)n_bags);
     // the batch kernel needs enough lookups to fill the chip with lanes; below that one workgroup per lookup
@@ -498,7 +521,7 @@ int abft_eb_u8_checked(const abft_eb_table* Tp, const int64_t* indices, int64_t 
     p.rsum = check ? rsum : nullptr;
     p.csum = check ? csum : nullptr;
     p.bound = rel_bound;
-    HIP_TRY(abft::launch_eb(Tp->d, group, check, weights != nullptr, p, (hipStream_t)stream));
+    HIP_TRY(abft::launch_eb(Tp->code_bytes, Tp->bits, group, check, weights != nullptr, p, (hipStream_t)stream));
     return ABFT_OK;
 }
 

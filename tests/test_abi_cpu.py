@@ -70,8 +70,9 @@ def test_eb_bad_arguments_are_rejected_on_the_host(binding):
     assert L.abft_eb_pack_rowsum(dummy, 32, dummy, dummy, 10, 64, 0, None, ctypes.byref(out)) == binding.ABFT_EINVAL  # ldt < d
     assert L.abft_eb_pack_rowsum(dummy, 100, dummy, dummy, 10, 100, 0, None, ctypes.byref(out)) == binding.ABFT_EUNSUPPORTED
     assert b"d=100" in L.abft_last_error()
-    assert L.abft_eb_pack_rowsum(dummy, 64, dummy, dummy, 10, 64, 6, None, ctypes.byref(out)) == binding.ABFT_EINVAL  # unknown flag
-    assert L.abft_eb_table_dims(None, None, None, None) == binding.ABFT_EINVAL
+    assert L.abft_eb_pack_rowsum(dummy, 64, dummy, dummy, 10, 64, 12, None, ctypes.byref(out)) == binding.ABFT_EINVAL  # unknown flag
+    assert L.abft_eb_pack_rowsum(dummy, 64, dummy, dummy, 10, 16, 2, None, ctypes.byref(out)) == binding.ABFT_EUNSUPPORTED  # 8 bytes a row
+    assert L.abft_eb_table_dims(None, None, None, None, None) == binding.ABFT_EINVAL
     assert L.abft_eb_table_get_rowsums(None, dummy, None) == binding.ABFT_EINVAL
     assert L.abft_eb_table_flip_bit(None, 0, 0, 0, None) == binding.ABFT_EINVAL
     assert L.abft_eb_u8_checked(None, dummy, 0, dummy, 0, None, dummy, 64, dummy, None, None, 1e-5, 0, None) == binding.ABFT_EINVAL

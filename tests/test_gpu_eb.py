@@ -30,9 +30,10 @@ def dev(a):
 
 
 class GpuTable:
-    def __init__(self, b, T, scale, bias, aligned=False):
+    def __init__(self, b, T, scale, bias, aligned=False, bits=8):
         self.b = b
-        self.Tp = b.abft_eb_pack_rowsum(dev(T), dev(scale), dev(bias), b.ABFT_EB_PACK_LINE_ALIGNED if aligned else 0)
+        self.Tp = b.abft_eb_pack_rowsum(dev(T), dev(scale), dev(bias), (b.ABFT_EB_PACK_LINE_ALIGNED if aligned else 0) |
+                                        (b.ABFT_EB_PACK_INT4 if bits == 4 else 0))
         torch.cuda.synchronize()
 
     def rowsums(self):
@@ -61,15 +62,15 @@ def same_bits(x, y):
     return np.array_equal(np.ascontiguousarray(x).view(np.uint32), np.ascontiguousarray(y).view(np.uint32))
 
 
-def compare(out, ref, T, scale, bias, indices, offsets, weights, exact_nan=False):
+def compare(out, ref, T, scale, bias, indices, offsets, weights, bits=8):
     assert same_bits(out["R"], ref.R), "R differs from the oracle's float evaluation"
     assert np.array_equal(out["csum"].view(np.uint64), ref.csum.view(np.uint64)), "CSum differs"
     fin = np.isfinite(ref.rsum)
     assert np.allclose(out["rsum"][fin], ref.rsum[fin], rtol=1e-13, atol=0)
     assert ref.robust.all(), "seed gives a comparison that depends on summation order; pick another"
     assert np.array_equal(out["flags"], ref.flags)
-    R64 = eb.forward(T, scale, bias, indices, offsets, weights, "f64")
-    tol = eb.roundoff_tolerance(T, scale, bias, indices, offsets, weights)
+    R64 = eb.forward(T, scale, bias, indices, offsets, weights, "f64", bits)
+    tol = eb.roundoff_tolerance(T, scale, bias, indices, offsets, weights, bits)
     ok = np.isfinite(R64)
     assert np.all(np.abs(out["R"].astype(np.float64) - R64)[ok] <= (tol[:, None] + np.zeros_like(R64))[ok] + 1e-30)
 
@@ -89,7 +90,7 @@ def test_eb_matches_oracle(b, d, variant):
         aligned = regime == "gauss"     # one of the three passes runs on line-aligned records
         g = GpuTable(b, T, scale, bias, aligned)
         stride = {16: 32, 32: 64, 64: 128}.get(d, d + 16) if aligned else d + 16
-        assert b.abft_eb_table_dims(g.Tp) == (3000, d, stride)
+        assert b.abft_eb_table_dims(g.Tp) == (3000, d, stride, 8)
         assert np.array_equal(g.rowsums(), eb.table_rowsums(T))
         ref = eb.checked_eb(T, scale, bias, indices, offsets, weights)
         out = g.run(indices, offsets, weights, variant)
@@ -235,3 +236,38 @@ def test_table1_shapes_full_size(b, d):
     for wts in (None, weights):
         ref = eb.checked_eb(x.T, x.scale, x.bias, indices, offsets, wts, C_T=C_T)
         compare(g.run(indices, offsets, wts), ref, x.T, x.scale, x.bias, indices, offsets, wts)
+
+
+@pytest.mark.parametrize("d", [32, 64, 128, 256, 512, 1024])
+@pytest.mark.parametrize("variant", ["batch", "group"])
+def test_int4_tables_match_oracle(b, d, variant):
+    """4-bit codes, two per byte: same bar as the 8-bit tables, plus flips of each of the four bits of
+    codes in even and odd columns."""
+    for weighted, regime, lengths, aligned in ((False, "uniform", "spread", False), (True, "gauss", "ragged", True)):
+        rng = w.rng_for(200 + d, 0, int(weighted))
+        T, scale, bias = w.draw_table(rng, 2000, d, regime, bits=4)
+        assert T.shape == (2000, d // 2)
+        indices, offsets = w.draw_bags(rng, 2000, 100, 40, lengths)
+        extra = rng.integers(0, 2000, size=1300, dtype=np.int64)
+        indices = np.concatenate([indices, extra])
+        offsets = np.concatenate([offsets, [indices.size]]).astype(np.int64)
+        weights = w.draw_weights(rng, indices.size) if weighted else None
+        g = GpuTable(b, T, scale, bias, aligned, bits=4)
+        stride = {16: 32, 32: 64, 64: 128}.get(d // 2, d // 2 + 16) if aligned else d // 2 + 16
+        assert b.abft_eb_table_dims(g.Tp) == (2000, d, stride, 4)
+        C_T = eb.table_rowsums(T, bits=4)
+        assert np.array_equal(g.rowsums(), C_T)
+        ref = eb.checked_eb(T, scale, bias, indices, offsets, weights, bits=4)
+        compare(g.run(indices, offsets, weights, variant), ref, T, scale, bias, indices, offsets, weights, bits=4)
+        for col, bit in ((0, 0), (1, 3), (d - 1, 2), (d // 2, 1)):
+            row = int(indices[offsets[-2] + 5])
+            b.abft_eb_table_flip_bit(g.Tp, row, col, bit)
+            T2 = T.copy()
+            T2[row, col // 2] ^= np.uint8(1 << (bit + 4 * (col & 1)))
+            ref = eb.checked_eb(T2, scale, bias, indices, offsets, weights, C_T=C_T, bits=4)
+            out = g.run(indices, offsets, weights, variant)
+            assert same_bits(out["R"], ref.R)
+            assert np.array_equal(out["flags"][ref.robust], ref.flags[ref.robust])
+            b.abft_eb_table_flip_bit(g.Tp, row, col, bit)
+        with pytest.raises(b.AbftError):
+            b.abft_eb_table_flip_bit(g.Tp, 0, 0, 4)     # a 4-bit code has bits 0..3
