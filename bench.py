@@ -258,13 +258,14 @@ EB_TABLE_MIN_BYTES = 2 << 30
 
 
 class EbJob:
-    def __init__(self, b, torch, wl, max_sets=2048, aligned=False):
+    def __init__(self, b, torch, wl, max_sets=2048, aligned=False, bits=8):
         import numpy as np
         from paper_2103_00130_amd import eb_workloads as ew
         self.b, self.torch, self.wl = b, torch, wl
-        rec = wl.d + 16
+        self.bits = bits
+        rec = wl.d * bits // 8 + 16
         rng = ew.rng_for(900 + wl.d)
-        self.T, self.scale, self.bias = ew.draw_table(rng, wl.rows, wl.d, wl.regime)
+        self.T, self.scale, self.bias = ew.draw_table(rng, wl.rows, wl.d, wl.regime, bits)
         copies = max(1, -(-EB_TABLE_MIN_BYTES // (wl.rows * rec)))
         self.rows_big = wl.rows * copies
         T = torch.from_numpy(self.T).cuda().repeat(copies, 1)
@@ -272,7 +273,8 @@ class EbJob:
         bias = torch.from_numpy(self.bias).cuda().repeat(copies)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        self.Tp = b.abft_eb_pack_rowsum(T, scale, bias, b.ABFT_EB_PACK_LINE_ALIGNED if aligned else b.ABFT_EB_PACK_COMPACT)
+        self.Tp = b.abft_eb_pack_rowsum(T, scale, bias, (b.ABFT_EB_PACK_LINE_ALIGNED if aligned else b.ABFT_EB_PACK_COMPACT) |
+                                        (b.ABFT_EB_PACK_INT4 if bits == 4 else 0))
         torch.cuda.synchronize()
         self.pack_ms = (time.perf_counter() - t0) * 1e3
         del T
@@ -333,12 +335,12 @@ class EbJob:
         """The CPU oracle on the 4,000,000-row table with the same index sets folded into it."""
         from oracle import eb_oracle as oracle
         wl = self.wl
-        C_T = oracle.table_rowsums(self.T)
+        C_T = oracle.table_rowsums(self.T, self.bits)
         t0 = time.perf_counter()
         n = 0
         while True:
             indices, offsets, weights = self.host_sets[n % len(self.host_sets)]
-            oracle.checked_eb(self.T, self.scale, self.bias, indices % wl.rows, offsets, weights, C_T=C_T)
+            oracle.checked_eb(self.T, self.scale, self.bias, indices % wl.rows, offsets, weights, C_T=C_T, bits=self.bits)
             n += 1
             dt = time.perf_counter() - t0
             if dt > target_s or n >= 4 * len(self.host_sets):
@@ -348,12 +350,13 @@ class EbJob:
                 "sample": f"{n} calls of the oracle (lookup in float, RSum, CSum, comparison; row sums precomputed), {dt:.1f} s wall"}
 
 
-def measure_eb(b, torch, wl, cpu=True, aligned=False):
-    job = EbJob(b, torch, wl, aligned=aligned)
+def measure_eb(b, torch, wl, cpu=True, aligned=False, bits=8):
+    job = EbJob(b, torch, wl, aligned=aligned, bits=bits)
     us_c = min(job.time_calls(True), job.time_calls(True))
     us_u = min(job.time_calls(False), job.time_calls(False))
     res = {
-        "workload": wl.name + ("_line_aligned" if aligned else ""), "rows": wl.rows, "d": wl.d,
+        "workload": wl.name + ("_int4" if bits == 4 else "") + ("_line_aligned" if aligned else ""), "rows": wl.rows, "d": wl.d,
+        "code_bits": bits,
         "record_stride_bytes": job.table_bytes // job.rows_big, "n_bags": wl.n_bags, "pooling": wl.pooling, "weighted": wl.weighted,
         "us_per_call": us_c, "us_per_call_unchecked": us_u, "abft_overhead_pct": 100.0 * (us_c - us_u) / us_u,
         "pooled_rows_per_s": job.mean_indices / us_c * 1e6, "table_bytes": job.table_bytes,
@@ -513,10 +516,12 @@ def main():
         out["eb"] = []
         # (workload, records line-aligned): the large batches of narrow rows are also run on records that
         # never straddle a 128-byte line
-        eb_runs = [(ewl, False) for ewl in eb_list] + [(ewl, True) for ewl in eb_list if ewl.n_bags > 1000 and ewl.d <= 64]
-        for ewl, aligned in eb_runs:
-            r = measure_eb(b, torch, ewl, cpu=not args.no_cpu_baseline and not aligned, aligned=aligned)
-            if eb_traffic is not None and ewl.name == ew.LARGE_BATCH[64].name and not aligned:
+        eb_runs = [(ewl, False, 8) for ewl in eb_list] + [(ewl, True, 8) for ewl in eb_list if ewl.n_bags > 1000 and ewl.d <= 64]
+        if args.others:   # 4-bit codes: Table I at d = 128 (the same 64 code bytes a row as d = 64 at 8 bits) and its large batch
+            eb_runs += [(ew.TABLE1[128], False, 4), (ew.LARGE_BATCH[128], False, 4)]
+        for ewl, aligned, bits in eb_runs:
+            r = measure_eb(b, torch, ewl, cpu=not args.no_cpu_baseline and not aligned, aligned=aligned, bits=bits)
+            if eb_traffic is not None and ewl.name == ew.LARGE_BATCH[64].name and not aligned and bits == 8:
                 r["roofline"]["traffic"] = eb_traffic["read"] + eb_traffic["write"]
                 r["roofline"]["traffic_read"] = eb_traffic["read"]
                 r["roofline"]["traffic_write"] = eb_traffic["write"]

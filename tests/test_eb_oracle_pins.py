@@ -2,6 +2,8 @@
 other than itself - exact rational arithmetic on tiny inputs, the identity the check rests
 on (arXiv 2103.00130 Section V, Eq. 4), an independent library routine, integer special
 cases, and the closed-form detection threshold of Algorithm 2."""
+import json
+import os
 from fractions import Fraction
 
 import numpy as np
@@ -242,3 +244,22 @@ def test_int4_flip_changes_the_named_element_only():
         flags = eb.campaign_table_flips(Tp, scale, bias, C_T, indices, offsets, None, [row], [col], [bit], bits=4)
         # RSum is about 50*32*7.5 = 12000: the bound 1e-5 is 0.12, every flip is caught
         assert flags[0, 0] == 1
+
+
+def test_paper_figures_fixture():
+    """What the paper prints for the EmbeddingBag check (tests/golden/paper_eb_figures.json): the bound
+    the oracle defaults to, the shapes the workloads module names, and the overhead model, which must
+    be the ratio of the two operation counts it is derived from."""
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_eb_figures.json")))
+    assert eb.REL_BOUND == g["relative_bound"]
+    t1 = g["table1"]
+    assert sorted(w.TABLE1) == t1["columns"]
+    for d, wl in w.TABLE1.items():
+        assert (wl.rows, wl.d, wl.pooling, wl.n_bags) == (t1["rows"], d, t1["average_pooling"], t1["batch"])
+    for m, d in ((100, 32), (100, 256), (7, 64)):
+        env = {"m": Fraction(m), "d": Fraction(d), "p": Fraction(8)}
+        assert eval(g["ops_extra"], {}, env) / eval(g["ops_without_abft"], {}, env) == eval(g["overhead_fraction"], {}, env)
+        # the row sum is one 32-bit word per row of p*d bits
+        assert eval(g["rowsum_memory_fraction"], {}, env) == Fraction(32, 8 * d)
+    hi, lo, fp = (Fraction(*g["table3_detected"][k]) for k in ("high_bits", "low_bits", "no_error"))
+    assert hi > lo > fp
