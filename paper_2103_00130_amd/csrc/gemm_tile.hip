@@ -8,6 +8,7 @@ ABFT_DECL(a256w24);
 ABFT_DECL(a256w42);
 ABFT_DECL(a128);
 ABFT_DECL(a64);
+ABFT_DECL(a64s8);
 ABFT_DECL(g128);
 ABFT_DECL(g64);
 #undef ABFT_DECL
@@ -24,7 +25,14 @@ hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, c
     switch (variant) {
         case kTile256: return launch_gemm_tile_a256(check, want_c, want_q, p, s);
         case kTile128: return launch_gemm_tile_a128(check, want_c, want_q, p, s);
-        case kTile64: return launch_gemm_tile_a64(check, want_c, want_q, p, s);
+        case kTile64: {
+            // At most one workgroup per compute unit and a long K loop: the deep ring (it takes most of a
+            // unit's LDS, and filling it costs more than it saves below about sixteen stages).  Measured:
+            // 1024x1024x4096 12.9 against 14.3 us, 512x512x512 4.3 against 3.9 us.
+            const int64_t tiles = (int64_t)((p.M + 63) / 64) * ((p.N + 63) / 64);
+            if (tiles <= 256 && p.K >= 2048) return launch_gemm_tile_a64s8(check, want_c, want_q, p, s);
+            return launch_gemm_tile_a64(check, want_c, want_q, p, s);
+        }
         case kTile256w24: return launch_gemm_tile_a256w24(check, want_c, want_q, p, s);
         case kTile256w42: return launch_gemm_tile_a256w42(check, want_c, want_q, p, s);
         default: return hipErrorInvalidValue;

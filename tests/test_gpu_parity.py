@@ -550,3 +550,24 @@ def test_long_and_wide_ragged_shapes(binding, gpu_util, oracle, M, N, K):
     out = run.gemm(A, injections=inj)
     assert np.array_equal(out["C"], ref.C) and np.array_equal(out["flags"], ref.flags)
     assert out["err_count"] == ref.err_count == 3 and not out["ws"].any()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("M,N,K", [(200, 300, 2304), (1000, 1000, 4096), (65, 64, 2048)])
+@pytest.mark.parametrize("variant", ["auto", "tile64"])
+def test_small_grid_long_k(binding, gpu_util, oracle, M, N, K, variant):
+    """At most 256 tiles of 64x64 and K of sixteen stages or more: the 64x64 kernel with the deep ring
+    of stages, with injections, in the exact check and modulo 127."""
+    say(f"small grid, long K {M}x{N}x{K} {variant}")
+    A, B = operands(M, N, K, 3 * M + N + K)
+    inj = [(M - 1, N - 1, 1 << 30), (0, 0, 1), (M // 2, N // 3, 0x00020000)]
+    ref = oracle.checked_gemm(A, B, flips_c=inj)
+    run = gpu_util.GpuRun(binding, B)
+    out = run.gemm(A, variant=variant, injections=inj)
+    assert np.array_equal(out["C"], ref.C) and np.array_equal(out["flags"], ref.flags)
+    assert out["err_count"] == ref.err_count == 3 and not out["ws"].any()
+    clean = run.gemm(A, variant=variant)
+    assert clean["err_count"] == 0 and not clean["flags"].any()
+    C127, flags127, count127 = oracle.checked_gemm_mod127(A, B, flips_c=inj)
+    out127 = run.gemm(A, variant=variant, injections=inj, mod127=True)
+    assert np.array_equal(out127["C"], C127) and np.array_equal(out127["flags"], flags127) and out127["err_count"] == count127
