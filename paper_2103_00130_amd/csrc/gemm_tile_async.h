@@ -207,7 +207,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     v4i limb[2];
     limb[0] = limb[1] = v4i{0, 0, 0, 0};
     // This tile column's contiguous share [ck_lo, ck_hi) of the checksum product's K range.  Its
-    // digits (512 bytes per stage) are copied to LDS once, before the main loop, when they fit
+    // digits (512 bytes per stage) are copied to LDS once, behind the loads of the first stages, when they fit
     // (kLimbStages stages): the stages that use them then read LDS instead of waiting on a global
     // load behind all the direct-to-LDS loads in flight.
     constexpr int kLimbStages = 32;
@@ -215,9 +215,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     const int ck_hi = kCheck ? (int)(((int64_t)(tile_n + 1) * NS) / tiles_n) : 0;
     const bool limbs_in_lds = ck_hi - ck_lo <= kLimbStages;
     uint8_t* const s_limb = smem + S * (A_STAGE + B_STAGE) + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t);
-    if (kCheck && limbs_in_lds)
-        for (int i = tid; i < (ck_hi - ck_lo) * 32; i += NT)
-            reinterpret_cast<v4i*>(s_limb)[i] = reinterpret_cast<const v4i*>(p.limbs + (int64_t)ck_lo * 512)[i];
     auto load_limbs = [&](int s) __attribute__((always_inline)) {
         const int q = ((lane >> 4) * kLimbs + (lane & 15)) << 4;  // this lane's digit inside a k-block
 #pragma unroll
@@ -306,6 +303,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     for (int st = 0; st < S - 1; ++st)
 #pragma unroll
         for (int n = 0; n < N_LD; ++n) issue_load(min(st, NS - 1), st, n);
+    // the digits of this tile column's share go to LDS behind the first stages, so that their
+    // round trip to memory overlaps with that of the stages instead of preceding it
+    if (kCheck && limbs_in_lds)
+        for (int i = tid; i < (ck_hi - ck_lo) * 32; i += NT)
+            reinterpret_cast<v4i*>(s_limb)[i] = reinterpret_cast<const v4i*>(p.limbs + (int64_t)ck_lo * 512)[i];
     wait_vmem_but(pending_c{});
     __syncthreads();
     // first share of the stage after those
@@ -391,7 +393,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     int32_t* const s_bs = reinterpret_cast<int32_t*>(smem + S * (A_STAGE + B_STAGE));
     int32_t* const s_rs = s_bs + 4 * BN;
     int32_t* const s_ck = s_rs + WGN * BM;
-    int* const s_ctl = s_ck + BM;
     // column sums of the streamed B: lane halves hold the two k-groups, waves wm = 0 and 1 (or a
     // lone wave) hold alternate k-steps; every byte carried a bias of 128
     constexpr int SUM_WAVES = WGM == 1 ? 1 : 2;
@@ -531,7 +532,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                 v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);
                 if (d == 0) s_ck[wm * WTM + (wn * CB + c) * 16 + 4 * (lane >> 4) + e] = (int32_t)v;
             }
-        if (tid == 0) s_ctl[1] = 0;
         __syncthreads();
         // Row r of the product is spread over the tile columns; each of them adds its share of
         // (row sum - checksum) to the row's 64-bit workspace word with ONE returned atomic:
@@ -541,42 +541,48 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         // No cache maintenance is involved: all data that crosses workgroups moves through
         // device-scope atomics.
         unsigned long long* const ws_rows = reinterpret_cast<unsigned long long*>(p.ws + kWsHeaderInts);
-        int my_err = 0;
-        for (int r = tid; r < BM; r += NT) {
-            if (row0 + r < p.M) {
-                uint32_t d = 0;
+        static_assert(BM <= NT, "one row per thread at most");
+        bool fin = false, bad = false;  // this thread completed its row / found it corrupted
+        const int r = tid;
+        if (r < BM && row0 + r < p.M) {
+            uint32_t d = 0;
 #pragma unroll
-                for (int w = 0; w < WGN; ++w) d += (uint32_t)s_rs[w * BM + r];
-                if (mod127) {
-                    // residues: sums of at most 32 lanes x WGN waves of values below 127, minus the exact
-                    // checksum share, as a residue again so that the workspace word cannot wrap
-                    long long dd = (long long)d - (long long)s_ck[r];
-                    if (tile_n == 0) dd -= 128ll * (long long)(*p.total);
-                    d = (uint32_t)floor_mod127(dd);
-                } else {
-                    d -= (uint32_t)s_ck[r];
-                    if (tile_n == 0) d -= 128u * (uint32_t)(*p.total);  // sum_k 128*S_B[k], once per row
-                }
-                const unsigned long long old = __hip_atomic_fetch_add(ws_rows + row0 + r, ((unsigned long long)d << 32) | 1ull,
-                                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if ((uint32_t)old == (uint32_t)tiles_n - 1u) {
-                    const uint32_t diff = (uint32_t)(old >> 32) + d;
-                    const int bad_row = mod127 ? (diff % 127u != 0) : (diff != 0);
-                    __hip_atomic_store(ws_rows + row0 + r, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    p.row_flags[row0 + r] = bad_row;
-                    my_err += bad_row;
-                }
+            for (int w = 0; w < WGN; ++w) d += (uint32_t)s_rs[w * BM + r];
+            if (mod127) {
+                // residues: sums of at most 32 lanes x WGN waves of values below 127, minus the exact
+                // checksum share, as a residue again so that the workspace word cannot wrap
+                long long dd = (long long)d - (long long)s_ck[r];
+                if (tile_n == 0) dd -= 128ll * (long long)(*p.total);
+                d = (uint32_t)floor_mod127(dd);
+            } else {
+                d -= (uint32_t)s_ck[r];
+                if (tile_n == 0) d -= 128u * (uint32_t)(*p.total);  // sum_k 128*S_B[k], once per row
+            }
+            const unsigned long long old = __hip_atomic_fetch_add(ws_rows + row0 + r, ((unsigned long long)d << 32) | 1ull,
+                                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((uint32_t)old == (uint32_t)tiles_n - 1u) {
+                const uint32_t diff = (uint32_t)(old >> 32) + d;
+                bad = mod127 ? (diff % 127u != 0) : (diff != 0);
+                __hip_atomic_store(ws_rows + row0 + r, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                p.row_flags[row0 + r] = bad ? 1 : 0;
+                fin = true;
             }
         }
-        // errCount: flagged rows are summed inside the workgroup and carried by its arrival (two
-        // levels of returned atomics, see arrive_two_level); every thread has its row atomics back
-        // by then, since it branched on their results.  The last arrival holds the total.
-        if (my_err) atomicAdd(&s_ctl[1], my_err);
-        __syncthreads();
-        if (tid == 0) {
-            uint32_t total = 0;
-            if (arrive_two_level(p.ws, (uint32_t)s_ctl[1], gridDim.x, blockIdx.x, &total) && p.err_count)
-                *p.err_count = (int32_t)total;
+        // errCount: every row is completed by exactly one thread of the grid.  A wavefront that completed
+        // rows reports them with one more returned atomic on the word of finished rows (count in the low
+        // half, corrupted ones in the high half); the report that brings the count to M has the total,
+        // writes errCount and clears the word.  Workgroups that completed nothing are done here, and no
+        // barrier stands between the two atomics.
+        const unsigned long long fin_mask = __ballot(fin), bad_mask = __ballot(fin && bad);
+        if (fin_mask != 0ull && lane == __builtin_ctzll(fin_mask)) {
+            unsigned long long* const w_done = reinterpret_cast<unsigned long long*>(p.ws + kWsDoneWord);
+            const uint32_t n_fin = (uint32_t)__builtin_popcountll(fin_mask), n_bad = (uint32_t)__builtin_popcountll(bad_mask);
+            const unsigned long long old = __hip_atomic_fetch_add(w_done, ((unsigned long long)n_bad << 32) | n_fin,
+                                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((uint32_t)old + n_fin == (uint32_t)p.M) {
+                if (p.err_count) *p.err_count = (int32_t)((uint32_t)(old >> 32) + n_bad);
+                __hip_atomic_store(w_done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
     // direct-to-LDS loads that are still in flight must not outlive the workgroup's LDS
