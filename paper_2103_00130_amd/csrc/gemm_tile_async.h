@@ -207,23 +207,29 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     v4i limb[2];
     limb[0] = limb[1] = v4i{0, 0, 0, 0};
     // This tile column's contiguous share [ck_lo, ck_hi) of the checksum product's K range.  Its
-    // digits (512 bytes per stage) are copied to LDS once, behind the loads of the first stages, when they fit
-    // (kLimbStages stages): the stages that use them then read LDS instead of waiting on a global
-    // load behind all the direct-to-LDS loads in flight.
+    // digits (512 bytes per stage) are staged in LDS, kLimbStages stages at a time: the first lot
+    // behind the loads of the first stages, a further lot (shares longer than that: K beyond
+    // 4096 per tile column) between two runs of stages.  The stages that use them read LDS, so
+    // that the loop holds no global load the compiler knows of: it would put a wait for *all*
+    // vector-memory traffic, the direct-to-LDS loads of the next stage included, in front of the
+    // digit MFMAs.
     constexpr int kLimbStages = 32;
     const int ck_lo = kCheck ? (int)(((int64_t)tile_n * NS) / tiles_n) : 0;
     const int ck_hi = kCheck ? (int)(((int64_t)(tile_n + 1) * NS) / tiles_n) : 0;
-    const bool limbs_in_lds = ck_hi - ck_lo <= kLimbStages;
     uint8_t* const s_limb = smem + S * (A_STAGE + B_STAGE) + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t);
+    int limb_base = ck_lo;  // stage whose digits sit at the start of s_limb
+    auto stage_limbs = [&](int s0) __attribute__((always_inline)) {
+        const int n = min(ck_hi - s0, kLimbStages);
+        for (int i = tid; i < n * 32; i += NT)
+            reinterpret_cast<v4i*>(s_limb)[i] = reinterpret_cast<const v4i*>(p.limbs + (int64_t)s0 * 512)[i];
+        limb_base = s0;
+    };
     auto load_limbs = [&](int s) __attribute__((always_inline)) {
         const int q = ((lane >> 4) * kLimbs + (lane & 15)) << 4;  // this lane's digit inside a k-block
 #pragma unroll
         for (int kbl = 0; kbl < 2; ++kbl) {
             limb[kbl] = v4i{0, 0, 0, 0};
-            if ((lane & 15) < kLimbs) {
-                if (limbs_in_lds) limb[kbl] = *reinterpret_cast<const v4i*>(s_limb + ((s - ck_lo) * 2 + kbl) * 256 + q);
-                else limb[kbl] = *reinterpret_cast<const v4i*>(p.limbs + (int64_t)(2 * s + kbl) * 256 + q);
-            }
+            if ((lane & 15) < kLimbs) limb[kbl] = *reinterpret_cast<const v4i*>(s_limb + ((s - limb_base) * 2 + kbl) * 256 + q);
         }
     };
     int ck_off[2];
@@ -305,9 +311,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         for (int n = 0; n < N_LD; ++n) issue_load(min(st, NS - 1), st, n);
     // the digits of this tile column's share go to LDS behind the first stages, so that their
     // round trip to memory overlaps with that of the stages instead of preceding it
-    if (kCheck && limbs_in_lds)
-        for (int i = tid; i < (ck_hi - ck_lo) * 32; i += NT)
-            reinterpret_cast<v4i*>(s_limb)[i] = reinterpret_cast<const v4i*>(p.limbs + (int64_t)ck_lo * 512)[i];
+    if (kCheck && ck_hi > ck_lo) stage_limbs(ck_lo);
     wait_vmem_but(pending_c{});
     __syncthreads();
     // first share of the stage after those
@@ -372,7 +376,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     auto run_all = [&](auto ph_c) __attribute__((always_inline)) {
         if (kCheck) {
             run(0, ck_lo, std::false_type{}, ph_c);
-            run(ck_lo, ck_hi, std::true_type{}, ph_c);
+            for (int c0 = ck_lo; c0 < ck_hi; c0 += kLimbStages) {
+                if (c0 > ck_lo) {
+                    // every wave has left the stages that read the previous lot (their digits were in
+                    // registers before the barrier that ended the last of them)
+                    stage_limbs(c0);
+                    __syncthreads();
+                }
+                run(c0, min(c0 + kLimbStages, ck_hi), std::true_type{}, ph_c);
+            }
             run(ck_hi, NS, std::false_type{}, ph_c);
         } else {
             run(0, NS, std::false_type{}, ph_c);

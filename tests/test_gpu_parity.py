@@ -571,3 +571,25 @@ def test_small_grid_long_k(binding, gpu_util, oracle, M, N, K, variant):
     C127, flags127, count127 = oracle.checked_gemm_mod127(A, B, flips_c=inj)
     out127 = run.gemm(A, variant=variant, injections=inj, mod127=True)
     assert np.array_equal(out127["C"], C127) and np.array_equal(out127["flags"], flags127) and out127["err_count"] == count127
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("M,N,K,variant", [(100, 64, 8320, "tile64"), (300, 256, 12288, "tile256"), (130, 128, 4224, "tile128")])
+def test_long_checksum_share(binding, gpu_util, oracle, M, N, K, variant):
+    """One tile column and a long K: its share of the checksum product is longer than one lot of
+    digits in LDS (32 stages of 128), so the digits are staged in several lots."""
+    say(f"long checksum share {M}x{N}x{K} {variant}")
+    A, B = operands(M, N, K, 5 * M + N + K)
+    inj = [(M - 1, N - 1, 1 << 31), (0, 0, 1 << 5)]
+    ref = oracle.checked_gemm(A, B, flips_c=inj)
+    run = gpu_util.GpuRun(binding, B)
+    out = run.gemm(A, variant=variant, injections=inj)
+    assert np.array_equal(out["C"], ref.C) and np.array_equal(out["flags"], ref.flags)
+    assert out["err_count"] == ref.err_count == 2 and not out["ws"].any()
+    assert run.gemm(A, variant=variant)["err_count"] == 0
+    # a fault in the weight, late in K (second lot of digits): the rows it corrupts, as the oracle says
+    k, j = K - 7, N // 2
+    binding.abft_packed_b_flip_bit(run.Bp, k, j, 6)
+    refb = oracle.checked_gemm(A, B, flips_b=[(k, j, 6)])
+    outb = run.gemm(A, variant=variant)
+    assert np.array_equal(outb["C"], refb.C) and np.array_equal(outb["flags"], refb.flags) and outb["err_count"] == refb.err_count
