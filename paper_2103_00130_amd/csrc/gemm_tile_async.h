@@ -232,6 +232,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
             if ((lane & 15) < kLimbs) limb[kbl] = *reinterpret_cast<const v4i*>(s_limb + ((s - limb_base) * 2 + kbl) * 256 + q);
         }
     };
+    // The digit MFMA with its accumulator in ordinary vector registers.  All 256 accumulation
+    // registers hold the tile; left to the compiler, the digit accumulators would be swapped into
+    // them and out again around every digit MFMA (it gives every MFMA of a function the same
+    // register class for its result).  The instruction takes either class, so it is written out
+    // here; the two wait states that a vector write needs before a matrix instruction reads the
+    // register (the XOR on the operand) are part of the string, since no hazard pass sees inside it.
+    auto mfma_digits = [](v4i& c, v4i a, v4i b) __attribute__((always_inline)) {
+        asm volatile("s_nop 1\n\tv_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+    };
     int ck_off[2];
 #pragma unroll
     for (int kbl = 0; kbl < 2; ++kbl)
@@ -355,12 +364,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                 // the resident stage
                 const uint8_t* sA = smem + cur * A_STAGE;
 #pragma unroll
-                for (int kbl = 0; kbl < 2; ++kbl)
+                for (int kbl = 0; kbl < 2; ++kbl) {
+                    v4i av[CB];
 #pragma unroll
-                    for (int c = 0; c < CB; ++c) {
-                        const v4i a = *reinterpret_cast<const v4i*>(sA + ck_off[kbl] + c * 16 * BK) ^ (int)0x80808080;
-                        cacc[c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, limb[kbl], cacc[c], 0, 0, 0);
-                    }
+                    for (int c = 0; c < CB; ++c) av[c] = *reinterpret_cast<const v4i*>(sA + ck_off[kbl] + c * 16 * BK);
+#pragma unroll
+                    for (int c = 0; c < CB; ++c) mfma_digits(cacc[c], av[c] ^ (int)0x80808080, limb[kbl]);
+                }
+                // the digit accumulators are next read by vector instructions (epilogue) or by the digit
+                // MFMAs of a later stage; cover the longest write-to-read distance of a 4-pass MFMA once
+                asm volatile("s_nop 7\n\ts_nop 7");
             }
             // publish the next stage: this wave's loads of it have landed, and after the
             // barrier nobody reads the current stage any more
