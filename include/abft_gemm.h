@@ -123,7 +123,7 @@ typedef struct {
 
 /* Scratch the checked GEMM needs for a problem with M rows against Bp: one
  * 64-bit word per row (partial row sum - checksum, and how many column blocks
- * have contributed) and an arrival counter.
+ * have contributed) and a few counting words (rows finished, rows corrupted).
  * The memory must be zero before its first use (abft_workspace_init) and every
  * call leaves it zero again, so one workspace serves any number of calls that
  * are ordered on one stream.  Calls that may overlap need one workspace each. */

@@ -98,12 +98,13 @@ struct GemmParams {
     RequantDev rq;
     const void* inj;           // abft_inject_t[n_inj]
     int n_inj;
-    int32_t* ws;               // workspace: arrival words in the first kWsHeaderInts ints, then the per-row words
+    int32_t* ws;               // workspace: counting words in the first kWsHeaderInts ints, then the per-row words
 };
 
-constexpr int kWsHeaderInts = 64;   // top arrival word, 16 group arrival words, padding
+constexpr int kWsHeaderInts = 64;   // top arrival word, 16 group arrival words (any-alignment kernel), word of finished rows
 constexpr int kTicketGroups = 16;
-constexpr int kWsDoneWord = 48;     // int offset of the streaming kernel's finished-rows word inside the header
+constexpr int kWsDoneWord = 48;     // int offset, inside the header, of the 64-bit word that counts finished rows (low half)
+                                    // and corrupted ones among them (high half): direct-to-LDS tile kernels, streaming kernel
 constexpr int kTicketFlatMax = 128;  // grids up to this size count their arrivals on one word
 // the streaming kernel spreads its per-row sums over kSmallMSlots slots of kSmallMRows rows
 constexpr int kSmallMSlots = 32;
@@ -114,8 +115,8 @@ constexpr int kSmallMRows = 64;
 // than a few dozen atomics at once (hundreds of returned atomics on one address serialise for
 // microseconds): a workgroup arrives at the word of its group (block id modulo kTicketGroups) with
 // its contribution `mine` in the high half; the last of a group carries the group's sum on to
-// the top word (grids of at most kTicketFlatMax workgroups skip the first level).  True for the one workgroup that completes the top word, *total then holds the
-// sum over the grid; both levels leave their words at zero.  Everything a workgroup did with
+// the top word (grids of at most kTicketFlatMax workgroups skip the first level).  True for the
+// one workgroup that completes the top word, *total then holds the sum over the grid; both levels leave their words at zero.  Everything a workgroup did with
 // returned device-scope atomics before it arrives is complete when the last one gets here.
 __device__ inline bool arrive_two_level(int32_t* ws, uint32_t mine, uint32_t n_blocks, uint32_t block, uint32_t* total) {
     unsigned long long* const top0 = reinterpret_cast<unsigned long long*>(ws);
