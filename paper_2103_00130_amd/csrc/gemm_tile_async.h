@@ -220,7 +220,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
 #pragma unroll
     for (int j = 0; j < TN; ++j) bsum[j] = 0;
 
-    v4i fa[2][TM], fb[2][TN];
+    // Small wave tiles (at most four MFMAs per k-step) read their fragments two k-steps ahead: one
+    // k-step of such a tile is shorter than the latency of an LDS read, so with one k-step of
+    // lookahead every k-step would end in a wait for its successor's operands.  Four fragment sets,
+    // one per k-step of a stage.
+    constexpr bool kAhead2 = TM * TN <= 4;
+    constexpr int NSETS = kAhead2 ? 4 : 2;
+    v4i fa[NSETS][TM], fb[NSETS][TN];
     auto read_frags = [&](int buf, int j, int f) __attribute__((always_inline)) {
         const uint8_t* sA = smem + buf * A_STAGE;
         const uint8_t* sB = smem + buf * B_STAGE;
@@ -277,6 +283,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         ck_off[kbl] = (wm * WTM + wn * CB * 16 + (lane & 15)) * BK + (((4 * kbl + (lane >> 4)) ^ a_swz) << 4);
     auto wait_lds = []() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0xC07F); };
     auto wait_vmem = []() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };
+    // at most n LDS operations still in flight (they complete in order)
+    auto wait_lds_but = [](auto n_c) __attribute__((always_inline)) {
+        constexpr int n = decltype(n_c)::value;
+        static_assert(n >= 0 && n < 16, "lgkmcnt is a 4-bit field");
+        __builtin_amdgcn_s_waitcnt(0xC07F | (n << 8));
+    };
     // at most n vector-memory operations still in flight (they complete in order)
     auto wait_vmem_but = [](auto n_c) __attribute__((always_inline)) {
         constexpr int n = decltype(n_c)::value;
@@ -284,7 +296,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         __builtin_amdgcn_s_waitcnt(((n >> 4) << 14) | (n & 15) | 0x0F70);
     };
 
-    // One k-step of 32: TM x TN MFMAs on fragment set f while fragment set f^1 is read for
+    // One k-step of 32: TM x TN MFMAs on fragment set f while fragment set fr is read for
     // k-step jn of buffer rbuf and loads [ld_lo, ld_hi) of stage ld_s go out to buffer ld_buf.
     // The k-step is cut into regions of two MFMAs that the instruction scheduler may not move
     // anything across; each region carries its share of the other work, so that every LDS
@@ -297,7 +309,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     //    int8 into a biased uint8 whose four bytes v_sad_u8 sums against zero (the bias, 128
     //    per byte, is taken off in the epilogue);
     //  * the direct-to-LDS loads are spread evenly instead of arriving in a burst.
-    auto phase = [&](int f, int rbuf, int jn, auto sum_b_c, int ld_s, int ld_buf, int ld_lo, int ld_hi)
+    auto phase = [&](int f, int fr, int rbuf, int jn, auto sum_b_c, int ld_s, int ld_buf, int ld_lo, int ld_hi)
                      __attribute__((always_inline)) {
         constexpr bool SUM_B = decltype(sum_b_c)::value;
         constexpr int Q = TM * TN, NR = Q / 2, R = TM + TN, RR = NR >= 2 ? NR / 2 : 1, D = 4 * TN;
@@ -314,8 +326,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
             if (r < RR) {
 #pragma unroll
                 for (int x = R * r / RR; x < R * (r + 1) / RR; ++x) {
-                    if (x < TM) fa[f ^ 1][x] = *reinterpret_cast<const v4i*>(sA + x * 32 * BK);
-                    else fb[f ^ 1][x - TM] = *reinterpret_cast<const v4i*>(sB + (x - TM) * 2048);
+                    if (x < TM) fa[fr][x] = *reinterpret_cast<const v4i*>(sA + x * 32 * BK);
+                    else fb[fr][x - TM] = *reinterpret_cast<const v4i*>(sB + (x - TM) * 2048);
                 }
             }
             if (SUM_B) {
@@ -344,21 +356,41 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     constexpr int LD_C0 = S == 2 ? N_LD * 3 / 8 : N_LD / 4, LD_C1 = S == 2 ? N_LD * 6 / 8 : N_LD / 2,
                   LD_C2 = S == 2 ? N_LD : N_LD * 3 / 4;
     using pending_c = std::integral_constant<int, (S - 2) * N_LD>;
+    // Two k-steps of lookahead (kAhead2): all S slots are filled before the loop; in stage s the first two
+    // k-steps read the last two fragment sets of the stage, a barrier then publishes stage s+1 and
+    // releases the slot of stage s (everything read from it is in registers), and the last two
+    // k-steps read the first two fragment sets of stage s+1 while the loads of stage s+S go out, one
+    // half per k-step, to the slot just released.
+    using frag_reads_c = std::integral_constant<int, TM + TN>;  // LDS reads of one k-step
+    if constexpr (kAhead2) {
 #pragma unroll
-    for (int st = 0; st < S - 1; ++st)
+        for (int st = 0; st < S; ++st)
 #pragma unroll
-        for (int n = 0; n < N_LD; ++n) issue_load(min(st, NS - 1), st, n);
-    // the digits of this tile column's share go to LDS behind the first stages, so that their
-    // round trip to memory overlaps with that of the stages instead of preceding it
-    if (kCheck && ck_hi > ck_lo) stage_limbs(ck_lo);
-    wait_vmem_but(pending_c{});
-    __syncthreads();
-    // first share of the stage after those
+            for (int n = 0; n < N_LD; ++n) issue_load(min(st, NS - 1), st, n);
+        if (kCheck && ck_hi > ck_lo) stage_limbs(ck_lo);
+        wait_vmem_but(std::integral_constant<int, (S - 1) * N_LD>{});
+        __syncthreads();
+        read_frags(0, 0, 0);
+        read_frags(0, 1, 1);
+        wait_lds();
+        __builtin_amdgcn_sched_barrier(0);
+    } else {
 #pragma unroll
-    for (int n = 0; n < LD_C0; ++n) issue_load(min(S - 1, NS - 1), S - 1, n);
-    read_frags(0, 0, 0);
-    wait_lds();
-    __builtin_amdgcn_sched_barrier(0);
+        for (int st = 0; st < S - 1; ++st)
+#pragma unroll
+            for (int n = 0; n < N_LD; ++n) issue_load(min(st, NS - 1), st, n);
+        // the digits of this tile column's share go to LDS behind the first stages, so that their
+        // round trip to memory overlaps with that of the stages instead of preceding it
+        if (kCheck && ck_hi > ck_lo) stage_limbs(ck_lo);
+        wait_vmem_but(pending_c{});
+        __syncthreads();
+        // first share of the stage after those
+#pragma unroll
+        for (int n = 0; n < LD_C0; ++n) issue_load(min(S - 1, NS - 1), S - 1, n);
+        read_frags(0, 0, 0);
+        wait_lds();
+        __builtin_amdgcn_sched_barrier(0);
+    }
 
     int cur = 0;
     // A run of stages [s_begin, s_end) with or without the checksum-digit MFMAs (separate loops
@@ -373,47 +405,73 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         constexpr int PH = decltype(ph_c)::value;
         using even_c = std::integral_constant<bool, PH != 1>;
         using odd_c = std::integral_constant<bool, PH != 0>;
-        for (int s = s_begin; s < s_end; ++s) {
-            // stage whose loads go out now, the slot they go to, and the slot of the next stage
-            const int s1 = min(s + S - 1, NS - 1), s2 = min(s + S, NS - 1);
-            const int nxt = cur + 1 == S ? 0 : cur + 1, tgt = cur == 0 ? S - 1 : cur - 1;
-            // the digit operands of this stage are needed three quarters of a stage from now
-            if (CHK) load_limbs(s);
-            phase(0, cur, 1, even_c{}, s1, tgt, LD_C0, LD_C1);
-            wait_lds();
-            __builtin_amdgcn_sched_barrier(0);
-            phase(1, cur, 2, odd_c{}, s1, tgt, LD_C1, LD_C2);
-            wait_lds();
-            __builtin_amdgcn_sched_barrier(0);
-            phase(0, cur, 3, even_c{}, s1, tgt, LD_C2, N_LD);
-            wait_lds();
-            __builtin_amdgcn_sched_barrier(0);
-            if (CHK) {
-                // checksum-digit columns for this wave's share of the rows (16-row blocks
-                // wn*CB ..) over both k-blocks of the stage; the A operands are re-read from
-                // the resident stage
-                const uint8_t* sA = smem + cur * A_STAGE;
+        // checksum-digit columns for this wave's share of the rows (16-row blocks wn*CB ..) over both
+        // k-blocks of the stage in slot `buf`; the A operands are re-read from the resident stage
+        auto digit_block = [&](int buf) __attribute__((always_inline)) {
+            const uint8_t* sA = smem + buf * A_STAGE;
 #pragma unroll
-                for (int kbl = 0; kbl < 2; ++kbl) {
-                    v4i av[CB];
+            for (int kbl = 0; kbl < 2; ++kbl) {
+                v4i av[CB];
 #pragma unroll
-                    for (int c = 0; c < CB; ++c) av[c] = *reinterpret_cast<const v4i*>(sA + ck_off[kbl] + c * 16 * BK);
+                for (int c = 0; c < CB; ++c) av[c] = *reinterpret_cast<const v4i*>(sA + ck_off[kbl] + c * 16 * BK);
 #pragma unroll
-                    for (int c = 0; c < CB; ++c) mfma_digits(cacc[c], av[c] ^ (int)0x80808080, limb[kbl]);
-                }
-                // the digit accumulators are next read by vector instructions (epilogue) or by the digit
-                // MFMAs of a later stage; cover the longest write-to-read distance of a 4-pass MFMA once
-                asm volatile("s_nop 7\n\ts_nop 7");
+                for (int c = 0; c < CB; ++c) mfma_digits(cacc[c], av[c] ^ (int)0x80808080, limb[kbl]);
             }
-            // publish the next stage: this wave's loads of it have landed, and after the
-            // barrier nobody reads the current stage any more
-            wait_vmem_but(pending_c{});
-            __syncthreads();
-            __builtin_amdgcn_sched_barrier(0);
-            phase(1, nxt, 0, odd_c{}, s2, cur, 0, LD_C0);
-            wait_lds();
-            __builtin_amdgcn_sched_barrier(0);
-            cur = nxt;
+            // the digit accumulators are next read by vector instructions (epilogue) or by the digit
+            // MFMAs of a later stage; cover the longest write-to-read distance of a 4-pass MFMA once
+            asm volatile("s_nop 7\n\ts_nop 7");
+        };
+        if constexpr (kAhead2) {
+            for (int s = s_begin; s < s_end; ++s) {
+                const int nxt = cur + 1 == S ? 0 : cur + 1;
+                const int s_new = min(s + S, NS - 1);  // refills the slot of this stage once it is released
+                if (CHK) load_limbs(s);
+                phase(0, 2, cur, 2, even_c{}, 0, 0, 0, 0);
+                if (CHK) wait_lds();
+                else wait_lds_but(frag_reads_c{});
+                __builtin_amdgcn_sched_barrier(0);
+                phase(1, 3, cur, 3, odd_c{}, 0, 0, 0, 0);
+                wait_lds();  // every fragment of this stage is in registers
+                __builtin_amdgcn_sched_barrier(0);
+                if (CHK) digit_block(cur);
+                wait_vmem_but(pending_c{});
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+                phase(2, 0, nxt, 0, even_c{}, s_new, cur, 0, N_LD / 2);
+                wait_lds_but(frag_reads_c{});
+                __builtin_amdgcn_sched_barrier(0);
+                phase(3, 1, nxt, 1, odd_c{}, s_new, cur, N_LD / 2, N_LD);
+                wait_lds_but(frag_reads_c{});
+                __builtin_amdgcn_sched_barrier(0);
+                cur = nxt;
+            }
+        } else {
+            for (int s = s_begin; s < s_end; ++s) {
+                // stage whose loads go out now, the slot they go to, and the slot of the next stage
+                const int s1 = min(s + S - 1, NS - 1), s2 = min(s + S, NS - 1);
+                const int nxt = cur + 1 == S ? 0 : cur + 1, tgt = cur == 0 ? S - 1 : cur - 1;
+                // the digit operands of this stage are needed three quarters of a stage from now
+                if (CHK) load_limbs(s);
+                phase(0, 1, cur, 1, even_c{}, s1, tgt, LD_C0, LD_C1);
+                wait_lds();
+                __builtin_amdgcn_sched_barrier(0);
+                phase(1, 0, cur, 2, odd_c{}, s1, tgt, LD_C1, LD_C2);
+                wait_lds();
+                __builtin_amdgcn_sched_barrier(0);
+                phase(0, 1, cur, 3, even_c{}, s1, tgt, LD_C2, N_LD);
+                wait_lds();
+                __builtin_amdgcn_sched_barrier(0);
+                if (CHK) digit_block(cur);
+                // publish the next stage: this wave's loads of it have landed, and after the
+                // barrier nobody reads the current stage any more
+                wait_vmem_but(pending_c{});
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+                phase(1, 0, nxt, 0, odd_c{}, s2, cur, 0, LD_C0);
+                wait_lds();
+                __builtin_amdgcn_sched_barrier(0);
+                cur = nxt;
+            }
         }
     };
     auto run_all = [&](auto ph_c) __attribute__((always_inline)) {
