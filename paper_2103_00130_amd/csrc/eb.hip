@@ -9,12 +9,14 @@
 //  * The table is kept as fused records [codes][scale][bias][C_T][unused]: the row sum that
 //    Eq. 4 needs arrives in the same memory transaction as the scale and bias the lookup needs
 //    anyway, so the check adds no memory traffic at all.
-//  * Batch kernel (large batches): one lane per 16 code bytes of a row; every lane owns their columns and reads
-//    those 16 code bytes per pooled row straight into registers, eight rows in flight per lane; the
-//    chip is filled by lookups, and the lanes of a lookup walk its index list in order.
+//  * Batch kernel (large batches): one lane per 16 code bytes of a row.  Every lane owns the columns
+//    of its bytes and reads them per pooled row straight into registers, eight rows in flight per
+//    lane; the chip is filled by lookups, and the lanes of a lookup walk its index list in order.
 //  * Group kernel (small batches): one workgroup per lookup.  All threads fetch different 16-byte
-//    pieces of the lookup's records into LDS (1024 pieces in flight per workgroup), then the
-//    threads, now owning columns, walk the staged rows in index order.
+//    pieces of the lookup's records into LDS (1024 or 2048 pieces in flight per workgroup), then
+//    the threads, now owning columns, walk the staged rows in index order.
+//  * Every load is unconditional (clamped position, row 0 in place of a bad index): a load under
+//    `if (valid)` is followed by a wait, which would put the loads of a lookup one after the other.
 //  Both accumulate every output column in the same order (index order, one fused multiply-add
 //  per row, biases summed apart), so they give the same bits; RSum and CSum are taken in
 //  binary64, CSum in index order.
