@@ -8,7 +8,7 @@ ABFT_DECL(a256w24);
 ABFT_DECL(a256w42);
 ABFT_DECL(a128);
 ABFT_DECL(a64);
-ABFT_DECL(a64s8);
+ABFT_DECL(a64w4);
 ABFT_DECL(g128);
 ABFT_DECL(g64);
 #undef ABFT_DECL
@@ -19,22 +19,26 @@ hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, c
     const bool fast_a = p.a_vec_ok && (p.K % 16 == 0) && ((int64_t)(p.M - 1) * p.lda + p.K <= 0x7fffffffll);
     if (!fast_a) {
         if (p.mod127) return hipErrorNotSupported;
-        if (variant == kTile64) return launch_gemm_tile_g64(check, want_c, want_q, p, s);
+        if (variant == kTile64 || variant == kTile64w22) return launch_gemm_tile_g64(check, want_c, want_q, p, s);
         return launch_gemm_tile_g128(check, want_c, want_q, p, s);
     }
     switch (variant) {
         case kTile256: return launch_gemm_tile_a256(check, want_c, want_q, p, s);
         case kTile128: return launch_gemm_tile_a128(check, want_c, want_q, p, s);
         case kTile64: {
-            // At most one workgroup per compute unit and a long K loop: the deep ring (it takes most of a
-            // unit's LDS, and filling it costs more than it saves below about sixteen stages).  Measured:
-            // 1024x1024x4096 12.9 against 14.3 us, 512x512x512 4.3 against 3.9 us.
+            // At most one workgroup per compute unit and a long K loop: four wavefronts of 32x32 and a
+            // ring of eight stages (it takes most of a unit's LDS, and filling it costs more than it
+            // saves below about sixteen stages).  The 64x64 kernels are bound by instruction issue and
+            // the LDS reads of a wavefront, not by the matrix cores, so four wavefronts on four SIMDs
+            // beat two.  Measured at 1024x1024x4096, unchecked: 14.3 us (2 wavefronts, 2 stages),
+            // 12.9 us (2 wavefronts, 8 stages), 11.8 us (4 wavefronts, 8 stages).
             const int64_t tiles = (int64_t)((p.M + 63) / 64) * ((p.N + 63) / 64);
-            if (tiles <= 256 && p.K >= 2048) return launch_gemm_tile_a64s8(check, want_c, want_q, p, s);
+            if (tiles <= 256 && p.K >= 2048) return launch_gemm_tile_a64w4(check, want_c, want_q, p, s);
             return launch_gemm_tile_a64(check, want_c, want_q, p, s);
         }
         case kTile256w24: return launch_gemm_tile_a256w24(check, want_c, want_q, p, s);
         case kTile256w42: return launch_gemm_tile_a256w42(check, want_c, want_q, p, s);
+        case kTile64w22: return launch_gemm_tile_a64w4(check, want_c, want_q, p, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -343,6 +343,33 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         }
     };
 
+    // The same k-step for small wave tiles (at most four MFMAs): too short to be cut into regions.
+    // Reads first, then the MFMAs with the vector work behind them.
+    auto phase_small = [&](int f, int fr, int rbuf, int jn, auto sum_b_c, int ld_s, int ld_buf, int ld_lo, int ld_hi)
+                           __attribute__((always_inline)) {
+        constexpr bool SUM_B = decltype(sum_b_c)::value;
+        const uint8_t* const sA = smem + rbuf * A_STAGE + a_off[jn];
+        const uint8_t* const sB = smem + rbuf * B_STAGE + (jn >> 1) * (BN * 64) + b_off + (jn & 1) * 1024;
+#pragma unroll
+        for (int x = 0; x < TM; ++x) fa[fr][x] = *reinterpret_cast<const v4i*>(sA + x * 32 * BK);
+#pragma unroll
+        for (int x = 0; x < TN; ++x) fb[fr][x] = *reinterpret_cast<const v4i*>(sB + x * 2048);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const v4i a = fa[f][i] ^ (int)0x80808080;
+#pragma unroll
+            for (int t = 0; t < TN; ++t) acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, fb[f][t], acc[i][t], 0, 0, 0);
+        }
+        if (SUM_B) {
+#pragma unroll
+            for (int d = 0; d < 4 * TN; ++d)
+                bsum[d >> 2] = __builtin_amdgcn_sad_u8((uint32_t)fb[f][d >> 2][d & 3] ^ 0x80808080u, 0u, bsum[d >> 2]);
+        }
+#pragma unroll
+        for (int n = ld_lo; n < ld_hi; ++n) issue_load(ld_s, ld_buf, n);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
     // Load schedule.
     // Double buffer (S = 2): 3/8 of the loads of stage s+1 go out during the last k-step of
     // stage s-1, 3/8 during the first and 2/8 during the second k-step of stage s (measured best
@@ -426,21 +453,21 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
                 const int nxt = cur + 1 == S ? 0 : cur + 1;
                 const int s_new = min(s + S, NS - 1);  // refills the slot of this stage once it is released
                 if (CHK) load_limbs(s);
-                phase(0, 2, cur, 2, even_c{}, 0, 0, 0, 0);
+                phase_small(0, 2, cur, 2, even_c{}, 0, 0, 0, 0);
                 if (CHK) wait_lds();
                 else wait_lds_but(frag_reads_c{});
                 __builtin_amdgcn_sched_barrier(0);
-                phase(1, 3, cur, 3, odd_c{}, 0, 0, 0, 0);
+                phase_small(1, 3, cur, 3, odd_c{}, 0, 0, 0, 0);
                 wait_lds();  // every fragment of this stage is in registers
                 __builtin_amdgcn_sched_barrier(0);
                 if (CHK) digit_block(cur);
                 wait_vmem_but(pending_c{});
                 __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
-                phase(2, 0, nxt, 0, even_c{}, s_new, cur, 0, N_LD / 2);
+                phase_small(2, 0, nxt, 0, even_c{}, s_new, cur, 0, N_LD / 2);
                 wait_lds_but(frag_reads_c{});
                 __builtin_amdgcn_sched_barrier(0);
-                phase(3, 1, nxt, 1, odd_c{}, s_new, cur, N_LD / 2, N_LD);
+                phase_small(3, 1, nxt, 1, odd_c{}, s_new, cur, N_LD / 2, N_LD);
                 wait_lds_but(frag_reads_c{});
                 __builtin_amdgcn_sched_barrier(0);
                 cur = nxt;
