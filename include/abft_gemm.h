@@ -58,7 +58,6 @@ extern "C" {
 #define ABFT_VARIANT_SMALLM 0x400u /* streaming kernel, M <= 64 */
 #define ABFT_VARIANT_TILE256_W2X4 0x500u /* 256x256 tile, 8 wavefronts as 2x4 */
 #define ABFT_VARIANT_TILE256_W4X2 0x600u /* 256x256 tile, 8 wavefronts as 4x2 */
-#define ABFT_VARIANT_TILE64_W2X2 0x700u  /* 64x64 tile, 4 wavefronts as 2x2 */
 
 /* Opaque packed weight: B in matrix-core fragment order, its checksum column
  * S_B = B e as four signed base-256 digit columns, S_B itself, and the column

@@ -147,7 +147,7 @@ __device__ inline bool arrive_two_level(int32_t* ws, uint32_t mine, uint32_t n_b
 }
 #endif
 
-enum Variant { kTile256 = 1, kTile128 = 2, kTile64 = 3, kSmallM = 4, kTile256w24 = 5, kTile256w42 = 6, kTile64w22 = 7, kVariantEnd = 8 };
+enum Variant { kTile256 = 1, kTile128 = 2, kTile64 = 3, kSmallM = 4, kTile256w24 = 5, kTile256w42 = 6, kVariantEnd = 7 };
 
 // launchers (each returns the hipError_t of its launch)
 hipError_t launch_pack(const int8_t* B, int64_t ldb, int transposed, abft_packed_b* h, hipStream_t s);

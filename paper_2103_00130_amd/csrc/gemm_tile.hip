@@ -19,18 +19,18 @@ hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, c
     const bool fast_a = p.a_vec_ok && (p.K % 16 == 0) && ((int64_t)(p.M - 1) * p.lda + p.K <= 0x7fffffffll);
     if (!fast_a) {
         if (p.mod127) return hipErrorNotSupported;
-        if (variant == kTile64 || variant == kTile64w22) return launch_gemm_tile_g64(check, want_c, want_q, p, s);
+        if (variant == kTile64) return launch_gemm_tile_g64(check, want_c, want_q, p, s);
         return launch_gemm_tile_g128(check, want_c, want_q, p, s);
     }
     switch (variant) {
         case kTile256: return launch_gemm_tile_a256(check, want_c, want_q, p, s);
         case kTile128: return launch_gemm_tile_a128(check, want_c, want_q, p, s);
         case kTile64: {
-            // At most one workgroup per compute unit and a long K loop: four wavefronts of 32x32 and a
-            // ring of eight stages (it takes most of a unit's LDS, and filling it costs more than it
-            // saves below about sixteen stages).  The 64x64 kernels are bound by instruction issue and
-            // the LDS reads of a wavefront, not by the matrix cores, so four wavefronts on four SIMDs
-            // beat two.  Measured at 1024x1024x4096, unchecked: 14.3 us (2 wavefronts, 2 stages),
+            // The 64x64 kernels are bound by instruction issue and the LDS reads of a wavefront, not by
+            // the matrix cores, so they run as four wavefronts of 32x32 on four SIMDs (5-10 % faster than
+            // two of 32x64).  At most one workgroup per compute unit and a long K loop: a ring of eight
+            // stages (it takes most of a unit's LDS, and filling it costs more than it saves below about
+            // sixteen stages).  Measured at 1024x1024x4096, unchecked: 14.3 us (2 wavefronts, 2 stages),
             // 12.9 us (2 wavefronts, 8 stages), 11.8 us (4 wavefronts, 8 stages).
             const int64_t tiles = (int64_t)((p.M + 63) / 64) * ((p.N + 63) / 64);
             if (tiles <= 256 && p.K >= 2048) return launch_gemm_tile_a64w4(check, want_c, want_q, p, s);
@@ -38,7 +38,6 @@ hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, c
         }
         case kTile256w24: return launch_gemm_tile_a256w24(check, want_c, want_q, p, s);
         case kTile256w42: return launch_gemm_tile_a256w42(check, want_c, want_q, p, s);
-        case kTile64w22: return launch_gemm_tile_a64w4(check, want_c, want_q, p, s);
         default: return hipErrorInvalidValue;
     }
 }

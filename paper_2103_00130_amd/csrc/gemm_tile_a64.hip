@@ -1,8 +1,8 @@
-// Direct-to-LDS tiled checked GEMM: 64x64 workgroup tile, 2x1 wavefronts.
+// Direct-to-LDS tiled checked GEMM: 64x64 workgroup tile, 2x2 wavefronts (32x32 each), two stages.
 #include "gemm_tile_async.h"
 
 namespace abft {
 hipError_t launch_gemm_tile_a64(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
-    return atile::launch_cfg<64, 64, 2, 1, 2>(check, want_c, want_q, p, s);
+    return atile::launch_cfg<64, 64, 2, 2, 2>(check, want_c, want_q, p, s);
 }
 }  // namespace abft

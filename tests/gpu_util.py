@@ -6,7 +6,7 @@ import numpy as np
 import torch
 
 VARIANTS = {"auto": 0, "tile256": 0x100, "tile128": 0x200, "tile64": 0x300, "smallm": 0x400,
-            "tile256w2x4": 0x500, "tile256w4x2": 0x600, "tile64w2x2": 0x700}
+            "tile256w2x4": 0x500, "tile256w4x2": 0x600}
 
 
 def dev(a: np.ndarray) -> torch.Tensor:
