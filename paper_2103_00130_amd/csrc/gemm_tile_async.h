@@ -362,8 +362,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         }
         if (SUM_B) {
 #pragma unroll
-            for (int d = 0; d < 4 * TN; ++d)
-                bsum[d >> 2] = __builtin_amdgcn_sad_u8((uint32_t)fb[f][d >> 2][d & 3] ^ 0x80808080u, 0u, bsum[d >> 2]);
+            for (int d = 0; d < 4 * TN; ++d)  // signed byte sums, one instruction per word (no bias to take off later)
+                bsum[d >> 2] = (uint32_t)__builtin_amdgcn_sdot4(fb[f][d >> 2][d & 3], 0x01010101, (int)bsum[d >> 2], false);
         }
 #pragma unroll
         for (int n = ld_lo; n < ld_hi; ++n) issue_load(ld_s, ld_buf, n);
@@ -547,7 +547,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     for (int t = 0; t < TN; ++t) {
         uint32_t v = (uint32_t)s_bs[wn * WTN + t * 32 + lcol];
         if (SUM_WAVES == 2) v += (uint32_t)s_bs[BN + wn * WTN + t * 32 + lcol];
-        cs[t] = 128 * (int32_t)(v - 128u * (uint32_t)(NS * BK));
+        // (the k-steps of small wave tiles sum signed bytes directly, the others carry a bias of 128 per byte)
+        cs[t] = 128 * (int32_t)(kAhead2 ? v : v - 128u * (uint32_t)(NS * BK));
     }
     // C_temp = accumulator + cs (undoing the a - 128 shift); the sum is formed on the way to
     // memory, the accumulators stay as they are
