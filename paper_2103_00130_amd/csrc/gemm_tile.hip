@@ -8,7 +8,7 @@ ABFT_DECL(a256w24);
 ABFT_DECL(a256w42);
 ABFT_DECL(a128);
 ABFT_DECL(a64);
-ABFT_DECL(a64w4);
+ABFT_DECL(a64r8);
 ABFT_DECL(g128);
 ABFT_DECL(g64);
 #undef ABFT_DECL
@@ -33,7 +33,7 @@ hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, c
             // sixteen stages).  Measured at 1024x1024x4096, unchecked: 14.3 us (2 wavefronts, 2 stages),
             // 12.9 us (2 wavefronts, 8 stages), 11.8 us (4 wavefronts, 8 stages).
             const int64_t tiles = (int64_t)((p.M + 63) / 64) * ((p.N + 63) / 64);
-            if (tiles <= 256 && p.K >= 2048) return launch_gemm_tile_a64w4(check, want_c, want_q, p, s);
+            if (tiles <= 256 && p.K >= 2048) return launch_gemm_tile_a64r8(check, want_c, want_q, p, s);
             return launch_gemm_tile_a64(check, want_c, want_q, p, s);
         }
         case kTile256w24: return launch_gemm_tile_a256w24(check, want_c, want_q, p, s);

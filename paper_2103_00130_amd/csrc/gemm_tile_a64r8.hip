@@ -2,7 +2,7 @@
 #include "gemm_tile_async.h"
 
 namespace abft {
-hipError_t launch_gemm_tile_a64w4(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
+hipError_t launch_gemm_tile_a64r8(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
     return atile::launch_cfg<64, 64, 2, 2, 8>(check, want_c, want_q, p, s);
 }
 }  // namespace abft
