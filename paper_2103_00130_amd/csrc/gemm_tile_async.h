@@ -91,7 +91,9 @@ __device__ inline int32_t floor_mod127(long long v) {
     return r < 0 ? r + 127 : r;
 }
 
-template <int BM, int BN, int WGM, int WGN, int kStages, bool kCheck, int kOut>
+// kBlockSums: the cross-lane part of the row sums is done for the sixteen rows of a block together
+// (sum32_of16) instead of row by row between the stores; the launcher says when.
+template <int BM, int BN, int WGM, int WGN, int kStages, bool kCheck, int kOut, bool kBlockSums>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const GemmParams p, const int tiles_m,
                                                                         const int tiles_n) {
     constexpr int NW = WGM * WGN, NT = NW * 64;
@@ -573,15 +575,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     int32_t* cptr = kWantC ? p.C + (int64_t)(row0 + r_lane) * p.ldc + col0 + c_lane : nullptr;
     uint8_t* qptr = kWantQ ? p.Cq + (int64_t)(row0 + r_lane) * p.ldcq + col0 + c_lane : nullptr;
     const int rows_left = p.M - row0 - r_lane;  // rows of this lane's column that exist
-    auto store_blocks = [&](auto full_c, auto mod_c) __attribute__((always_inline)) {
+    auto store_blocks = [&](auto full_c, auto mod_c, auto scatter_c) __attribute__((always_inline)) {
         constexpr bool FULL = decltype(full_c)::value;  // no bounds to test inside a whole tile
         constexpr bool MOD = decltype(mod_c)::value;    // row sums as residues modulo 127 (Algorithm 1 as printed)
-        // Cross-lane part of the row sums.  Small wave tiles: the sixteen rows of a block together
-        // (sum32_of16), which halves the vector work of an epilogue that is short anyway.  The 128x128
-        // wave tile keeps one reduction per row between its stores: those take the time memory needs,
-        // the arithmetic hides behind them, and the sixteen extra live values would cost registers
-        // the kernel does not have (measured: 0.3 us slower at 4096^3 with the block form).
-        constexpr bool kScatterSum = TM * TN <= 4;
+        // Cross-lane part of the row sums: the sixteen rows of a block together (sum32_of16), or one
+        // reduction per row between the stores (see where the choice is made).
+        constexpr bool kScatterSum = decltype(scatter_c)::value;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             uint32_t rsv[16];  // this lane's part of the sixteen row sums of the block
@@ -631,12 +630,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     };
 
     const bool mod127 = kCheck && p.mod127 != 0;
+    auto store_form = [&](auto full_c, auto mod_c) __attribute__((always_inline)) {
+        store_blocks(full_c, mod_c, std::integral_constant<bool, kBlockSums>{});
+    };
     if (mod127) {
-        if (full) store_blocks(std::true_type{}, std::true_type{});
-        else store_blocks(std::false_type{}, std::true_type{});
+        if (full) store_form(std::true_type{}, std::true_type{});
+        else store_form(std::false_type{}, std::true_type{});
     } else {
-        if (full) store_blocks(std::true_type{}, std::false_type{});
-        else store_blocks(std::false_type{}, std::false_type{});
+        if (full) store_form(std::true_type{}, std::false_type{});
+        else store_form(std::false_type{}, std::false_type{});
     }
 
     if (p.n_inj > 0) {
@@ -753,9 +755,24 @@ hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p,
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(WGM * WGN * 64);
     const size_t lds = kStages * (size_t)(BM + BN) * BK + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t) + 32 * 512;
+    // Row sums in block form or per row.  Small wave tiles: always the block form, which halves the
+    // vector work of an epilogue that is short anyway.  The 128x128 wave tile: per row when the grid
+    // fills the chip - the stores then take the time memory needs and the arithmetic between them is
+    // hidden, while the sixteen extra live values of the block form cost registers the kernel does not
+    // have (0.3 us slower at 4096^3) - and the block form when it does not: with fewer workgroups than
+    // compute units the stores are not limited by memory and the arithmetic shows (3072^3: 45.0 us
+    // per row, 42.4 us in block form).  Two kernels rather than a branch in one: with both forms in
+    // one kernel the per-row form lost 1.7 us at 4096^3.
+    constexpr bool kSmallWaveTile = (BM / WGM / 32) * (BN / WGN / 32) <= 4;
+    const bool block_sums = kSmallWaveTile || grid.x < 256;
 #define ABFT_LAUNCH(CK, OUT)                                                                              \
     do {                                                                                                  \
-        auto kern = gemm_tile_async_kernel<BM, BN, WGM, WGN, kStages, CK, OUT>;                                    \
+        if (block_sums) ABFT_LAUNCH_FORM(CK, OUT, true);                                                  \
+        ABFT_LAUNCH_FORM(CK, OUT, (kSmallWaveTile || !(CK)));                                             \
+    } while (0)
+#define ABFT_LAUNCH_FORM(CK, OUT, BS)                                                                     \
+    do {                                                                                                  \
+        auto kern = gemm_tile_async_kernel<BM, BN, WGM, WGN, kStages, CK, OUT, ((BS) || !(CK))>;          \
         static bool attr_set = false;                                                                     \
         if (!attr_set) {                                                                                  \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                       \
@@ -776,6 +793,7 @@ hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p,
     ABFT_OUT(false);
 #undef ABFT_OUT
 #undef ABFT_LAUNCH
+#undef ABFT_LAUNCH_FORM
 }
 
 }  // namespace atile
