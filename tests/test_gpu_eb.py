@@ -271,3 +271,54 @@ def test_int4_tables_match_oracle(b, d, variant):
             b.abft_eb_table_flip_bit(g.Tp, row, col, bit)
         with pytest.raises(b.AbftError):
             b.abft_eb_table_flip_bit(g.Tp, 0, 0, 4)     # a 4-bit code has bits 0..3
+
+
+def test_large_batch_takes_the_batch_kernel_by_itself(b):
+    """70000 short lookups at d = 32: the library picks the batch kernel (lookups alone fill the chip);
+    same bar as everywhere."""
+    rng = w.rng_for(40)
+    T, scale, bias = w.draw_table(rng, 50000, 32, "uniform")
+    indices, offsets = w.draw_bags(rng, 50000, 70000, 6, "spread")
+    weights = w.draw_weights(rng, indices.size)
+    g = GpuTable(b, T, scale, bias)
+    ref = eb.checked_eb(T, scale, bias, indices, offsets, weights)
+    out = g.run(indices, offsets, weights, "auto")
+    compare(out, ref, T, scale, bias, indices, offsets, weights)
+    assert same_bits(g.run(indices, offsets, weights, "group")["R"], out["R"])
+
+
+def test_table_beyond_4_gib(b):
+    """Record offsets that do not fit 32 bits: a table of 17,000,000 records of 272 bytes (4.6 GB) built
+    on the device; the rows a batch pools are brought back and the oracle runs on that compacted table."""
+    rows, d = 17_000_000, 256
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    T = torch.randint(0, 256, (rows, d), dtype=torch.uint8, device="cuda", generator=gen)
+    scale = torch.rand(rows, device="cuda", generator=gen) * 0.015 + 0.005
+    bias = -0.5 * torch.rand(rows, device="cuda", generator=gen)
+    Tp = b.abft_eb_pack_rowsum(T, scale, bias)
+    torch.cuda.synchronize()
+    assert b.abft_eb_table_dims(Tp)[2] * rows > 2 ** 32
+    rng = w.rng_for(41)
+    indices, offsets = w.draw_bags(rng, rows, 300, 40, "spread")
+    indices[:50] = rows - 1 - np.arange(50)              # the far end of the table
+    uniq, inv = np.unique(indices, return_inverse=True)
+    sel = torch.from_numpy(uniq).cuda()
+    T_small, scale_small, bias_small = T[sel].cpu().numpy(), scale[sel].cpu().numpy(), bias[sel].cpu().numpy()
+    del T
+    ref = eb.checked_eb(T_small, scale_small, bias_small, inv.astype(np.int64), offsets)
+    rowsums = torch.empty(rows, dtype=torch.int32, device="cuda")
+    b.abft_eb_table_get_rowsums(Tp, rowsums)
+    assert np.array_equal(rowsums[sel].cpu().numpy(), ref.C_T)
+    for variant in ("group", "batch"):
+        R = torch.empty((300, d), dtype=torch.float32, device="cuda")
+        flags = torch.empty(300, dtype=torch.int32, device="cuda")
+        b.abft_eb_u8_checked(Tp, dev(indices), dev(offsets), R, flags, flags=VARIANTS[variant])
+        torch.cuda.synchronize()
+        assert same_bits(R.cpu().numpy(), ref.R) and np.array_equal(flags.cpu().numpy(), ref.flags)
+    # a planted fault at the far end is seen
+    b.abft_eb_table_flip_bit(Tp, rows - 1, 255, 7)
+    b.abft_eb_u8_checked(Tp, dev(indices), dev(offsets), R, flags)
+    torch.cuda.synchronize()
+    assert flags[0].item() == 1
+    Tp.destroy()
