@@ -593,3 +593,33 @@ def test_long_checksum_share(binding, gpu_util, oracle, M, N, K, variant):
     refb = oracle.checked_gemm(A, B, flips_b=[(k, j, 6)])
     outb = run.gemm(A, variant=variant)
     assert np.array_equal(outb["C"], refb.C) and np.array_equal(outb["flags"], refb.flags) and outb["err_count"] == refb.err_count
+
+
+@pytest.mark.gpu
+def test_output_beyond_4_gib(binding, gpu_util, oracle):
+    """C of 40000 x 30000 int32 (4.8 GB): element offsets that do not fit 32 bits.  The rows the oracle
+    recomputes are a sample (rows are independent in product and check); flags and count are complete."""
+    import torch
+    M, N, K = 40000, 30000, 32
+    say(f"large output {M}x{N}x{K}")
+    A, B = operands(M, N, K, 77)
+    inj = [(M - 1, N - 1, 1 << 29), (12345, 6789, 1 << 3)]
+    Bp = binding.abft_pack_b_checksum(gpu_util.dev(B))
+    C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    flags = torch.empty(M, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+    ws = binding.Workspace(M, Bp)
+    binding.abft_gemm_u8s8s32_checked(gpu_util.dev(A), Bp, C, flags, cnt, inj=binding.make_injections(inj), n_inj=2,
+                                      workspace=ws.tensor)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, 12345, M - 257, M - 2, M - 1],
+                                     np.random.default_rng(5).integers(0, M, size=56)]))
+    sub = {int(r): i for i, r in enumerate(rows)}
+    ref = oracle.checked_gemm(A[rows], B, flips_c=[(sub[r], c, m) for (r, c, m) in inj])
+    got = C[torch.from_numpy(rows).cuda()].cpu().numpy()
+    assert np.array_equal(got, ref.C)
+    f = flags.cpu().numpy()
+    assert f.sum() == 2 and f[M - 1] == 1 and f[12345] == 1 and int(cnt.item()) == 2
+    assert np.array_equal(f[rows], ref.flags) and not ws.tensor.any().item()
+    del C
+    Bp.destroy()
