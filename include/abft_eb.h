@@ -20,7 +20,9 @@
  *     added to every column at the end.  With weights, scale and bias are first
  *     multiplied by the weight in binary32.
  *   - RSum and CSum are accumulated in binary64 (RSum over the binary32 values of R; CSum one
- *     term scale * C_T + d * bias per pooled row, in index order).
+ *     term scale * C_T + d * bias per pooled row, each term rounded once; the order in which
+ *     the terms are added is index order in one kernel and a tree in the other, a difference
+ *     of at most n * 2^-53 * sum |term|).
  *   - err <=> not (|RSum - CSum| <= rel_bound * max(|RSum|, |CSum|)), or the difference is
  *     not finite.  The paper's choice is rel_bound = 1e-5 (Section V, round-off bound).
  *   - the row sums travel inside the table: a row is one record

@@ -170,8 +170,11 @@ hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream
 hipError_t launch_row_checksum(const uint8_t* A, int64_t lda, int M, int K, const int32_t* S_B,
                                int32_t* row_chk, hipStream_t s);
 
-// EmbeddingBag: lanes (lookups x max(d/16, 4)) from which the batch kernel is chosen over the group kernel
-constexpr int64_t kEbBatchMinLanes = 262144;
+// EmbeddingBag: lookups from which the batch kernel is chosen over the group kernel, by the number of
+// 16-byte pieces of a row's codes
+constexpr int64_t eb_batch_min_lookups(int pieces) {
+    return pieces <= 1 ? 49152 : pieces == 2 ? 32768 : pieces == 4 ? 98304 : pieces == 8 ? 262144 : pieces == 16 ? 7168 : 16384;
+}
 
 // records `code` and a message for abft_last_error(); returns `code`
 int set_error(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));

@@ -76,6 +76,44 @@ __device__ inline int compare_sums(double rs, double cs, double bound) {
     return (!(diff <= bound * fmax(fabs(rs), fabs(cs))) || !(diff < (double)INFINITY)) ? ABFT_EB_ERR : 0;
 }
 
+// Value that lane ^ M holds, without a trip through memory: DPP inside a row of 16 lanes, the swizzle
+// crossbar for M = 4 and 8, the row and half swaps beyond (both give {own, partner} in an order that
+// depends on the lane, hence the XOR).
+template <int M>
+__device__ inline unsigned int from_lane_xor(unsigned int v) {
+    static_assert(M == 1 || M == 2 || M == 4 || M == 8 || M == 16 || M == 32, "one bit of the lane number");
+    if constexpr (M == 1) return (unsigned int)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
+    else if constexpr (M == 2) return (unsigned int)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
+    else if constexpr (M == 4) return (unsigned int)__builtin_amdgcn_ds_swizzle((int)v, 0x101F);
+    else if constexpr (M == 8) return (unsigned int)__builtin_amdgcn_ds_swizzle((int)v, 0x201F);
+    else if constexpr (M == 16) {
+        const auto sw = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        return sw[0] ^ sw[1] ^ v;
+    } else {
+        const auto sw = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+        return sw[0] ^ sw[1] ^ v;
+    }
+}
+
+template <int M>
+__device__ inline double from_lane_xor(double v) {
+    const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
+    const unsigned long long o = (unsigned long long)from_lane_xor<M>((unsigned int)b) |
+                                 ((unsigned long long)from_lane_xor<M>((unsigned int)(b >> 32)) << 32);
+    return __builtin_bit_cast(double, o);
+}
+
+// sum over the 64 lanes, the same value in every lane: a butterfly (lane pairs, then pairs of pairs, ...)
+__device__ inline double wave_sum(double v) {
+    v += from_lane_xor<1>(v);
+    v += from_lane_xor<2>(v);
+    v += from_lane_xor<4>(v);
+    v += from_lane_xor<8>(v);
+    v += from_lane_xor<16>(v);
+    v += from_lane_xor<32>(v);
+    return v;
+}
+
 // the columns held by 16 code bytes of one pooled row: acc[k] = a * code[k] + acc[k].
 // 8-bit codes: 16 columns; 4-bit codes: 32 columns, the even column in the low half of its byte.
 template <int BITS>
@@ -90,7 +128,7 @@ __device__ inline void fma_codes(float (&acc)[128 / BITS], float a, v4u q) {
 
 // ---------------------------------------------------------------------------------------------
 // Batch kernel: G lanes per lookup, one per 16 code bytes of a row.
-template <int G, int BITS, bool kCheck, bool kWeighted>
+template <int G, int BITS, bool kCheck, bool kWeighted, bool kTwoSets>
 __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
     constexpr int CB = 16 * G;            // code bytes per row
     constexpr int CPP = 128 / BITS;       // columns per 16-byte piece
@@ -110,46 +148,92 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
     int flag = 0;
     const uint8_t* const base = p.tab + piece * 16;
 
-    // Every load below is unconditional (clamped position, row 0 in place of a bad index): the
-    // eight index loads go out together, then the sixteen row loads, and only then anything waits.
+    // Rows are handled in sets of U.  Every load is unconditional inside its set (clamped position,
+    // row 0 in place of a bad index): the index loads of a set go out together, then its row loads,
+    // and only then anything waits.
+    // kTwoSets: two sets in flight - the row loads of a set go out while the set before it is being
+    // pooled, and the indices of the set after it are already on their way - so that the latency of
+    // the indices, the latency of the rows and the arithmetic overlap instead of adding up.  A launch
+    // of a few wavefronts per SIMD has nothing else to hide them behind; with many wavefronts the
+    // other wavefronts do that, and the registers of the second set cost more than it gains.
     // A row that is not pooled enters the sums with scale, bias and row sum 0, which leaves every
     // accumulator as it is, bit for bit.
-    for (int64_t pos = beg; pos < end; pos += U) {
+    struct IdxSet {
         int64_t idx[U];
-        bool ok[U];
-        v4u q[U], tl[U];
         float wv[U];
+    };
+    struct RowSet {
+        float wv[U];
+        v4u q[U], tl[U];
+        bool ok[U];
+    };
+    auto load_indices = [&](IdxSet& r, int64_t pos) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t pp = pos + u < end ? pos + u : end - 1;
-            idx[u] = p.indices[pp];
-            if (kWeighted) wv[u] = p.weights[pp];
+            r.idx[u] = p.indices[pp];
+            if (kWeighted) r.wv[u] = p.weights[pp];
         }
+    };
+    auto load_rows = [&](RowSet& r, const IdxSet& ix, int64_t pos) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const bool in = pos + u < end;
-            ok[u] = in && (uint64_t)idx[u] < (uint64_t)p.rows;
-            if (in && !ok[u]) flag |= ABFT_EB_BAD_INDEX;
-            const uint8_t* r = base + (ok[u] ? idx[u] : 0) * p.stride;
-            q[u] = *reinterpret_cast<const v4u*>(r);
-            tl[u] = *reinterpret_cast<const v4u*>(r + (CB - piece * 16));
+            r.ok[u] = in && (uint64_t)ix.idx[u] < (uint64_t)p.rows;
+            if (in && !r.ok[u]) flag |= ABFT_EB_BAD_INDEX;
+            if (kWeighted) r.wv[u] = ix.wv[u];
+            const uint8_t* rec = base + (r.ok[u] ? ix.idx[u] : 0) * p.stride;
+            r.q[u] = *reinterpret_cast<const v4u*>(rec);
+            r.tl[u] = *reinterpret_cast<const v4u*>(rec + (CB - piece * 16));
         }
+    };
+    auto pool = [&](const RowSet& r) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            float a = as_f32(tl[u][0]), c = as_f32(tl[u][1]);
+            float a = as_f32(r.tl[u][0]), c = as_f32(r.tl[u][1]);
             if (kWeighted) {
-                a = wv[u] * a;
-                c = wv[u] * c;
+                a = r.wv[u] * a;
+                c = r.wv[u] * c;
             }
-            a = ok[u] ? a : 0.0f;
-            c = ok[u] ? c : 0.0f;
-            fma_codes<BITS>(acc, a, q[u]);
+            a = r.ok[u] ? a : 0.0f;
+            c = r.ok[u] ? c : 0.0f;
+            fma_codes<BITS>(acc, a, r.q[u]);
             beta_sum = beta_sum + c;
             if (kCheck) {
                 // Eq. 4, the term of one pooled row: scale * C_T + d * bias, rounded once (both products
                 // are exact in binary64), then added to the running sum
-                cs = cs + fma((double)a, (double)(ok[u] ? (int32_t)tl[u][2] : 0), (double)D * (double)c);
+                cs = cs + fma((double)a, (double)(r.ok[u] ? (int32_t)r.tl[u][2] : 0), (double)D * (double)c);
             }
+        }
+    };
+    if (!kTwoSets) {
+        for (int64_t pos = beg; pos < end; pos += U) {
+            IdxSet ia;
+            RowSet ra;
+            load_indices(ia, pos);
+            load_rows(ra, ia, pos);
+            pool(ra);
+        }
+    } else if (beg < end) {
+        IdxSet ia, ib;
+        RowSet ra, rb;
+        load_indices(ia, beg);
+        load_rows(ra, ia, beg);
+        load_indices(ib, beg + U);
+        for (int64_t pos = beg;; pos += 2 * U) {
+            // here the rows of ra and the indices ib are in flight
+            if (pos + U < end) {
+                load_rows(rb, ib, pos + U);
+                load_indices(ia, pos + 2 * U);
+            }
+            pool(ra);
+            if (pos + U >= end) break;
+            if (pos + 2 * U < end) {
+                load_rows(ra, ia, pos + 2 * U);
+                load_indices(ib, pos + 3 * U);
+            }
+            pool(rb);
+            if (pos + 2 * U >= end) break;
         }
     }
 
@@ -166,8 +250,11 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
         *reinterpret_cast<v4f*>(out + 4 * w) = v;
     }
     if (kCheck) {
-#pragma unroll
-        for (int m = 1; m < G; m <<= 1) rs += __shfl_xor(rs, m);
+        if constexpr (G > 1) rs += from_lane_xor<1>(rs);
+        if constexpr (G > 2) rs += from_lane_xor<2>(rs);
+        if constexpr (G > 4) rs += from_lane_xor<4>(rs);
+        if constexpr (G > 8) rs += from_lane_xor<8>(rs);
+        if constexpr (G > 16) rs += from_lane_xor<16>(rs);
         if (piece == 0) {
             p.flags[bag] = flag | compare_sums(rs, cs, p.bound);
             if (p.rsum) p.rsum[bag] = rs;
@@ -185,8 +272,9 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
 //  2. per-row scalars, rows in parallel: the weighted scale and bias of every staged row, and
 //     the two exact binary64 products of its Eq. 4 term;
 //  3. pooling, rows in index order: threads own columns and do one LDS read, one convert and one
-//     fused multiply-add per row; meanwhile the last two wavefronts walk the chains that do not
-//     depend on the column (sum of biases, CSum).
+//     fused multiply-add per row; meanwhile the last two wavefronts form the sums that do not
+//     depend on the column (the biases, in index order like the columns; the terms of CSum, lanes
+//     in parallel).
 template <int G, int BITS, bool kCheck, bool kWeighted>
 __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
     constexpr int CB = 16 * G;                 // code bytes per row
@@ -198,9 +286,9 @@ __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
     constexpr int NW = (ROWS + 255) / 256;     // rows per thread in the per-row pass
     constexpr int BPT = CB > 256 ? CB / 256 : 1;  // code bytes per thread in the pooling phase
     constexpr int CPL = BPT * 8 / BITS;           // columns per thread
+    // (the per-row scalars replace the tail piece of their staged record: no LDS beyond the records,
+    // so that eight workgroups - all the wavefront slots - fit a compute unit at every row width)
     __shared__ v4u s_rec[PIECES];
-    __shared__ float s_a[ROWS], s_c[ROWS];
-    __shared__ double s_t[kCheck ? ROWS : 1];
     __shared__ double s_rs[4], s_cs;
     __shared__ float s_beta;
     __shared__ int s_flag;
@@ -219,6 +307,10 @@ __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
     // the chains that do not depend on the column run on wavefronts that own few or no columns
     const bool beta_wave = wave == 2, cs_wave = wave == 3;
     const uint8_t* const s_bytes = reinterpret_cast<const uint8_t*>(s_rec);
+    // staged tail of row r after the per-row pass: [weighted scale f32][weighted bias f32][Eq. 4 term f64]
+    auto row_scale = [&](int r) __attribute__((always_inline)) { return *reinterpret_cast<const float*>(s_bytes + r * REC + CB); };
+    auto row_bias = [&](int r) __attribute__((always_inline)) { return *reinterpret_cast<const float*>(s_bytes + r * REC + CB + 4); };
+    auto row_term = [&](int r) __attribute__((always_inline)) { return *reinterpret_cast<const double*>(s_bytes + r * REC + CB + 8); };
     if (tid == 0) s_flag = 0;
 
     for (int64_t pos = beg; pos < end; pos += ROWS) {
@@ -265,11 +357,19 @@ __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
                 }
                 a = bad ? 0.0f : a;
                 c = bad ? 0.0f : c;
-                s_a[r] = a;
-                s_c[r] = c;
-                // Eq. 4, the term of one pooled row: scale * C_T + d * bias, rounded once (both products
-                // are exact in binary64)
-                if (kCheck) s_t[r] = fma((double)a, (double)(bad ? 0 : (int32_t)tl[2]), (double)D * (double)c);
+                v4u out;
+                out[0] = __builtin_bit_cast(unsigned int, a);
+                out[1] = __builtin_bit_cast(unsigned int, c);
+                out[2] = out[3] = 0u;
+                if (kCheck) {
+                    // Eq. 4, the term of one pooled row: scale * C_T + d * bias, rounded once (both products
+                    // are exact in binary64)
+                    const double t = fma((double)a, (double)(bad ? 0 : (int32_t)tl[2]), (double)D * (double)c);
+                    const unsigned long long tb = __builtin_bit_cast(unsigned long long, t);
+                    out[2] = (unsigned int)tb;
+                    out[3] = (unsigned int)(tb >> 32);
+                }
+                s_rec[r * P + G] = out;
             }
         }
         if (bad_any) atomicOr(&s_flag, bad_any);
@@ -278,7 +378,7 @@ __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
         if (col_thread) {
 #pragma unroll 8
             for (int r = 0; r < n; ++r) {
-                const float a = s_a[r];
+                const float a = row_scale(r);
                 const uint8_t* codes = s_bytes + r * REC + tid * BPT;
                 unsigned int cw = BPT == 1 ? (unsigned int)*codes : (unsigned int)*reinterpret_cast<const uint16_t*>(codes);
 #pragma unroll
@@ -287,16 +387,23 @@ __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
         }
         if (beta_wave) {
 #pragma unroll 8
-            for (int r = 0; r < n; ++r) beta_sum = beta_sum + s_c[r];
+            for (int r = 0; r < n; ++r) beta_sum = beta_sum + row_bias(r);
         }
         if (kCheck && cs_wave) {
-#pragma unroll 8
-            for (int r = 0; r < n; ++r) cs = cs + s_t[r];
+            // CSum: the lanes of this wavefront take every 64th row each and are added up at the end.  (The
+            // terms are exact to their one rounding; only the order of their sum differs from index order,
+            // by at most n * 2^-53 * sum |term|, eleven decimal orders below the bound of the comparison.
+            // Walking them in index order is a chain of dependent binary64 additions that takes longer
+            // than the pooling it runs beside.)
+            for (int r = lane; r < n; r += 64) cs = cs + row_term(r);
         }
     }
 
     if (beta_wave && lane == 0) s_beta = beta_sum;
-    if (cs_wave && lane == 0) s_cs = cs;
+    if (kCheck && cs_wave) {
+        cs = wave_sum(cs);
+        if (lane == 0) s_cs = cs;
+    }
     __syncthreads();
     const float beta = s_beta;
     double rs = 0.0;
@@ -309,8 +416,7 @@ __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
         }
     }
     if (kCheck) {
-#pragma unroll
-        for (int m = 1; m < 64; m <<= 1) rs += __shfl_xor(rs, m);
+        rs = wave_sum(rs);
         if (lane == 0) s_rs[wave] = rs;
         __syncthreads();
         if (tid == 0) {
@@ -326,10 +432,15 @@ __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
 
 template <int G, int BITS>
 hipError_t launch_g(bool group, bool check, bool weighted, const EbParams& p, hipStream_t s) {
+    // one set of rows per lane only where the rows are wide and the launch has at least four wavefronts
+    // per SIMD (measured at 16384 and 65536 lookups of 256 columns: 2 and 4 % faster than two sets;
+    // everywhere else two sets are faster, by up to 30 % at 4096 lookups)
+    const bool two_sets = G < 16 || p.n_bags * G < (int64_t)4096 * 64;
 #define ABFT_EB_LAUNCH(CK, WT)                                                                                     \
     do {                                                                                                           \
         if (group) eb_group_kernel<G, BITS, CK, WT><<<dim3((unsigned)p.n_bags), dim3(256), 0, s>>>(p);             \
-        else eb_batch_kernel<G, BITS, CK, WT><<<dim3((unsigned)((p.n_bags * G + 255) / 256)), dim3(256), 0, s>>>(p); \
+        else if (two_sets) eb_batch_kernel<G, BITS, CK, WT, true><<<dim3((unsigned)((p.n_bags * G + 255) / 256)), dim3(256), 0, s>>>(p); \
+        else eb_batch_kernel<G, BITS, CK, WT, (G < 16)><<<dim3((unsigned)((p.n_bags * G + 255) / 256)), dim3(256), 0, s>>>(p); \
         return hipGetLastError();                                                                                  \
     } while (0)
     if (check && weighted) ABFT_EB_LAUNCH(true, true);
@@ -503,9 +614,12 @@ int abft_eb_u8_checked(const abft_eb_table* Tp, const int64_t* indices, int64_t 
     const int G = Tp->code_bytes / 16;
     if (n_bags > 0x7fffffffll || (n_bags * G + 255) / 256 > 0x7fffffffll)
         return abft::set_error(ABFT_EUNSUPPORTED, "%s: n_bags=%lld too large for one launch", fn, (long long)n_bags);
-    // the batch kernel needs enough lookups to fill the chip with lanes; below that one workgroup per lookup
-    // keeps more bytes in flight (measured crossover: 65536 lookups at d <= 64, 16384 at d = 256)
-    bool group = n_bags * (G < 4 ? 4 : G) < abft::kEbBatchMinLanes;
+    // The batch kernel needs enough lookups to fill the chip with lanes; below that one workgroup per lookup
+    // keeps more bytes in flight.  Crossovers measured with 100 rows per lookup on a 2 GiB table, checked
+    // (code bytes per row: lookups): 16: between 32768 and 65536; 32: 32768, within 2 % of each other
+    // beyond; 64 and 128: the group kernel still ahead by 1 % at 65536 and 131072; 256: between 6144 and
+    // 8192 (7 % either way); 512: group ahead by 4 % at 8192.
+    bool group = n_bags < abft::eb_batch_min_lookups(G);
     if (variant == ABFT_EB_VARIANT_BATCH) group = false;
     if (variant == ABFT_EB_VARIANT_GROUP) group = true;
     abft::EbParams p;
