@@ -139,8 +139,13 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
             bsum += s_bsum[w][lane];
         }
         // column sum of the streamed B for column lcol: the four k-groups sit in lanes lcol + 16*g
-        bsum += (uint32_t)__shfl_xor((int)bsum, 16);
-        bsum += (uint32_t)__shfl_xor((int)bsum, 32);
+        // (row swap and half swap: both return {own, partner} in an order that depends on the lane)
+        {
+            const auto r16 = __builtin_amdgcn_permlane16_swap(bsum, bsum, false, false);
+            bsum = r16[0] + r16[1];
+            const auto r32 = __builtin_amdgcn_permlane32_swap(bsum, bsum, false, false);
+            bsum = r32[0] + r32[1];
+        }
         // every lane summed 16 biased bytes per k-block slot; 4 waves x n_batches x BATCH slots x 4 k-groups
         const uint32_t bias = 128u * 16u * 4u * 4u * (uint32_t)(n_batches * BATCH);
         const int32_t cs128 = 128 * (int32_t)(bsum - bias);

@@ -540,7 +540,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     constexpr int SUM_WAVES = WGM == 1 ? 1 : 2;
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
-        bsum[t] += (uint32_t)__shfl_xor((int)bsum[t], 32);
+        const auto halves = __builtin_amdgcn_permlane32_swap(bsum[t], bsum[t], false, false);  // {own, lane ^ 32} in either order
+        bsum[t] = halves[0] + halves[1];
         if (wm < SUM_WAVES && lhalf == 0) s_bs[wm * BN + wn * WTN + t * 32 + lcol] = (int32_t)bsum[t];
     }
     __syncthreads();
