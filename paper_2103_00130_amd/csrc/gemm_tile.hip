@@ -9,6 +9,7 @@ ABFT_DECL(a256w42);
 ABFT_DECL(a128);
 ABFT_DECL(a64);
 ABFT_DECL(a64r8);
+ABFT_DECL(a64k2);
 ABFT_DECL(g128);
 ABFT_DECL(g64);
 #undef ABFT_DECL
@@ -28,11 +29,19 @@ hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, c
         case kTile64: {
             // The 64x64 kernels are bound by instruction issue and the LDS reads of a wavefront, not by
             // the matrix cores, so they run as four wavefronts of 32x32 on four SIMDs (5-10 % faster than
-            // two of 32x64).  At most one workgroup per compute unit and a long K loop: a ring of eight
-            // stages (it takes most of a unit's LDS, and filling it costs more than it saves below about
-            // sixteen stages).  Measured at 1024x1024x4096, unchecked: 14.3 us (2 wavefronts, 2 stages),
-            // 12.9 us (2 wavefronts, 8 stages), 11.8 us (4 wavefronts, 8 stages).
+            // two of 32x64).  At most one workgroup per compute unit and a long K loop: K is split between
+            // two such groups of wavefronts, so that every SIMD has two wavefronts to issue from (10-15 %
+            // faster from K = 1536 on: 1024x1024x4096 unchecked 11.7 -> 10.4 us, 512x1024x4096 10.9 -> 8.9;
+            // slower at K <= 1024, where the hand-over at the end costs more than the loop gains; four
+            // groups, or four lone wavefronts of 64x64, are slower than two groups).  The launcher refuses
+            // a K that does not split evenly or whose checksum share per tile column is too long for the
+            // staged digits; then one group with a ring of eight stages takes a long K (it takes most of
+            // a unit's LDS, and filling it costs more than it saves below about sixteen stages).
             const int64_t tiles = (int64_t)((p.M + 63) / 64) * ((p.N + 63) / 64);
+            if (tiles <= 256 && p.K >= 1536) {
+                const hipError_t e = launch_gemm_tile_a64k2(check, want_c, want_q, p, s);
+                if (e != hipErrorNotSupported) return e;
+            }
             if (tiles <= 256 && p.K >= 2048) return launch_gemm_tile_a64r8(check, want_c, want_q, p, s);
             return launch_gemm_tile_a64(check, want_c, want_q, p, s);
         }

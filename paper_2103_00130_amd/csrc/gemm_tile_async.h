@@ -93,10 +93,23 @@ __device__ inline int32_t floor_mod127(long long v) {
 
 // kBlockSums: the cross-lane part of the row sums is done for the sixteen rows of a block together
 // (sum32_of16) instead of row by row between the stores; the launcher says when.
-template <int BM, int BN, int WGM, int WGN, int kStages, bool kCheck, int kOut, bool kBlockSums>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const GemmParams p, const int tiles_m,
-                                                                        const int tiles_n) {
-    constexpr int NW = WGM * WGN, NT = NW * 64;
+// LDS bytes of one group of WGM x WGN wavefronts: the stage ring, the scratch of the epilogue, the staged
+// checksum digits (kLimbStages stages of 512 bytes)
+template <int BM, int BN, int WGN, int kStages, int WGK>
+constexpr size_t group_lds_bytes() {
+    return kStages * (size_t)(BM + BN) * BK + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t) + (32 / WGK) * 512;
+}
+
+// WGK > 1: K split inside the workgroup.  WGK groups of WGM x WGN wavefronts work on the same tile; group g
+// takes the g-th run of stages with a stage ring of its own, so that a SIMD has WGK wavefronts to issue
+// from (a tile of 64x64 keeps one wavefront per SIMD busy with about a hundred instructions per stage,
+// and one wavefront issues at most one instruction every four cycles).  The groups pass the same
+// barriers (same number of stages each, the launcher sees to it); at the end groups 1.. hand their
+// accumulators to group 0 through LDS and leave, and group 0 runs the epilogue.
+template <int BM, int BN, int WGM, int WGN, int kStages, bool kCheck, int kOut, bool kBlockSums, int WGK>
+__global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(const GemmParams p, const int tiles_m,
+                                                                             const int tiles_n) {
+    constexpr int NW = WGM * WGN, NT = NW * 64;    // wavefronts and threads of one group
     constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
     constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 blocks per wave
     constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK;
@@ -109,11 +122,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     static_assert(A_LD >= 1 && B_LD >= 1 && CB >= 1 && (WTM / 16) % WGN == 0, "tile too small for the workgroup");
     static_assert(BN >= 64 && NT <= 4 * BN, "epilogue scratch layout");
 
-    // LDS: [S][A_STAGE] then [S][B_STAGE], then the scratch of the epilogue
-    extern __shared__ __align__(1024) uint8_t smem[];
+    // LDS of a group: [S][A_STAGE] then [S][B_STAGE], then the scratch of the epilogue, then the digits
+    extern __shared__ __align__(1024) uint8_t smem_all[];
+    constexpr size_t GROUP_LDS = (group_lds_bytes<BM, BN, WGN, kStages, WGK>() + 1023) / 1024 * 1024;
+    const int grp = WGK > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x / NT) : 0;
+    uint8_t* const smem = smem_all + grp * GROUP_LDS;
     const uint32_t lds_base = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) uint8_t*)smem);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tid = (int)threadIdx.x - grp * NT, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
     // Workgroups go round-robin over the 8 XCDs; give every XCD a compact block of tiles
     // (consecutive ids inside an XCD walk down a strip of 4 tile rows) so that its L2 sees
@@ -131,7 +147,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         tile_m = strip * strip_h + r - tile_n * h;
     }
     const int row0 = tile_m * BM, col0 = tile_n * BN;
-    const int NS = p.KB2;  // stages of 128 k-values
+    const int NS_all = p.KB2;          // stages of 128 k-values
+    const int NS = NS_all / WGK;       // ... of this group (the launcher splits only what divides)
+    const int s_base = grp * NS;       // its first stage
 
     // ---- direct global->LDS loads ---------------------------------------------------
     // One instruction moves 16 bytes per lane to LDS address m0 + lane*16.  They are issued
@@ -152,14 +170,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     // of B), hence the second set of offsets.
     uint32_t a_voff[A_LD], a_voff_last[A_LD], a_lds[A_LD];
     {
-        const int c16_max = p.K - 16 - (NS - 1) * BK;
+        const int c16_max = p.K - 16 - (NS_all - 1) * BK;
 #pragma unroll
         for (int i = 0; i < A_LD; ++i) {
             const int r = (wave * A_LD + i) * 8 + (lane >> 3);
             const int c16 = ((lane & 7) ^ ((r >> 1) & 7)) * 16;
             const uint32_t rowoff = (uint32_t)min(row0 + r, p.M - 1) * (uint32_t)p.lda;
             a_voff[i] = rowoff + (uint32_t)c16;
-            a_voff_last[i] = rowoff + (uint32_t)min(c16, c16_max);
+            a_voff_last[i] = rowoff + (uint32_t)(grp == WGK - 1 ? min(c16, c16_max) : c16);  // only the last group meets K's end
             a_lds[i] = lds_base + (wave * A_LD + i) * 1024;
         }
     }
@@ -175,7 +193,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     {
         const int bc0 = wave * B_LD, kbl = bc0 / B_CHUNKS_PER_KB, cc0 = bc0 % B_CHUNKS_PER_KB;
         b_wave = p.packed + packed_unit_offset(tile_n / TILES_PER_NT, 0, (tile_n % TILES_PER_NT) * (BN / 32), p.KB2 * 2) +
-                 (int64_t)kbl * B_KB_STRIDE + cc0 * 1024;
+                 (int64_t)kbl * B_KB_STRIDE + cc0 * 1024 + (int64_t)s_base * (2 * B_KB_STRIDE);
         b_lds = lds_base + S * A_STAGE + kbl * (BN * 64) + cc0 * 1024;
     }
 
@@ -185,7 +203,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     auto issue_load = [&](int s, int buf, int n) __attribute__((always_inline)) {
         if (n < A_LD) {
             const uint32_t voff = (s == NS - 1) ? a_voff_last[n] : a_voff[n];
-            dma(a_lds[n] + buf * A_STAGE, voff, p.A + (int64_t)s * BK, std::integral_constant<int, 0>{});
+            dma(a_lds[n] + buf * A_STAGE, voff, p.A + (int64_t)(s_base + s) * BK, std::integral_constant<int, 0>{});
         } else {
             const int j = n - A_LD, g = j >> 2;
             const int8_t* const base = b_wave + (int64_t)s * (2 * B_KB_STRIDE) + g * 4096;
@@ -251,15 +269,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     // that the loop holds no global load the compiler knows of: it would put a wait for *all*
     // vector-memory traffic, the direct-to-LDS loads of the next stage included, in front of the
     // digit MFMAs.
-    constexpr int kLimbStages = 32;
-    const int ck_lo = kCheck ? (int)(((int64_t)tile_n * NS) / tiles_n) : 0;
-    const int ck_hi = kCheck ? (int)(((int64_t)(tile_n + 1) * NS) / tiles_n) : 0;
+    constexpr int kLimbStages = 32 / WGK;
+    // (stage numbers of this group: the share is cut against the group's run of stages)
+    const int ck_lo = kCheck ? min(max((int)(((int64_t)tile_n * NS_all) / tiles_n) - s_base, 0), NS) : 0;
+    const int ck_hi = kCheck ? min(max((int)(((int64_t)(tile_n + 1) * NS_all) / tiles_n) - s_base, 0), NS) : 0;
     uint8_t* const s_limb = smem + S * (A_STAGE + B_STAGE) + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t);
     int limb_base = ck_lo;  // stage whose digits sit at the start of s_limb
     auto stage_limbs = [&](int s0) __attribute__((always_inline)) {
         const int n = min(ck_hi - s0, kLimbStages);
         for (int i = tid; i < n * 32; i += NT)
-            reinterpret_cast<v4i*>(s_limb)[i] = reinterpret_cast<const v4i*>(p.limbs + (int64_t)s0 * 512)[i];
+            reinterpret_cast<v4i*>(s_limb)[i] = reinterpret_cast<const v4i*>(p.limbs + (int64_t)(s_base + s0) * 512)[i];
         limb_base = s0;
     };
     auto load_limbs = [&](int s) __attribute__((always_inline)) {
@@ -526,6 +545,53 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     // (the last stage re-issued loads into a dead buffer; the epilogue keeps its scratch outside
     // the stage buffers, so nobody waits for them before the very end of the kernel)
 
+    // ------------------------- K split: the groups' results come together -------------------------
+    if constexpr (WGK > 1) {
+        static_assert(TM * TN <= 4, "the K split is for small wave tiles");
+        constexpr int kVals = 16 * TM * TN + TN + 4 * CB;  // accumulators, column sums, digit accumulators per lane
+        static_assert((size_t)kVals * NT * sizeof(int32_t) <= GROUP_LDS, "a group's values fit its own LDS");
+        // every direct-to-LDS load of every group has landed and every wavefront has left the loop: the
+        // LDS of groups 1.. is free (that of group 0 holds the scratch its epilogue is about to use)
+        wait_vmem();
+        __syncthreads();
+        int32_t* const xch = reinterpret_cast<int32_t*>(smem_all + GROUP_LDS);
+        if (grp > 0) {
+            int32_t* const mine = xch + (size_t)(grp - 1) * kVals * NT + tid;
+            int k = 0;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int t = 0; t < TN; ++t)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) mine[(k++) * NT] = acc[i][t][e];
+#pragma unroll
+            for (int t = 0; t < TN; ++t) mine[(k++) * NT] = (int32_t)bsum[t];
+#pragma unroll
+            for (int c = 0; c < CB; ++c)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) mine[(k++) * NT] = cacc[c][e];
+        }
+        __syncthreads();
+        if (grp > 0) return;  // (nothing of this group is in flight: its loads were awaited above)
+#pragma unroll
+        for (int g = 1; g < WGK; ++g) {
+            const int32_t* const theirs = xch + (size_t)(g - 1) * kVals * NT + tid;
+            int k = 0;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int t = 0; t < TN; ++t)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[i][t][e] += theirs[(k++) * NT];
+#pragma unroll
+            for (int t = 0; t < TN; ++t) bsum[t] += (uint32_t)theirs[(k++) * NT];
+#pragma unroll
+            for (int c = 0; c < CB; ++c)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) cacc[c][e] += theirs[(k++) * NT];
+        }
+    }
+
     // ---------------------------------- epilogue ----------------------------------
     // accumulator layout of the 32x32 MFMA: lane l, element e of block (i, t) is
     // row 8*(e/4) + 4*(l/32) + e%4, column l%32 of that block.
@@ -551,7 +617,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
         uint32_t v = (uint32_t)s_bs[wn * WTN + t * 32 + lcol];
         if (SUM_WAVES == 2) v += (uint32_t)s_bs[BN + wn * WTN + t * 32 + lcol];
         // (the k-steps of small wave tiles sum signed bytes directly, the others carry a bias of 128 per byte)
-        cs[t] = 128 * (int32_t)(kAhead2 ? v : v - 128u * (uint32_t)(NS * BK));
+        cs[t] = 128 * (int32_t)(kAhead2 ? v : v - 128u * (uint32_t)(NS_all * BK));
     }
     // C_temp = accumulator + cs (undoing the a - 128 shift); the sum is formed on the way to
     // memory, the accumulators stay as they are
@@ -751,11 +817,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_async_kernel(const Ge
     wait_vmem();
 }
 
-template <int BM, int BN, int WGM, int WGN, int kStages>
+template <int BM, int BN, int WGM, int WGN, int kStages, int WGK = 1>
 hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(WGM * WGN * 64);
-    const size_t lds = kStages * (size_t)(BM + BN) * BK + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t) + 32 * 512;
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(WGM * WGN * WGK * 64);
+    const size_t lds = WGK * ((group_lds_bytes<BM, BN, WGN, kStages, WGK>() + 1023) / 1024 * 1024);
+    if (WGK > 1) {
+        // every group must pass the same barriers: equal runs of stages, and a share of the checksum
+        // product that its staged digits hold without a refill (32 / WGK stages)
+        const int ns = p.KB2;
+        if (ns % WGK != 0 || ns / WGK < 2 || (ns + tiles_n - 1) / tiles_n + 1 > 32 / WGK) return hipErrorNotSupported;
+    }
     // Row sums in block form or per row.  Small wave tiles: always the block form, which halves the
     // vector work of an epilogue that is short anyway.  The 128x128 wave tile: per row when the grid
     // fills the chip - the stores then take the time memory needs and the arithmetic between them is
@@ -773,7 +845,7 @@ hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p,
     } while (0)
 #define ABFT_LAUNCH_FORM(CK, OUT, BS)                                                                     \
     do {                                                                                                  \
-        auto kern = gemm_tile_async_kernel<BM, BN, WGM, WGN, kStages, CK, OUT, ((BS) || !(CK))>;          \
+        auto kern = gemm_tile_async_kernel<BM, BN, WGM, WGN, kStages, CK, OUT, ((BS) || !(CK)), WGK>;     \
         static bool attr_set = false;                                                                     \
         if (!attr_set) {                                                                                  \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                       \

@@ -574,6 +574,41 @@ def test_small_grid_long_k(binding, gpu_util, oracle, M, N, K, variant):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("M,N,K", [(200, 130, 2000), (192, 64, 1792), (130, 200, 3008), (300, 520, 1536)])
+def test_k_split_between_wavefront_groups(binding, gpu_util, oracle, M, N, K):
+    """The 64x64 kernel that splits K between two groups of wavefronts (few tiles, K of twelve stages or
+    more, an even number of them): a K that ends inside the last stage (the second group meets it), one
+    tile column whose whole checksum share straddles the two groups, ragged M and N, injections, faults in
+    the weight early and late in K (one per group), requantized output, and the check modulo 127."""
+    say(f"K split {M}x{N}x{K}")
+    A, B = operands(M, N, K, 7 * M + N + K, full_range_b=False)
+    inj = [(M - 1, N - 1, 1 << 29), (0, 0, 1 << 3), (M // 2, N // 2, 0x00400000)]
+    ref = oracle.checked_gemm(A, B, flips_c=inj)
+    run = gpu_util.GpuRun(binding, B)
+    out = run.gemm(A, variant="tile64", injections=inj)
+    assert np.array_equal(out["C"], ref.C) and np.array_equal(out["flags"], ref.flags)
+    assert out["err_count"] == ref.err_count == 3 and not out["ws"].any()
+    auto = run.gemm(A)
+    assert np.array_equal(auto["C"], oracle.checked_gemm(A, B).C) and auto["err_count"] == 0 and not auto["flags"].any()
+    rng = np.random.default_rng(K)
+    mult = wlmod.draw_mult(rng, N, "channel")
+    bias = rng.integers(-5000, 5000, size=N).astype(np.int32)
+    q = run.gemm(A, variant="tile64", requant=(128, 128, mult, bias), want_c=False)
+    clean = oracle.checked_gemm(A, B)
+    assert np.array_equal(q["Cq"], oracle.requantize(clean.C, clean.colsum, 128, 128, mult, bias, precision="f32"))
+    assert q["err_count"] == 0
+    C127, flags127, count127 = oracle.checked_gemm_mod127(A, B, flips_c=inj)
+    out127 = run.gemm(A, variant="tile64", injections=inj, mod127=True)
+    assert np.array_equal(out127["C"], C127) and np.array_equal(out127["flags"], flags127) and out127["err_count"] == count127
+    for k, j, bit in ((5, N // 3, 6), (K - 3, N - 1, 2)):
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        refb = oracle.checked_gemm(A, B, flips_b=[(k, j, bit)])
+        outb = run.gemm(A, variant="tile64")
+        assert np.array_equal(outb["C"], refb.C) and np.array_equal(outb["flags"], refb.flags) and outb["err_count"] == refb.err_count
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("M,N,K,variant", [(100, 64, 8320, "tile64"), (300, 256, 12288, "tile256"), (130, 128, 4224, "tile128")])
 def test_long_checksum_share(binding, gpu_util, oracle, M, N, K, variant):
     """One tile column and a long K: its share of the checksum product is longer than one lot of
