@@ -65,7 +65,9 @@ extern "C" {
 #define ABFT_EB_ERR 1          /* Algorithm 2's err: RSum and CSum differ by more than the bound */
 #define ABFT_EB_BAD_INDEX 2    /* an index of the lookup lies outside the table; it was not pooled */
 
-/* Opaque table: the fused row records described above.  The library owns its device memory. */
+/* Opaque table: the fused row records described above.  The library owns its device memory; the table
+ * belongs to the device that was current when it was built (a lookup with another device current
+ * returns ABFT_EINVAL). */
 typedef struct abft_eb_table abft_eb_table;
 
 /* Section V, "pre-computed row sums of T": build the table once.

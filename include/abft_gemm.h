@@ -19,7 +19,9 @@
  *     elements.  `stream` is a hipStream_t passed as void* (NULL = default
  *     stream).  Calls enqueue work on `stream` and return; they never
  *     synchronise.  Only abft_pack_b_checksum / abft_packed_b_destroy
- *     allocate or free device memory.
+ *     allocate or free device memory.  A packed B belongs to the device that
+ *     was current when it was packed; the checked GEMM returns ABFT_EINVAL
+ *     when called with another device current.
  *   - Return value: ABFT_OK, or a negative code for a usage or runtime error;
  *     abft_last_error() then gives a message (thread-local, host).  Nothing is
  *     enqueued when a call returns ABFT_EINVAL or ABFT_EUNSUPPORTED.

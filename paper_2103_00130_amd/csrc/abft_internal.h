@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace abft {
 
 // ---- packed weight layout -----------------------------------------------------------
@@ -174,6 +176,19 @@ hipError_t launch_row_checksum(const uint8_t* A, int64_t lda, int M, int K, cons
 // 16-byte pieces of a row's codes
 constexpr int64_t eb_batch_min_lookups(int pieces) {
     return pieces <= 1 ? 49152 : pieces == 2 ? 32768 : pieces == 4 ? 98304 : pieces == 8 ? 262144 : pieces == 16 ? 7168 : 16384;
+}
+
+// Lets `kern` use `bytes` of dynamic LDS on the current device: the attribute belongs to the device, so it
+// is set once per device and kernel (`done`: one bit per device ordinal, shared by the threads of the host)
+inline hipError_t allow_dynamic_lds(const void* kern, size_t bytes, std::atomic<uint64_t>& done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return e;
 }
 
 // records `code` and a message for abft_last_error(); returns `code`

@@ -163,6 +163,10 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
     if (!A || !Bp) return fail(ABFT_EINVAL, "%s: null A or packed B", fn);
     if (M < 1) return fail(ABFT_EINVAL, "%s: M=%d must be >= 1", fn, M);
     if (lda < Bp->K) return fail(ABFT_EINVAL, "%s: lda=%lld < K=%d", fn, (long long)lda, Bp->K);
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != Bp->device)
+        return fail(ABFT_EINVAL, "%s: the packed B lives on device %d, the current device is %d", fn, Bp->device, dev);
     const bool check = !(flags & ABFT_NOCHECK);
     const bool want_c = C != nullptr, want_q = rq != nullptr;
     if (!want_c && !want_q) return fail(ABFT_EINVAL, "%s: C is NULL and no requantization was asked for", fn);

@@ -608,6 +608,10 @@ int abft_eb_u8_checked(const abft_eb_table* Tp, const int64_t* indices, int64_t 
     if (check && !(rel_bound >= 0.0)) return abft::set_error(ABFT_EINVAL, "%s: rel_bound must be >= 0", fn);
     if (ldr < Tp->d || ldr % 4 != 0 || (reinterpret_cast<uintptr_t>(R) & 15) != 0)
         return abft::set_error(ABFT_EINVAL, "%s: R needs ldr >= d, ldr a multiple of 4 and 16-byte alignment", fn);
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != Tp->device)
+        return abft::set_error(ABFT_EINVAL, "%s: the table lives on device %d, the current device is %d", fn, Tp->device, dev);
     const unsigned variant = flags & ABFT_EB_VARIANT_MASK;
     if (variant != 0 && variant != ABFT_EB_VARIANT_BATCH && variant != ABFT_EB_VARIANT_GROUP)
         return abft::set_error(ABFT_EINVAL, "%s: unknown variant %#x", fn, variant);

@@ -846,13 +846,9 @@ hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p,
 #define ABFT_LAUNCH_FORM(CK, OUT, BS)                                                                     \
     do {                                                                                                  \
         auto kern = gemm_tile_async_kernel<BM, BN, WGM, WGN, kStages, CK, OUT, ((BS) || !(CK)), WGK>;     \
-        static bool attr_set = false;                                                                     \
-        if (!attr_set) {                                                                                  \
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                       \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);     \
-            if (e != hipSuccess) return e;                                                                \
-            attr_set = true;                                                                              \
-        }                                                                                                 \
+        static std::atomic<uint64_t> lds_allowed{0};                                                      \
+        const hipError_t e_attr = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds, lds_allowed);\
+        if (e_attr != hipSuccess) return e_attr;                                                          \
         kern<<<grid, block, lds, s>>>(p, tiles_m, tiles_n);                                               \
         return hipGetLastError();                                                                         \
     } while (0)
