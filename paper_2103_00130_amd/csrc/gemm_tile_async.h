@@ -282,12 +282,12 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
         limb_base = s0;
     };
     auto load_limbs = [&](int s) __attribute__((always_inline)) {
-        const int q = ((lane >> 4) * kLimbs + (lane & 15)) << 4;  // this lane's digit inside a k-block
+        // this lane's digit inside a k-block.  Lanes of columns 4..15 read the last digit again: what they
+        // feed the MFMA lands in result columns that nobody reads, and an unconditional read costs no
+        // branch and no wait of its own.
+        const int q = ((lane >> 4) * kLimbs + min(lane & 15, kLimbs - 1)) << 4;
 #pragma unroll
-        for (int kbl = 0; kbl < 2; ++kbl) {
-            limb[kbl] = v4i{0, 0, 0, 0};
-            if ((lane & 15) < kLimbs) limb[kbl] = *reinterpret_cast<const v4i*>(s_limb + ((s - limb_base) * 2 + kbl) * 256 + q);
-        }
+        for (int kbl = 0; kbl < 2; ++kbl) limb[kbl] = *reinterpret_cast<const v4i*>(s_limb + ((s - limb_base) * 2 + kbl) * 256 + q);
     };
     // The digit MFMA with its accumulator in ordinary vector registers.  All 256 accumulation
     // registers hold the tile; left to the compiler, the digit accumulators would be swapped into
@@ -469,19 +469,37 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
             // MFMAs of a later stage; cover the longest write-to-read distance of a 4-pass MFMA once
             asm volatile("s_nop 7\n\ts_nop 7");
         };
+        // The same in two halves for the small wave tiles, whose stage is short enough for the latency
+        // of these reads to show: the reads go out behind the last fragment reads of the stage, the
+        // digit MFMAs follow the wait that those need anyway.
+        v4i dig_a[2][CB];
+        auto digit_reads = [&](int buf) __attribute__((always_inline)) {
+            const uint8_t* sA = smem + buf * A_STAGE;
+#pragma unroll
+            for (int kbl = 0; kbl < 2; ++kbl)
+#pragma unroll
+                for (int c = 0; c < CB; ++c) dig_a[kbl][c] = *reinterpret_cast<const v4i*>(sA + ck_off[kbl] + c * 16 * BK);
+        };
+        auto digit_mfmas = [&]() __attribute__((always_inline)) {
+#pragma unroll
+            for (int kbl = 0; kbl < 2; ++kbl)
+#pragma unroll
+                for (int c = 0; c < CB; ++c) mfma_digits(cacc[c], dig_a[kbl][c] ^ (int)0x80808080, limb[kbl]);
+            asm volatile("s_nop 7\n\ts_nop 7");
+        };
         if constexpr (kAhead2) {
             for (int s = s_begin; s < s_end; ++s) {
                 const int nxt = cur + 1 == S ? 0 : cur + 1;
                 const int s_new = min(s + S, NS - 1);  // refills the slot of this stage once it is released
                 if (CHK) load_limbs(s);
                 phase_small(0, 2, cur, 2, even_c{}, 0, 0, 0, 0);
-                if (CHK) wait_lds();
-                else wait_lds_but(frag_reads_c{});
+                wait_lds_but(frag_reads_c{});
                 __builtin_amdgcn_sched_barrier(0);
                 phase_small(1, 3, cur, 3, odd_c{}, 0, 0, 0, 0);
+                if (CHK) digit_reads(cur);
                 wait_lds();  // every fragment of this stage is in registers
                 __builtin_amdgcn_sched_barrier(0);
-                if (CHK) digit_block(cur);
+                if (CHK) digit_mfmas();
                 wait_vmem_but(pending_c{});
                 __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
