@@ -86,8 +86,8 @@ int abft_packed_b_get_checksum(const abft_packed_b* Bp, int32_t* S_B, void* stre
 /* Copy e^T B (int32 [N]; rank-1 term of Eq. 1). */
 int abft_packed_b_get_col_offsets(const abft_packed_b* Bp, int32_t* colsum, void* stream);
 
-/* Fault-injection hooks (Section VI-B: "flipping a random bit" of a randomly
- * selected element, in B after its checksum has been calculated).
+/* Fault-injection hooks (the fault model of Section VI-B: one bit of one
+ * randomly chosen element is inverted, in B after its checksum was computed).
  * flip_bit inverts bit `bit` (0..7) of logical B[k][j] inside the packed
  * layout and leaves the checksum stale; flip_checksum_bit inverts bit `bit`
  * (0..31) of the stored checksum entry S_B[k] as the kernels see it (the paper
@@ -163,8 +163,8 @@ int abft_requantize_u8(const int32_t* C, int64_t ldc, int M, int N, const abft_p
 
 /* Re-verification of a C_temp that has been sitting in memory (the paper's
  * "flip in the 32-bit intermediate" fault model applied after the GEMM):
- * row_chk[i] = (A S_B)[i] as produced by a checked GEMM with want_row_chk, or
- * supplied by the caller; flags rows whose sum differs.  */
+ * row_chk[i] = (A S_B)[i] as produced by abft_row_checksum, or supplied by the
+ * caller; flags rows whose sum differs.  */
 int abft_verify_rows(const int32_t* C, int64_t ldc, int M, int N, const int32_t* row_chk,
                      int32_t* row_flags, int32_t* err_count, void* stream);
 

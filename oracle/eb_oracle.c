@@ -70,7 +70,9 @@ void eb_oracle_forward_f64(const uint8_t* T, int64_t rows, int d, int bits, cons
     }
 }
 
-/* The same in float, in the order stated in the header. */
+/* The same in float, in the order stated in the header.  This is a regrouping of the definition
+ * (one fma per column and row, biases summed apart): tests use it to check that an implementation
+ * reproduces that documented order bit for bit.  The parity reference is _f64 above. */
 void eb_oracle_forward_f32(const uint8_t* T, int64_t rows, int d, int bits, const float* alpha, const float* beta,
                            const int64_t* indices, const int64_t* offsets, int64_t n_bags, const float* w, float* R) {
     for (int64_t b = 0; b < n_bags; ++b) {

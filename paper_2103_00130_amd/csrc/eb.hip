@@ -19,7 +19,8 @@
 //    `if (valid)` is followed by a wait, which would put the loads of a lookup one after the other.
 //  Both accumulate every output column in the same order (index order, one fused multiply-add
 //  per row, biases summed apart), so they give the same bits; RSum and CSum are taken in
-//  binary64, CSum in index order.
+//  binary64.  CSum adds one exactly rounded term per pooled row: in index order in the batch
+//  kernel, lanes in parallel (a tree) in the group kernel - Eq. 4 fixes the terms, not their order.
 #include <cmath>
 #include <cstring>
 #include <new>

@@ -1,11 +1,13 @@
 """GPU parity of the ABFT-checked EmbeddingBag (include/abft_eb.h) against the CPU oracle
 (oracle/eb_oracle.*), through the C ABI.
 
-Bar: the table's row sums and CSum are bit-exact; R is bit-exact against the oracle's float
-evaluation (same stated order) and within the derived round-off tolerance of the oracle's
-double evaluation; RSum agrees to double rounding (the kernels add the same doubles in a tree,
-the oracle in sequence); the flags are equal wherever the oracle says the comparison cannot
-depend on that order, which the tests require to be everywhere for their seeds."""
+Bar: R is compared element by element with the operator's definition evaluated in double
+(Section III-C) within the derived binary32 round-off tolerance - that is the parity claim; the
+table's row sums and the batch kernel's CSum are bit-exact; RSum agrees to double rounding (the
+kernels add the same doubles in a tree, the oracle in sequence); the flags are equal wherever the
+oracle says the comparison cannot depend on that order, which the tests require to be everywhere
+for their seeds.  On top of that R is checked bit for bit against a binary32 evaluation in the
+kernels' documented order: a reproducibility check, not the oracle."""
 import numpy as np
 import pytest
 import torch
@@ -63,13 +65,23 @@ def same_bits(x, y):
 
 
 def compare(out, ref, T, scale, bias, indices, offsets, weights, bits=8, csum_in_index_order=False):
-    """R bit for bit (both sides pool in index order in binary32).  CSum: its terms are exact to one
-    rounding on both sides; the batch kernel adds them in index order like the oracle (bit for bit), the
-    group kernel adds them lanes in parallel, which moves the sum by at most m * 2^-53 * sum|term|
-    (|term| <= d * (|scale| * code_max + |bias|): the magnitude roundoff_tolerance() is built on).
-    RSum: a binary64 sum of d binary32 values in the kernel's own order."""
-    assert same_bits(out["R"], ref.R), "R differs from the oracle's float evaluation"
+    """THE PARITY BAR for R: element by element against the operator's definition evaluated in double
+    (Section III-C: R = sum_i (alpha_i * eb_i + beta_i * e_d), `forward(..., "f64")`), within the
+    round-off bound of a binary32 evaluation of that sum that roundoff_tolerance() derives.
+    Row sums, flags: equal to the oracle's.  CSum: its terms are exact to one rounding on both sides; the
+    batch kernel adds them in index order like the oracle (bit for bit), the group kernel adds them lanes
+    in parallel, which moves the sum by at most m * 2^-53 * sum|term| (|term| <= d * (|scale| * code_max +
+    |bias|): the magnitude roundoff_tolerance() is built on).  RSum: a binary64 sum of d binary32 values in
+    the kernel's own order.
+    After the parity checks, one REPRODUCIBILITY check that is not the oracle: R bit for bit against the
+    binary32 evaluation in the one order the kernels document (one fused multiply-add per pooled row in
+    index order, biases summed apart) - it pins that order from run to run and between the two kernels."""
     tol = eb.roundoff_tolerance(T, scale, bias, indices, offsets, weights, bits)
+    R64 = eb.forward(T, scale, bias, indices, offsets, weights, "f64", bits)
+    ok = np.isfinite(R64)
+    assert np.array_equal(np.isfinite(out["R"]), ok)
+    assert np.all(np.abs(out["R"].astype(np.float64) - R64)[ok] <= (tol[:, None] + np.zeros_like(R64))[ok] + 1e-30), \
+        "R differs from the definition (double) by more than the binary32 round-off bound"
     if csum_in_index_order:
         assert np.array_equal(out["csum"].view(np.uint64), ref.csum.view(np.uint64)), "CSum differs"
     else:
@@ -81,9 +93,8 @@ def compare(out, ref, T, scale, bias, indices, offsets, weights, bits=8, csum_in
     assert np.allclose(out["rsum"][fin], ref.rsum[fin], rtol=1e-13, atol=0)
     assert ref.robust.all(), "seed gives a comparison that depends on summation order; pick another"
     assert np.array_equal(out["flags"], ref.flags)
-    R64 = eb.forward(T, scale, bias, indices, offsets, weights, "f64", bits)
-    ok = np.isfinite(R64)
-    assert np.all(np.abs(out["R"].astype(np.float64) - R64)[ok] <= (tol[:, None] + np.zeros_like(R64))[ok] + 1e-30)
+    # reproducibility of the documented evaluation order (not the parity bar)
+    assert same_bits(out["R"], ref.R), "R is not reproducible against the binary32 evaluation in the documented order"
 
 
 @pytest.mark.parametrize("d", [16, 32, 64, 128, 256, 512])
