@@ -83,6 +83,10 @@ int abft_packed_b_dims(const abft_packed_b* Bp, int* K, int* N);
 /* Copy S_B = B e (int32 [K]; Section IV, definition of the encoded column). */
 int abft_packed_b_get_checksum(const abft_packed_b* Bp, int32_t* S_B, void* stream);
 
+/* rowSum[k] = (B e)[k] mod 127 in [0,126] as int32 [K]: the 8-bit checksum column
+ * of Algorithm 1 as printed, for parity checks of ABFT_MOD127. */
+int abft_packed_b_get_checksum_mod127(const abft_packed_b* Bp, int32_t* rowSum, void* stream);
+
 /* Copy e^T B (int32 [N]; rank-1 term of Eq. 1). */
 int abft_packed_b_get_col_offsets(const abft_packed_b* Bp, int32_t* colsum, void* stream);
 
@@ -95,6 +99,12 @@ int abft_packed_b_get_col_offsets(const abft_packed_b* Bp, int32_t* colsum, void
  * the same arguments restores the weight. */
 int abft_packed_b_flip_bit(abft_packed_b* Bp, int k, int j, int bit, void* stream);
 int abft_packed_b_flip_checksum_bit(abft_packed_b* Bp, int k, int bit, void* stream);
+/* The same hook for the 8-bit column that ABFT_MOD127 reads (Section IV-A-2):
+ * inverts bit `bit` (0..7) of the stored int8 rowSum[k].  flip_checksum_bit above
+ * touches only the int32 column of the default check, this one only the 8-bit
+ * column; abft_packed_b_get_checksum_mod127 returns the entry as it now stands
+ * (sign-extended when bit 7 was inverted). */
+int abft_packed_b_flip_checksum_bit_mod127(abft_packed_b* Bp, int k, int bit, void* stream);
 
 /* Host call.  Frees the handle; the caller has synchronised every stream that
  * used it. */
@@ -198,10 +208,6 @@ int abft_recompute_flagged_rows(const uint8_t* A, int64_t lda, int M, const abft
  * the known-size reference that a profiler's HBM traffic counters are scaled
  * by when the GEMM kernels' traffic is reported. */
 int abft_calib_copy(const void* src, void* dst, size_t bytes, void* stream);
-
-/* rowSum[k] = (B e)[k] mod 127 in [0,126] as int32 [K]: the 8-bit checksum column
- * of Algorithm 1 as printed, for parity checks of ABFT_MOD127. */
-int abft_packed_b_get_checksum_mod127(const abft_packed_b* Bp, int32_t* rowSum, void* stream);
 
 /* Message for the last non-OK return on this host thread. */
 const char* abft_last_error(void);

@@ -223,12 +223,16 @@ def b_checksum_mod127(B: np.ndarray) -> np.ndarray:
     return out
 
 
-def checked_gemm_mod127(A, B, flips_b=(), flips_c=()):
-    """Algorithm 1 with its printed modulus -> (C, flags, errCount)."""
+def checked_gemm_mod127(A, B, flips_b=(), flips_c=(), flips_rowsum=()):
+    """Algorithm 1 with its printed modulus -> (C, flags, errCount).  flips_rowsum: (k, bit 0..7) inverts
+    one bit of the stored 8-bit entry rowSum[k] after it was computed (the paper assumes that column
+    error-free, Section IV-C; this is the fault it excludes)."""
     A = _c(A, np.uint8)
     B = np.array(_c(B, np.int8), copy=True)
     M, K = A.shape
     rs = b_checksum_mod127(B)
+    for (k, bit) in flips_rowsum:
+        rs.view(np.uint8)[k] ^= np.uint8(1 << bit)
     for (k, j, bit) in flips_b:
         B.view(np.uint8)[k, j] ^= np.uint8(1 << bit)
     C = gemm_u8s8s32(A, B)

@@ -22,7 +22,8 @@ ABFT_VARIANT_TILE256, ABFT_VARIANT_TILE128, ABFT_VARIANT_TILE64, ABFT_VARIANT_SM
 EXPORTS = (
     "abft_pack_b_checksum", "abft_packed_b_dims", "abft_packed_b_get_checksum", "abft_packed_b_get_checksum_mod127",
     "abft_packed_b_get_col_offsets",
-    "abft_packed_b_flip_bit", "abft_packed_b_flip_checksum_bit", "abft_packed_b_destroy",
+    "abft_packed_b_flip_bit", "abft_packed_b_flip_checksum_bit", "abft_packed_b_flip_checksum_bit_mod127",
+    "abft_packed_b_destroy",
     "abft_gemm_workspace_bytes", "abft_workspace_init", "abft_gemm_u8s8s32_checked", "abft_requantize_u8",
     "abft_verify_rows", "abft_row_checksum", "abft_recover_scratch_bytes", "abft_recompute_flagged_rows",
     "abft_calib_copy", "abft_last_error",
@@ -65,6 +66,7 @@ def _load() -> ctypes.CDLL:
     L.abft_packed_b_get_col_offsets.argtypes = [vp, vp, vp]
     L.abft_packed_b_flip_bit.argtypes = [vp, i32, i32, i32, vp]
     L.abft_packed_b_flip_checksum_bit.argtypes = [vp, i32, i32, vp]
+    L.abft_packed_b_flip_checksum_bit_mod127.argtypes = [vp, i32, i32, vp]
     L.abft_packed_b_destroy.argtypes = [vp]
     L.abft_packed_b_destroy.restype = None
     L.abft_gemm_workspace_bytes.argtypes = [i32, vp]
@@ -175,6 +177,10 @@ def abft_packed_b_flip_bit(Bp: PackedB, k: int, j: int, bit: int, stream=None):
 
 def abft_packed_b_flip_checksum_bit(Bp: PackedB, k: int, bit: int, stream=None):
     _check(lib.abft_packed_b_flip_checksum_bit(Bp.handle, int(k), int(bit), _stream(stream)))
+
+
+def abft_packed_b_flip_checksum_bit_mod127(Bp: PackedB, k: int, bit: int, stream=None):
+    _check(lib.abft_packed_b_flip_checksum_bit_mod127(Bp.handle, int(k), int(bit), _stream(stream)))
 
 
 def abft_gemm_workspace_bytes(M: int, Bp: PackedB) -> int:

@@ -155,6 +155,7 @@ enum Variant { kTile256 = 1, kTile128 = 2, kTile64 = 3, kSmallM = 4, kTile256w24
 hipError_t launch_pack(const int8_t* B, int64_t ldb, int transposed, abft_packed_b* h, hipStream_t s);
 hipError_t launch_flip_bit(abft_packed_b* h, int k, int j, int bit, hipStream_t s);
 hipError_t launch_flip_checksum_bit(abft_packed_b* h, int k, int bit, hipStream_t s);
+hipError_t launch_flip_checksum127_bit(abft_packed_b* h, int k, int bit, hipStream_t s);
 hipError_t launch_fill_zero(int32_t* p, size_t n_ints, hipStream_t s);
 hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s);
 hipError_t launch_gemm_smallm(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s);

@@ -140,6 +140,14 @@ int abft_packed_b_flip_checksum_bit(abft_packed_b* Bp, int k, int bit, void* str
     return ABFT_OK;
 }
 
+int abft_packed_b_flip_checksum_bit_mod127(abft_packed_b* Bp, int k, int bit, void* stream) {
+    if (!Bp) return fail(ABFT_EINVAL, "abft_packed_b_flip_checksum_bit_mod127: null handle");
+    if (k < 0 || k >= Bp->K || bit < 0 || bit > 7)
+        return fail(ABFT_EINVAL, "abft_packed_b_flip_checksum_bit_mod127: (k=%d, bit=%d) outside [0,%d) x [0,8)", k, bit, Bp->K);
+    HIP_TRY(abft::launch_flip_checksum127_bit(Bp, k, bit, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
 void abft_packed_b_destroy(abft_packed_b* Bp) { free_handle(Bp); }
 
 size_t abft_gemm_workspace_bytes(int M, const abft_packed_b* Bp) {

@@ -760,7 +760,11 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
                 const int32_t val = raw + cs_hit, bad = (int32_t)((uint32_t)val ^ mask);
                 if (kWantC) p.C[(int64_t)row * p.ldc + col] = bad;
                 if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_one(bad, zcs_hit, col, p.rq);
-                if (kCheck) atomicAdd(&s_rs[wn * BM + wm * WTM + r], mod127 ? floor_mod127((long long)bad - val) : bad - val);
+                // (the row sum was formed from the clean value; it is moved by the difference, taken in
+                // wrap-around arithmetic: a flip of bit 31 changes the value by 2^31)
+                if (kCheck)
+                    atomicAdd(&s_rs[wn * BM + wm * WTM + r],
+                              mod127 ? floor_mod127((long long)bad - val) : (int32_t)((uint32_t)bad - (uint32_t)val));
             }
         }
     }

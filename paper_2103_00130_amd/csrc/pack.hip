@@ -117,6 +117,15 @@ __global__ void flip_checksum_bit_kernel(int32_t* S_B, int8_t* limbs, int32_t* t
     *total = (int32_t)((uint32_t)*total + (now - old));
 }
 
+// the same for the 8-bit column of Algorithm 1 as printed: rowSum[k] is one int8 in memory
+__global__ void flip_checksum127_bit_kernel(int32_t* S_B127, int8_t* limbs127, int32_t* total127, int k, int bit) {
+    const int32_t old = S_B127[k];
+    const int32_t now = (int32_t)(int8_t)((uint8_t)old ^ (uint8_t)(1u << bit));
+    S_B127[k] = now;
+    write_digits(limbs127, k, now);
+    *total127 = (int32_t)((uint32_t)*total127 + ((uint32_t)now - (uint32_t)old));
+}
+
 __global__ void fill_zero_kernel(int32_t* p, size_t n) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0;
@@ -146,6 +155,11 @@ hipError_t launch_flip_bit(abft_packed_b* h, int k, int j, int bit, hipStream_t 
 
 hipError_t launch_flip_checksum_bit(abft_packed_b* h, int k, int bit, hipStream_t s) {
     flip_checksum_bit_kernel<<<dim3(1), dim3(1), 0, s>>>(h->S_B, h->limbs, h->total, k, bit);
+    return hipGetLastError();
+}
+
+hipError_t launch_flip_checksum127_bit(abft_packed_b* h, int k, int bit, hipStream_t s) {
+    flip_checksum127_bit_kernel<<<dim3(1), dim3(1), 0, s>>>(h->S_B127, h->limbs127, h->total + 1, k, bit);
     return hipGetLastError();
 }
 

@@ -14,14 +14,15 @@ namespace {
 __global__ void requantize_kernel(const int32_t* __restrict__ C, int64_t ldc, int M, int N,
                                   const int32_t* __restrict__ colsum, RequantDev rq, uint8_t* __restrict__ Cq,
                                   int64_t ldcq) {
-    const int row = blockIdx.y;
     const int j0 = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
-    if (row >= M || j0 >= N) return;
+    if (j0 >= N) return;
     const int n = min(4, N - j0);
-    for (int e = 0; e < n; ++e) {
-        const int col = j0 + e;
-        Cq[(int64_t)row * ldcq + col] = requant_one(C[(int64_t)row * ldc + col], colsum[col], col, rq);
-    }
+    // rows in strides of the grid's second dimension (which the hardware caps at 65535)
+    for (int row = blockIdx.y; row < M; row += gridDim.y)
+        for (int e = 0; e < n; ++e) {
+            const int col = j0 + e;
+            Cq[(int64_t)row * ldcq + col] = requant_one(C[(int64_t)row * ldc + col], colsum[col], col, rq);
+        }
 }
 
 // one workgroup (256 lanes) per row: tSum, comparison with row_chk, flag, count.
@@ -125,7 +126,7 @@ hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream
 
 hipError_t launch_requantize(const int32_t* C, int64_t ldc, int M, int N, const int32_t* colsum,
                              const RequantDev& rq, uint8_t* Cq, int64_t ldcq, hipStream_t s) {
-    const dim3 block(64), grid((unsigned)((N + 255) / 256), (unsigned)M);
+    const dim3 block(64), grid((unsigned)((N + 255) / 256), (unsigned)std::min(M, 65535));
     requantize_kernel<<<grid, block, 0, s>>>(C, ldc, M, N, colsum, rq, Cq, ldcq);
     return hipGetLastError();
 }

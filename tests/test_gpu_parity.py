@@ -658,3 +658,111 @@ def test_output_beyond_4_gib(binding, gpu_util, oracle):
     assert np.array_equal(f[rows], ref.flags) and not ws.tensor.any().item()
     del C
     Bp.destroy()
+
+
+# ---- further cases ---------------------------------------------------------------------------
+
+@pytest.mark.gpu
+def test_standalone_requantize_beyond_65535_rows(binding, gpu_util, oracle):
+    """More rows than the second grid dimension holds: the stand-alone requantization must equal the
+    fused epilogue and the oracle on every row."""
+    import torch
+    M, N, K = 70000, 64, 64
+    say(f"stand-alone requantization, {M} rows")
+    A, B = operands(M, N, K, 404, full_range_b=False)
+    mult = wlmod.draw_mult(np.random.default_rng(9), N, "channel")
+    run = gpu_util.GpuRun(binding, B)
+    out = run.gemm(A, requant=(128, 128, mult, None))
+    ref = oracle.checked_gemm(A, B)
+    q32 = oracle.requantize(ref.C, ref.colsum, 128, 128, mult, precision="f32")
+    assert np.array_equal(out["C"], ref.C) and np.array_equal(out["Cq"], q32)
+    mult_d = gpu_util.dev(mult)
+    rq = binding.make_requant(128, 128, mult_d)
+    Cq = torch.zeros((M, N), dtype=torch.uint8, device="cuda")
+    binding.abft_requantize_u8(gpu_util.dev(ref.C), run.Bp, rq, Cq)
+    assert np.array_equal(Cq.cpu().numpy(), q32)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("variant", ["auto", "tile64", "tile128", "tile256"])
+def test_accumulator_entries_wrap_on_the_matrix_cores(binding, gpu_util, oracle, variant):
+    """Constant operands that drive the matrix cores' 32-bit accumulators past 2^31: with a = 0 the
+    shifted operand is -128 and b = -128 gives 16384 per k, 2.29e9 after K = 140032 (the true entry is 0);
+    with a = 255, b = 127 both the accumulator (127 * 127 * K) and the true entry (255 * 127 * K) wrap.
+    Equality with the oracle shows that the accumulation is modulo 2^32 and does not saturate."""
+    M, N, K = 20, 24, 140032
+    say(f"accumulator wrap: {M}x{N}x{K} variant={variant}")
+    A = np.zeros((M, K), np.uint8)
+    B = np.full((K, N), -128, np.int8)
+    A[5:10] = 255
+    B[:, 8:16] = 127
+    A[10:15, ::2] = 1           # mixed rows: small entries next to wrapped ones
+    A[15:] = 128                # shifted operand 0: accumulator stays 0, the add-back alone carries the entry
+    ref = oracle.checked_gemm(A, B)
+    assert ref.err_count == 0
+    assert int(ref.C[5, 8]) != 255 * 127 * K and (255 * 127 * K - int(ref.C[5, 8])) % (1 << 32) == 0   # wrapped indeed
+    run = gpu_util.GpuRun(binding, B)
+    assert np.array_equal(run.checksum(), ref.S_B)
+    out = run.gemm(A, variant=variant)
+    assert np.array_equal(out["C"], ref.C)
+    assert not out["flags"].any() and out["err_count"] == 0 and not out["ws"].any()
+    inj = [(0, 0, 1 << 31), (7, 9, 1), (19, 23, 1 << 16)]
+    refi = oracle.checked_gemm(A, B, flips_c=inj)
+    out = run.gemm(A, variant=variant, injections=inj)
+    assert np.array_equal(out["C"], refi.C) and np.array_equal(out["flags"], refi.flags) and out["err_count"] == 3
+
+
+@pytest.mark.gpu
+def test_mod127_rowsum_entry_flip(binding, gpu_util, oracle):
+    """A fault in the stored 8-bit checksum entry itself (Section IV-C assumes there is none): flags follow
+    the oracle row by row, and a second call of the hook restores the column."""
+    import torch
+    M, N, K = 150, 290, 144
+    say("mod 127: checksum entry flips")
+    A, B = operands(M, N, K, 19, relu_like=True)
+    A[3, 9], A[40, 9] = 127, 254
+    run = gpu_util.GpuRun(binding, B)
+    rs0 = oracle.b_checksum_mod127(B).astype(np.int32)
+    rs = torch.empty(K, dtype=torch.int32, device="cuda")
+    hits = 0
+    for (k, bit) in [(9, 0), (9, 7), (0, 3), (143, 6), (77, 5)]:
+        Cw, fw, nw = oracle.checked_gemm_mod127(A, B, flips_rowsum=[(k, bit)])
+        binding.abft_packed_b_flip_checksum_bit_mod127(run.Bp, k, bit)
+        binding.abft_packed_b_get_checksum_mod127(run.Bp, rs)
+        want_entry = np.array([rs0[k]], np.int32).astype(np.uint8) ^ np.uint8(1 << bit)
+        assert int(rs.cpu().numpy()[k]) == int(want_entry.view(np.int8)[0])
+        out = run.gemm(A, mod127=True)
+        exact = run.gemm(A)                       # the int32 column is a different column: untouched
+        binding.abft_packed_b_flip_checksum_bit_mod127(run.Bp, k, bit)
+        assert np.array_equal(out["C"], Cw) and np.array_equal(out["flags"], fw) and out["err_count"] == nw
+        assert exact["err_count"] == 0
+        hits += nw
+    assert hits > 0
+    binding.abft_packed_b_get_checksum_mod127(run.Bp, rs)
+    assert np.array_equal(rs.cpu().numpy(), rs0)
+    assert run.gemm(A, mod127=True)["err_count"] == 0
+
+
+@pytest.mark.gpu
+def test_mod127_on_the_tall_skinny_workload(binding, gpu_util, oracle):
+    """Algorithm 1 with its printed modulus on workload 2's shape (M = 16), through whichever kernel the
+    library picks for it: clean, C faults, B faults including rows that pass modulo 127."""
+    ops = wlmod.make_operands(2)
+    A = ops.A.copy()
+    A[3, 100], A[7, 100], A[9, 100] = 127, 254, 0
+    say("mod 127: workload 2 shape")
+    run = gpu_util.GpuRun(binding, ops.B)
+    C0, f0, n0 = oracle.checked_gemm_mod127(A, ops.B)
+    out = run.gemm(A, mod127=True)
+    assert n0 == 0 and np.array_equal(out["C"], C0) and out["err_count"] == 0 and not out["flags"].any()
+    for inj in ([(15, 4095, 1 << 31)], [(0, 0, 1), (8, 2000, 1 << 13)]):
+        Cw, fw, nw = oracle.checked_gemm_mod127(A, ops.B, flips_c=inj)
+        out = run.gemm(A, mod127=True, injections=inj)
+        assert np.array_equal(out["C"], Cw) and np.array_equal(out["flags"], fw) and out["err_count"] == nw == len(inj)
+    for (k, j, bit) in [(100, 17, 0), (100, 4000, 7), (2047, 4095, 5), (0, 0, 6)]:
+        Cw, fw, nw = oracle.checked_gemm_mod127(A, ops.B, flips_b=[(k, j, bit)])
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        out = run.gemm(A, mod127=True)
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        assert np.array_equal(out["C"], Cw) and np.array_equal(out["flags"], fw) and out["err_count"] == nw
+    assert not out["ws"].any()

@@ -356,3 +356,21 @@ def test_overhead_model_identity():
         m, n, k = wl.M, wl.N, wl.K
         assert Fraction(k * n + 2 * m * k + m * n, 2 * m * n * k) == \
             Fraction(1, 2 * m) + Fraction(1, n) + Fraction(1, 2 * k)
+
+
+def test_mod127_rowsum_entry_flip_closed_form(oracle):
+    """A fault in the stored 8-bit checksum entry rowSum[k] (the case Section IV-C excludes): the checksum
+    product of row p moves by A[p][k] * delta, so row p is flagged iff that is not a multiple of 127."""
+    rng = np.random.default_rng(77)
+    M, N, K = 40, 9, 12
+    A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+    A[0, 5], A[1, 5], A[2, 5] = 0, 127, 254
+    B = rng.integers(-127, 128, size=(K, N), dtype=np.int8)
+    rs = oracle.b_checksum_mod127(B).astype(np.int64)
+    for bit in range(8):
+        new = np.array([rs[5]], np.int64).astype(np.uint8) ^ np.uint8(1 << bit)
+        delta = int(new.view(np.int8)[0]) - int(rs[5])
+        _, flags, n = oracle.checked_gemm_mod127(A, B, flips_rowsum=[(5, bit)])
+        want = ((A[:, 5].astype(np.int64) * delta) % 127 != 0).astype(np.int32)
+        assert np.array_equal(flags, want) and n == int(want.sum())
+        assert flags[0] == 0 and flags[1] == 0 and flags[2] == 0
