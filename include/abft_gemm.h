@@ -166,6 +166,24 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
                               const abft_inject_t* inj, int n_inj, uint32_t flags,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* abft_gemm_u8s8s32_checked for callers that cannot allocate device memory and
+ * have no workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments without the workspace, same
+ * kernels, same results; the counting words live in a device array built into
+ * the library (one copy per GPU, ABFT_STATIC_WS_MAX_M rows at most, about 1 MiB,
+ * held until the process ends).  The call itself allocates nothing and frees
+ * nothing; it enqueues one small fill kernel that zeroes the words it is about
+ * to use, then the GEMM.  Every call on one GPU shares that GPU's array: calls
+ * that may overlap on one GPU (different streams, no ordering) race - order them
+ * or use abft_gemm_u8s8s32_checked with one workspace per stream.
+ * Errors: as abft_gemm_u8s8s32_checked; ABFT_EUNSUPPORTED when
+ * M > ABFT_STATIC_WS_MAX_M. */
+#define ABFT_STATIC_WS_MAX_M 131072
+int abft_gemm_u8s8s32_checked_static(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp,
+                                     int32_t* C, int64_t ldc, int32_t* row_flags, int32_t* err_count,
+                                     const abft_requant_t* rq, uint8_t* Cq, int64_t ldcq,
+                                     const abft_inject_t* inj, int n_inj, uint32_t flags, void* stream);
+
 /* Stand-alone requantization of a stored int32 C_temp (Section III-B), using the
  * column sums held in Bp.  Same arithmetic as the fused epilogue. */
 int abft_requantize_u8(const int32_t* C, int64_t ldc, int M, int N, const abft_packed_b* Bp,

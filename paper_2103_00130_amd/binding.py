@@ -24,7 +24,8 @@ EXPORTS = (
     "abft_packed_b_get_col_offsets",
     "abft_packed_b_flip_bit", "abft_packed_b_flip_checksum_bit", "abft_packed_b_flip_checksum_bit_mod127",
     "abft_packed_b_destroy",
-    "abft_gemm_workspace_bytes", "abft_workspace_init", "abft_gemm_u8s8s32_checked", "abft_requantize_u8",
+    "abft_gemm_workspace_bytes", "abft_workspace_init", "abft_gemm_u8s8s32_checked", "abft_gemm_u8s8s32_checked_static",
+    "abft_requantize_u8",
     "abft_verify_rows", "abft_row_checksum", "abft_recover_scratch_bytes", "abft_recompute_flagged_rows",
     "abft_calib_copy", "abft_last_error",
 )
@@ -74,6 +75,8 @@ def _load() -> ctypes.CDLL:
     L.abft_workspace_init.argtypes = [vp, sz, vp]
     L.abft_gemm_u8s8s32_checked.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64,
                                             vp, i32, u32, vp, sz, vp]
+    L.abft_gemm_u8s8s32_checked_static.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64,
+                                                   vp, i32, u32, vp]
     L.abft_requantize_u8.argtypes = [vp, i64, i32, i32, vp, ctypes.POINTER(abft_requant_t), vp, i64, vp]
     L.abft_verify_rows.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
     L.abft_row_checksum.argtypes = [vp, i64, i32, vp, vp, vp]
@@ -226,6 +229,30 @@ def abft_gemm_u8s8s32_checked(A, Bp: PackedB, C, row_flags, err_count, rq=None, 
         None if rq is None else ctypes.byref(rq), _ptr(Cq, torch.uint8, "Cq"), 0 if Cq is None else _ld(Cq, "Cq"),
         _ptr(inj, torch.int32, "inj"), int(n_inj), int(flags),
         None if workspace is None else workspace.data_ptr(), ws_bytes, _stream(stream)))
+
+
+ABFT_STATIC_WS_MAX_M = 131072
+
+
+def abft_gemm_u8s8s32_checked_static(A, Bp: PackedB, C, row_flags, err_count, rq=None, Cq=None, inj=None, n_inj=0,
+                                     flags=ABFT_CHECK, stream=None):
+    """The checked GEMM on the library's built-in workspace (no allocation, no workspace argument)."""
+    M = A.shape[0]
+    if A.shape[1] != Bp.K:
+        raise ValueError(f"A is {tuple(A.shape)}, packed B has K={Bp.K}")
+    for t, nm in ((C, "C"), (Cq, "Cq")):
+        if t is not None and tuple(t.shape) != (M, Bp.N):
+            raise ValueError(f"{nm} must be {M}x{Bp.N}")
+    if row_flags is not None and row_flags.numel() < M:
+        raise ValueError("row_flags shorter than M")
+    if inj is not None and inj.numel() < 3 * n_inj:
+        raise ValueError("injection tensor shorter than n_inj entries")
+    _check(lib.abft_gemm_u8s8s32_checked_static(
+        _ptr(A, torch.uint8, "A"), _ld(A, "A"), M, Bp.handle,
+        _ptr(C, torch.int32, "C"), 0 if C is None else _ld(C, "C"),
+        _ptr(row_flags, torch.int32, "row_flags"), _ptr(err_count, torch.int32, "err_count"),
+        None if rq is None else ctypes.byref(rq), _ptr(Cq, torch.uint8, "Cq"), 0 if Cq is None else _ld(Cq, "Cq"),
+        _ptr(inj, torch.int32, "inj"), int(n_inj), int(flags), _stream(stream)))
 
 
 def abft_requantize_u8(C, Bp: PackedB, rq: abft_requant_t, Cq, stream=None):

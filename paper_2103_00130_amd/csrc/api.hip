@@ -2,6 +2,7 @@
 // kernel launches.  No arithmetic of the method happens on the host.
 #include <cstdarg>
 #include <cstdio>
+#include <atomic>
 #include <cstring>
 #include <new>
 
@@ -263,6 +264,56 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
     if (e == hipErrorNotSupported) return fail(ABFT_EUNSUPPORTED, "%s: variant %d is not available", fn, variant);
     if (e != hipSuccess) return hip_fail(e, fn);
     return ABFT_OK;
+}
+
+// ---- the entry point for callers that cannot allocate -------------------------------------------
+// Its workspace is this file-scope device array: every GPU the library runs on holds its own copy,
+// at its own address, until the process ends.
+#define ABFT_STATIC_WS_INTS (64 + 2 * ABFT_STATIC_WS_MAX_M)
+static_assert(ABFT_STATIC_WS_MAX_M % 64 == 0 && ABFT_STATIC_WS_INTS >= 64 + 4224, "covers the streaming kernel's words too");
+static __device__ __align__(256) int32_t scratch[ABFT_STATIC_WS_INTS];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<int32_t*> g_scratch_ptr[kMaxDevices];  // device address of `scratch` per device ordinal
+
+// Device address of this device's copy of `scratch` (the array's name is only a host-side stand-in
+// for it); looked up once per device, with that device current.
+int static_scratch(int dev, int32_t** out) {
+    if (dev < 0 || dev >= kMaxDevices) return fail(ABFT_EUNSUPPORTED, "device ordinal %d above %d", dev, kMaxDevices - 1);
+    int32_t* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        HIP_TRY(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(ABFT_EHIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // (two threads may both look it up: same answer)
+    }
+    *out = ptr;
+    return ABFT_OK;
+}
+}  // namespace
+
+int abft_gemm_u8s8s32_checked_static(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp, int32_t* C,
+                                     int64_t ldc, int32_t* row_flags, int32_t* err_count, const abft_requant_t* rq,
+                                     uint8_t* Cq, int64_t ldcq, const abft_inject_t* inj, int n_inj, uint32_t flags,
+                                     void* stream) {
+    const char* fn = "abft_gemm_u8s8s32_checked_static";
+    if (M > ABFT_STATIC_WS_MAX_M)
+        return fail(ABFT_EUNSUPPORTED, "%s: M=%d above the %d rows the built-in workspace holds", fn, M, ABFT_STATIC_WS_MAX_M);
+    if (M < 1) return fail(ABFT_EINVAL, "%s: M=%d must be >= 1", fn, M);
+    if (flags & ABFT_NOCHECK)
+        return abft_gemm_u8s8s32_checked(A, lda, M, Bp, C, ldc, row_flags, err_count, rq, Cq, ldcq, inj, n_inj, flags,
+                                         nullptr, 0, stream);
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    int32_t* ws = nullptr;
+    const int rc = static_scratch(dev, &ws);
+    if (rc != ABFT_OK) return rc;
+    const size_t ints = ws_ints(M);
+    // the array keeps whatever the last call on this device left (zeros, unless that call was cut short):
+    // the words this call counts on start at zero (a fill kernel, so that the call may be captured in a graph)
+    HIP_TRY(abft::launch_fill_zero(ws, ints, (hipStream_t)stream));
+    return abft_gemm_u8s8s32_checked(A, lda, M, Bp, C, ldc, row_flags, err_count, rq, Cq, ldcq, inj, n_inj, flags, ws,
+                                     ints * sizeof(int32_t), stream);
 }
 
 int abft_requantize_u8(const int32_t* C, int64_t ldc, int M, int N, const abft_packed_b* Bp,

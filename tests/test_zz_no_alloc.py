@@ -1,0 +1,83 @@
+"""The checked GEMM for callers that cannot allocate (abft_gemm_u8s8s32_checked_static): same results as
+abft_gemm_u8s8s32_checked on a caller's workspace, to the same bar (integers bit for bit), on calls in a
+row that share the library's built-in workspace, the later ones with smaller inputs."""
+import numpy as np
+import pytest
+
+from paper_2103_00130_amd import workloads as wlmod
+
+pytestmark = pytest.mark.gpu
+
+
+def run_both(b, gpu_util, A, B, injections=(), requant=None, mod127=False):
+    import torch
+    run = gpu_util.GpuRun(b, B)
+    want = run.gemm(A, injections=injections, requant=requant, mod127=mod127)
+    M, N = A.shape[0], B.shape[1]
+    C = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+    flags = torch.full((M,), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    rq = Cq = None
+    keep = []
+    if requant is not None:
+        zA, zC, mult, _ = requant
+        mult_d = gpu_util.dev(np.atleast_1d(mult).astype(np.float32))
+        keep.append(mult_d)
+        rq = b.make_requant(zA, zC, mult_d)
+        Cq = torch.full((M, N), 7, dtype=torch.uint8, device="cuda")
+    inj = b.make_injections(list(injections)) if len(injections) else None
+    A_dev = gpu_util.dev(A)
+    torch.cuda.synchronize()
+    before = torch.cuda.memory_allocated()
+    b.abft_gemm_u8s8s32_checked_static(A_dev, run.Bp, C, flags, cnt, rq=rq, Cq=Cq,
+                                       inj=inj, n_inj=len(injections), flags=b.ABFT_MOD127 if mod127 else b.ABFT_CHECK)
+    torch.cuda.synchronize()
+    assert torch.cuda.memory_allocated() == before
+    got = {"C": C.cpu().numpy(), "flags": flags.cpu().numpy(), "err_count": int(cnt.item()),
+           "Cq": None if Cq is None else Cq.cpu().numpy()}
+    assert np.array_equal(got["C"], want["C"]), "C differs between the two entry points"
+    assert np.array_equal(got["flags"], want["flags"]) and got["err_count"] == want["err_count"]
+    if Cq is not None:
+        assert np.array_equal(got["Cq"], want["Cq"])
+    return got
+
+
+def test_static_workspace_entry_point_matches_the_workspace_one():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2103_00130_amd import binding as b
+    import gpu_util
+    from oracle import abft_oracle as oracle
+    rng = np.random.Generator(np.random.PCG64(321))
+    # a tiled shape with several tile columns and a ragged tail, faults in two rows
+    M, N, K = 700, 900, 400
+    A = wlmod.draw_a(rng, M, K, False)
+    B = wlmod.draw_b(rng, K, N)
+    inj = [(3, 5, 1 << 30), (699, 899, 1)]
+    got = run_both(b, gpu_util, A, B, injections=inj)
+    ref = oracle.checked_gemm(A, B, flips_c=inj)
+    assert np.array_equal(got["C"], ref.C) and np.array_equal(got["flags"], ref.flags) and got["err_count"] == 2
+    # right after it, smaller inputs on the same built-in workspace: a tiled shape, then the streaming kernel
+    M2, N2, K2 = 130, 200, 144
+    A2 = wlmod.draw_a(rng, M2, K2, True)
+    B2 = wlmod.draw_b(rng, K2, N2)
+    mult = wlmod.draw_mult(rng, N2, "channel")
+    got = run_both(b, gpu_util, A2, B2, requant=(0, 128, mult, None))
+    ref = oracle.checked_gemm(A2, B2)
+    assert np.array_equal(got["C"], ref.C) and got["err_count"] == 0 and not got["flags"].any()
+    assert np.array_equal(got["Cq"], oracle.requantize(ref.C, ref.colsum, 0, 128, mult, precision="f32"))
+    A3 = wlmod.draw_a(rng, 16, 512, False)
+    B3 = wlmod.draw_b(rng, 512, 1000)
+    got = run_both(b, gpu_util, A3, B3, injections=[(15, 999, 1 << 31)])
+    ref = oracle.checked_gemm(A3, B3, flips_c=[(15, 999, 1 << 31)])
+    assert np.array_equal(got["C"], ref.C) and np.array_equal(got["flags"], ref.flags) and got["err_count"] == 1
+    # the printed modulus goes through the same words
+    got = run_both(b, gpu_util, A2[:, :144], B2, mod127=True)
+    assert got["err_count"] == 0
+    # sizes beyond the built-in workspace are refused on the host, nothing is enqueued
+    big = torch.zeros((b.ABFT_STATIC_WS_MAX_M + 1, 16), dtype=torch.uint8, device="cuda")
+    Bp = b.abft_pack_b_checksum(torch.zeros((16, 16), dtype=torch.int8, device="cuda"))
+    with pytest.raises(b.AbftError) as e:
+        b.abft_gemm_u8s8s32_checked_static(big, Bp, torch.empty((big.shape[0], 16), dtype=torch.int32, device="cuda"),
+                                           torch.empty(big.shape[0], dtype=torch.int32, device="cuda"), None)
+    assert e.value.code == b.ABFT_EUNSUPPORTED and "built-in workspace" in str(e.value)
