@@ -43,8 +43,10 @@ def algorithmic_bytes(wl, want_c=True, want_q=False):
 class Job:
     """Device-resident operands and outputs of one workload."""
 
-    def __init__(self, b, torch, cfg, n_rot=1, mod127=False):
+    def __init__(self, b, torch, cfg, n_rot=1, mod127=False, accumulate=True):
         self.mod127 = mod127
+        # errCount as a counter the caller zeroes and the launches add to (Algorithm 1's errCount++), or overwritten
+        self.count_flag = b.ABFT_ERRCOUNT_ACCUMULATE if accumulate else 0
         from paper_2103_00130_amd import workloads as w
         self.b, self.torch = b, torch
         self.ops = w.make_operands(cfg)
@@ -64,7 +66,7 @@ class Job:
             self.pack_ms = (time.perf_counter() - t0) * 1e3 / (n_rot - 1)
         self.C = torch.empty((wl.M, wl.N), dtype=torch.int32, device="cuda")
         self.flags = torch.empty(wl.M, dtype=torch.int32, device="cuda")
-        self.cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+        self.cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
         self.ws = b.Workspace(wl.M, self.Bp[0])
         self.rq = self.Cq = None
         if self.ops.mult is not None:
@@ -78,7 +80,7 @@ class Job:
         Bp = self.Bp[self.i % len(self.Bp)]
         self.i += 1
         b.abft_gemm_u8s8s32_checked(self.A, Bp, self.C, self.flags, self.cnt, rq=self.rq, Cq=self.Cq, inj=inj,
-                                    n_inj=n_inj, flags=((b.ABFT_MOD127 if self.mod127 else b.ABFT_CHECK) if check else b.ABFT_NOCHECK) | variant,
+                                    n_inj=n_inj, flags=((b.ABFT_MOD127 if self.mod127 else b.ABFT_CHECK) if check else b.ABFT_NOCHECK) | variant | self.count_flag,
                                     workspace=self.ws.tensor)
 
     def time_steps(self, steps, warmup, check=True, variant=0, graph=True):
@@ -121,6 +123,7 @@ def detection_sample(job, n=200):
     detected = wrong_rows = 0
     for t in range(n):
         inj = b.make_injections([(int(r[t]), int(c[t]), 1 << int(bit[t]))])
+        job.cnt.zero_()
         job.step(True, inj=inj, n_inj=1)
         f = job.flags
         hit = int(f[int(r[t])].item())
@@ -148,6 +151,7 @@ def recovery_sample(job, rows=(1, 64)):
         inj = b.make_injections([(int(r[t]), int(c[t]), 1 << int(bit[t])) for t in sel])
         best = None
         for _ in range(5):
+            job.cnt.zero_()
             job.step(True, inj=inj, n_inj=n)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -183,6 +187,62 @@ def cpu_baseline(job, target_s=12.0):
             f"(checksum, product, row sums, comparison), {dt:.1f} s wall"}
 
 
+def smallm_sweep(b, torch, steps, warmup, count_flag=0, M=16,
+                 shapes=((4096, 2048), (4096, 4096), (8192, 8192), (16384, 16384), (16384, 32768))):
+    """The streaming kernel on weights from 8 MiB to 512 MiB (N x K int8), M = 16: how close to the HBM
+    roofline it gets once the weight is large enough to amortise the launch.  Operands are seeded draws on
+    the device (timing only; parity of these kernels is the tests' business)."""
+    out = []
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(210300130)
+    A = torch.randint(0, 256, (M, max(k for _, k in shapes)), dtype=torch.uint8, device="cuda", generator=gen)
+    for N, K in shapes:
+        n_rot = max(2, -(-(768 << 20) // (N * K)))
+        Bps = []
+        for _ in range(n_rot):
+            B = torch.randint(-127, 128, (K, N), dtype=torch.int8, device="cuda", generator=gen)
+            Bps.append(b.abft_pack_b_checksum(B))
+            del B
+        a = A[:, :K]
+        C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+        flags = torch.empty(M, dtype=torch.int32, device="cuda")
+        cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ws = b.Workspace(M, Bps[0])
+        n_steps = max(n_rot * 2, min(steps, (4 << 30) // (N * K)))
+
+        def run(check, n):
+            for i in range(n):
+                b.abft_gemm_u8s8s32_checked(a, Bps[i % n_rot], C, flags, cnt,
+                                            flags=(b.ABFT_CHECK if check else b.ABFT_NOCHECK) | count_flag, workspace=ws.tensor)
+
+        def timed(check):
+            run(check, min(warmup, n_rot * 2))
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                run(check, n_steps)
+            g.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n_steps
+        ms_c = min(timed(True), timed(True))
+        ms_u = min(timed(False), timed(False))
+        by = M * K + K * N + 4 * K + 4 * M * N + 4 * M
+        out.append({"M": M, "N": N, "K": K, "weight_MiB": N * K / 2**20, "weight_copies_rotated": n_rot, "steps": n_steps,
+                    "us_checked": ms_c * 1e3, "us_unchecked": ms_u * 1e3, "abft_overhead_pct": 100.0 * (ms_c - ms_u) / ms_u,
+                    "algorithmic_bytes": by, "gbs": by / ms_c / 1e6, "hbm_frac": by / ms_c / 1e6 / PEAK_HBM_GBS,
+                    "tops_checked": 2.0 * M * N * K / ms_c / 1e9})
+        for Bp in Bps:
+            Bp.destroy()
+        del Bps, C
+        torch.cuda.empty_cache()
+    return out
+
+
 CALIB_COPY_BYTES = 256 << 20
 GEMM_KERNEL_TAGS = ("gemm_tile_async_kernel", "gemm_tile_kernel", "gemm_smallm_kernel")
 
@@ -195,7 +255,7 @@ def pmc_child(args):
     torch.cuda.set_device(0)
     src = torch.zeros(CALIB_COPY_BYTES // 4, dtype=torch.int32, device="cuda")
     dst = torch.empty_like(src)
-    job = Job(b, torch, args.workload, mod127=args.mod127)
+    job = Job(b, torch, args.workload, mod127=args.mod127, accumulate=not args.overwrite_count)
     torch.cuda.synchronize()
     b.abft_calib_copy(src, dst)
     for _ in range(4):
@@ -222,7 +282,8 @@ def measure_traffic(args, child_args=None, tags=None):
         cmd = ["timeout", "-s", "KILL", "170", "rocprofv3", "--pmc", counter, "-d", tmp, "-o", "pmc",
                "--output-format", "csv", "--", sys.executable, os.path.join(ROOT, "bench.py")]
         cmd += child_args if child_args is not None else (
-            ["--pmc-child", "--workload", str(args.workload), "--variant", str(args.variant)] + (["--mod127"] if args.mod127 else []))
+            ["--pmc-child", "--workload", str(args.workload), "--variant", str(args.variant)] + (["--mod127"] if args.mod127 else [])
+            + (["--overwrite-count"] if args.overwrite_count else []))
         try:
             r = subprocess.run(cmd, cwd=tmp, env=env, capture_output=True, text=True)
             files = glob.glob(os.path.join(tmp, "**", "*counter_collection.csv"), recursive=True)
@@ -394,13 +455,16 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", type=int, default=4, help="index into the five workloads (default: dense 4096^3)")
-    ap.add_argument("--others", action="store_true", help="also time the other workloads (reported under 'others')")
+    ap.add_argument("--others", action="store_true", help="EmbeddingBag: every width of Table I, weighted sums, 4-bit codes")
+    ap.add_argument("--only-headline", action="store_true", help="time only --workload (no per-workload list, no small-M sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-detection", action="store_true")
     ap.add_argument("--variant", type=lambda s: int(s, 0), default=0)
     ap.add_argument("--no-traffic", action="store_true", help="skip the two rocprofv3 counter passes")
     ap.add_argument("--mod127", action="store_true", help="check with the paper's printed modulus (8-bit checksum column, "
                     "comparison modulo 127) instead of the exact int32 checksum; tiled kernels only")
+    ap.add_argument("--overwrite-count", action="store_true", help="errCount overwritten by every launch (the library's default) "
+                    "instead of a counter that the launches add to (ABFT_ERRCOUNT_ACCUMULATE, what this benchmark times by default)")
     ap.add_argument("--pmc-child", action="store_true", help=argparse.SUPPRESS)
     ap.add_argument("--pmc-child-eb", type=str, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--no-eb", action="store_true", help="skip the EmbeddingBag entries (reported under 'eb')")
@@ -437,11 +501,11 @@ def main():
 
     def measure(cfg, steps, warmup, variant=0):
         wl = w.WORKLOADS[cfg]
-        hbm_bound = wl.M <= 64 and not args.mod127
+        hbm_bound = wl.M <= 64 and wl.K * wl.N >= (4 << 20) and not args.mod127
         # HBM-bound shapes: rotate through enough packed copies of the weight to exceed the caches
         n_rot = max(1, (768 << 20) // (wl.K * wl.N)) if hbm_bound else 1
         n_rot = min(n_rot, 128)
-        job = Job(b, torch, cfg, n_rot=n_rot, mod127=args.mod127)
+        job = Job(b, torch, cfg, n_rot=n_rot, mod127=args.mod127, accumulate=not args.overwrite_count)
         ms_c, wall_c = job.time_steps(steps, warmup, True, variant)
         ms_u, _ = job.time_steps(steps, warmup, False, variant)
         ms_c2, _ = job.time_steps(steps, warmup, True, variant)
@@ -454,13 +518,21 @@ def main():
             "abft_overhead_pct": 100.0 * (ms_c - ms_u) / ms_u, "pack_ms": job.pack_ms, "weight_copies_rotated": n_rot,
             "host_wall_ms_per_step": wall_c,
         }
+        by = algorithmic_bytes(wl, True, job.rq is not None)
+        hbm = {"bound": "hbm", "achieved": by / ms_c / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+               "frac": by / ms_c / 1e6 / PEAK_HBM_GBS, "traffic": None, "algorithmic_bytes": by}
+        mfma = {"bound": "mfma", "achieved": ops_per_step / ms_c / 1e9 / 1e3, "peak": PEAK_INT8_TOPS / 1e3,
+                "unit": "POP/s", "frac": ops_per_step / ms_c / 1e9 / PEAK_INT8_TOPS, "traffic": None}
         if hbm_bound:
-            by = algorithmic_bytes(wl, True, job.rq is not None)
-            res["roofline"] = {"bound": "hbm", "achieved": by / ms_c / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                               "frac": by / ms_c / 1e6 / PEAK_HBM_GBS, "traffic": None}
+            res["roofline"] = hbm
+        elif ops_per_step < 1e9:
+            # ideal times of these shapes (0.03-0.16 us on either roofline) are below the latency of a launch:
+            # reported as latency-bound, with both fractions for the record
+            res["roofline"] = {"bound": "latency", "achieved": ms_c * 1e3, "unit": "us per launch", "peak": None, "frac": None,
+                               "traffic": None, "mfma_frac": mfma["frac"], "hbm_frac": hbm["frac"],
+                               "note": "launch/latency-bound: neither roofline applies at this size"}
         else:
-            res["roofline"] = {"bound": "mfma", "achieved": ops_per_step / ms_c / 1e9 / 1e3, "peak": PEAK_INT8_TOPS / 1e3,
-                               "unit": "POP/s", "frac": ops_per_step / ms_c / 1e9 / PEAK_INT8_TOPS, "traffic": None}
+            res["roofline"] = mfma
         return job, res
 
     job, main_res = measure(args.workload, args.steps, args.warmup, args.variant)
@@ -472,7 +544,9 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": wl.name, "M": wl.M, "N": wl.N, "K": wl.K, "requant": wl.requant,
                    "baseline_config_index": wl.index,
-                   "check": "int8 checksum column, comparison modulo 127" if args.mod127 else "exact int32 checksum, comparison modulo 2^32"},
+                   "check": "int8 checksum column, comparison modulo 127" if args.mod127 else "exact int32 checksum, comparison modulo 2^32",
+                   "err_count": "overwritten per launch" if args.overwrite_count else
+                   "a counter zeroed by the caller that launches add to (ABFT_ERRCOUNT_ACCUMULATE)"},
         "abft_overhead_pct": main_res["abft_overhead_pct"], "tops_unchecked": main_res["tops_unchecked"],
         "pack_ms": main_res["pack_ms"], "roofline": main_res["roofline"],
         "launch": "the timed steps are captured in one HIP graph and replayed (events bracket the replay)",
@@ -494,13 +568,21 @@ def main():
         out["recovery_note"] = "host wall time of abft_recompute_flagged_rows (gather, re-checked GEMM, scatter; synchronises)"
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(job)
-    if args.others:
-        out["others"] = []
+    if not args.only_headline:
+        # every workload of the baseline's list, same timing method (the headline's entry repeats the figures above)
+        out["configs"] = []
         for cfg in range(len(w.WORKLOADS)):
             if cfg == args.workload:
-                continue
-            _, r = measure(cfg, args.steps, args.warmup)
-            out["others"].append(r)
+                r = dict(main_res)
+                r["roofline"] = {k: v for k, v in out["roofline"].items() if not k.startswith("traffic_note")}
+            else:
+                _, r = measure(cfg, args.steps, args.warmup)
+            r["baseline_config_index"] = cfg
+            out["configs"].append(r)
+        torch.cuda.empty_cache()
+        out["smallm_sweep"] = smallm_sweep(b, torch, args.steps, args.warmup, 0 if args.overwrite_count else b.ABFT_ERRCOUNT_ACCUMULATE)
+        out["smallm_sweep_note"] = ("streaming kernel, M = 16, weights of growing size rotated through >= 768 MiB of packed "
+                                    "copies (nothing served from cache): algorithmic bytes / time against 8 TB/s")
     if not args.no_eb:
         # second operator (Algorithm 2): Table I at d = 64 and the same table under a large batch; with
         # --others every width of Table I, regular and weighted sum

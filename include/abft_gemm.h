@@ -53,6 +53,14 @@ extern "C" {
                                      IV-A-2), and a row is flagged when its sum and its
                                      checksum entry differ modulo 127.  Tiled kernels,
                                      16-byte aligned A, K <= 65536. */
+#define ABFT_ERRCOUNT_ACCUMULATE 4u /* errCount as Algorithm 1 writes it, a counter that is
+                                     incremented: the number of flagged rows is ADDED to
+                                     *err_count (which the caller set, normally to zero, and
+                                     may leave to run over several calls) instead of
+                                     overwriting it.  A launch that flags nothing does not
+                                     touch the counter, and no workgroup has to learn that
+                                     it is the last one, which takes one dependent memory
+                                     round trip off the end of every launch. */
 #define ABFT_VARIANT_MASK 0xF00u  /* 0 = choose by shape */
 #define ABFT_VARIANT_TILE256 0x100u
 #define ABFT_VARIANT_TILE128 0x200u
@@ -151,10 +159,12 @@ int abft_workspace_init(void* workspace, size_t bytes, void* stream);
  *   C          int32 M x N, ldc >= N; may be NULL when rq != NULL (then only
  *              the uint8 output is written).
  *   row_flags  int32 [M], overwritten with 0/1 per row (ignored with ABFT_NOCHECK).
- *   err_count  int32 [1], overwritten with the number of flagged rows; may be NULL.
+ *   err_count  int32 [1], overwritten with the number of flagged rows (added to
+ *              with ABFT_ERRCOUNT_ACCUMULATE); may be NULL.
  *   rq, Cq     host struct or NULL; uint8 M x N output with ldcq >= N.
  *   inj        device array of n_inj simulated faults, or NULL / 0.
- *   flags      ABFT_CHECK or ABFT_NOCHECK, optionally | ABFT_VARIANT_*.
+ *   flags      ABFT_CHECK or ABFT_NOCHECK, optionally | ABFT_MOD127,
+ *              | ABFT_ERRCOUNT_ACCUMULATE, | ABFT_VARIANT_*.
  *   workspace  abft_gemm_workspace_bytes(M, Bp) bytes, zeroed once; may be
  *              NULL with ABFT_NOCHECK.
  * Errors: ABFT_EINVAL for null/shape/ld/workspace problems (inj is device

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libabftgemm.so")
 
 ABFT_OK, ABFT_EINVAL, ABFT_EUNSUPPORTED, ABFT_EHIP = 0, -1, -2, -3
-ABFT_CHECK, ABFT_NOCHECK, ABFT_MOD127 = 0, 1, 2
+ABFT_CHECK, ABFT_NOCHECK, ABFT_MOD127, ABFT_ERRCOUNT_ACCUMULATE = 0, 1, 2, 4
 ABFT_VARIANT_TILE256, ABFT_VARIANT_TILE128, ABFT_VARIANT_TILE64, ABFT_VARIANT_SMALLM = 0x100, 0x200, 0x300, 0x400
 
 EXPORTS = (

@@ -87,6 +87,7 @@ struct GemmParams {
     int KB2;                   // stages of 128 k-values = KB / 2
     int a_vec_ok;              // A and lda are multiples of 16 bytes
     int mod127;                // compare modulo 127 (Algorithm 1 as printed) instead of 2^32
+    int err_accumulate;        // flagged rows are added to *err_count instead of overwriting it
     const int8_t* packed;
     const int8_t* limbs;
     const int32_t* colsum;

@@ -223,6 +223,7 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
     p.inj = inj;
     p.n_inj = n_inj;
     p.ws = (int32_t*)workspace;
+    p.err_accumulate = (flags & ABFT_ERRCOUNT_ACCUMULATE) != 0;
     const bool mod127 = check && (flags & ABFT_MOD127) != 0;
     if (mod127) {
         // exact (unwrapped) 32-bit entries are what the congruence modulo 127 needs

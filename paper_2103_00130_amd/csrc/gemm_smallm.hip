@@ -62,6 +62,9 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
     // this column block's share of the checksum product's K range
     const int lo = (int)(((int64_t)cb * KB) / n_blocks), hi = (int)(((int64_t)(cb + 1) * KB) / n_blocks);
 
+    // sum_k S_B[k] for the first column block's share of the check, fetched ahead of its use at the very end
+    const int32_t total_sb = (kCheck && cb == 0) ? *p.total : 0;
+
     v4i acc[RB], cacc[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) acc[rb] = cacc[rb] = v4i{0, 0, 0, 0};
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
             }
         if (kCheck) {
             const int slot = cb & (kSmallMSlots - 1);
-            const uint32_t total128 = cb == 0 ? 128u * (uint32_t)(*p.total) : 0u;  // sum_k 128*S_B[k], once per row
+            const uint32_t total128 = 128u * (uint32_t)total_sb;  // sum_k 128*S_B[k], once per row (first column block)
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -224,7 +227,12 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
                     }
                     n_row = (uint32_t)kSmallMSlots;
                 }
-                if (go) {
+                if (n_blocks == 1) {
+                    // a single column block holds the whole row: nothing crosses workgroups
+                    bad = t != 0u;
+                    p.row_flags[lane] = (int32_t)bad;
+                    fin = true;
+                } else if (go) {
                     const unsigned long long old = __hip_atomic_fetch_add(w_row, ((unsigned long long)t << 32) | 1ull,
                                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if ((uint32_t)old == n_row - 1u) {
@@ -235,14 +243,20 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
                     }
                 }
             }
+            // errCount: not asked for / added to by the wavefronts that found corrupted rows (no return value,
+            // nobody waits) / overwritten by the report that brings the count of finished rows to M
             const unsigned long long fin_mask = __ballot(fin), bad_mask = __ballot(fin && bad);
-            if (fin_mask != 0ull && lane == __builtin_ctzll(fin_mask)) {
+            if (p.err_count == nullptr) {
+            } else if (p.err_accumulate) {
+                if (bad_mask != 0ull && lane == __builtin_ctzll(bad_mask))
+                    __hip_atomic_fetch_add(p.err_count, (int32_t)__builtin_popcountll(bad_mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else if (fin_mask != 0ull && lane == __builtin_ctzll(fin_mask)) {
                 unsigned long long* const w_done = reinterpret_cast<unsigned long long*>(p.ws + kWsDoneWord);
                 const uint32_t n_fin = (uint32_t)__builtin_popcountll(fin_mask), n_bad = (uint32_t)__builtin_popcountll(bad_mask);
                 const unsigned long long old = __hip_atomic_fetch_add(w_done, ((unsigned long long)n_bad << 32) | n_fin,
                                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if ((uint32_t)old + n_fin == (uint32_t)p.M) {
-                    if (p.err_count) *p.err_count = (int32_t)((uint32_t)(old >> 32) + n_bad);
+                    *p.err_count = (int32_t)((uint32_t)(old >> 32) + n_bad);
                     __hip_atomic_store(w_done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }

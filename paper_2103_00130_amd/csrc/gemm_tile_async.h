@@ -274,11 +274,20 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
     const int ck_lo = kCheck ? min(max((int)(((int64_t)tile_n * NS_all) / tiles_n) - s_base, 0), NS) : 0;
     const int ck_hi = kCheck ? min(max((int)(((int64_t)(tile_n + 1) * NS_all) / tiles_n) - s_base, 0), NS) : 0;
     uint8_t* const s_limb = smem + S * (A_STAGE + B_STAGE) + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t);
+    // sum_k S_B[k], which the first tile column needs at the very end (the u8 -> s8 shift of A moves every
+    // checksum product by 128 times it): fetched now, so that the epilogue does not wait for memory
+    int32_t total_sb = (kCheck && tile_n == 0) ? *p.total : 0;
     int limb_base = ck_lo;  // stage whose digits sit at the start of s_limb
+    // (copied by the same direct global->LDS loads as the stages, 1 KiB per instruction: no trip through
+    // registers, and no wait that the compiler would place - it does not see the direct loads and would
+    // wait for every one of them.  A lot that ends in half an instruction re-reads its last chunk into
+    // LDS words behind the lot, which nobody reads.)
+    const uint32_t lds_limb = lds_base + (uint32_t)(S * (A_STAGE + B_STAGE) + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t));
     auto stage_limbs = [&](int s0) __attribute__((always_inline)) {
         const int n = min(ck_hi - s0, kLimbStages);
-        for (int i = tid; i < n * 32; i += NT)
-            reinterpret_cast<v4i*>(s_limb)[i] = reinterpret_cast<const v4i*>(p.limbs + (int64_t)(s_base + s0) * 512)[i];
+        const int8_t* const src = p.limbs + (int64_t)(s_base + s0) * 512;
+        for (int i = wave; i * 2 < n; i += NW)
+            dma(lds_limb + i * 1024, (uint32_t)min(i * 1024 + lane * 16, n * 512 - 16), src, std::integral_constant<int, 0>{});
         limb_base = s0;
     };
     auto load_limbs = [&](int s) __attribute__((always_inline)) {
@@ -410,12 +419,14 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
     // k-steps read the first two fragment sets of stage s+1 while the loads of stage s+S go out, one
     // half per k-step, to the slot just released.
     using frag_reads_c = std::integral_constant<int, TM + TN>;  // LDS reads of one k-step
+    // (the digits of this tile column's share go out first: whatever wait publishes the first stage then
+    // covers them as well, and their round trip to memory runs beside that of the stages)
     if constexpr (kAhead2) {
+        if (kCheck && ck_hi > ck_lo) stage_limbs(ck_lo);
 #pragma unroll
         for (int st = 0; st < S; ++st)
 #pragma unroll
             for (int n = 0; n < N_LD; ++n) issue_load(min(st, NS - 1), st, n);
-        if (kCheck && ck_hi > ck_lo) stage_limbs(ck_lo);
         wait_vmem_but(std::integral_constant<int, (S - 1) * N_LD>{});
         __syncthreads();
         read_frags(0, 0, 0);
@@ -423,13 +434,11 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
         wait_lds();
         __builtin_amdgcn_sched_barrier(0);
     } else {
+        if (kCheck && ck_hi > ck_lo) stage_limbs(ck_lo);
 #pragma unroll
         for (int st = 0; st < S - 1; ++st)
 #pragma unroll
             for (int n = 0; n < N_LD; ++n) issue_load(min(st, NS - 1), st, n);
-        // the digits of this tile column's share go to LDS behind the first stages, so that their
-        // round trip to memory overlaps with that of the stages instead of preceding it
-        if (kCheck && ck_hi > ck_lo) stage_limbs(ck_lo);
         wait_vmem_but(pending_c{});
         __syncthreads();
         // first share of the stage after those
@@ -440,6 +449,7 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
         __builtin_amdgcn_sched_barrier(0);
     }
 
+    asm volatile("" : "+s"(total_sb));  // (the value is in its register from here on)
     int cur = 0;
     // A run of stages [s_begin, s_end) with or without the checksum-digit MFMAs (separate loops
     // keep every loop body one straight block).  PH says on which k-steps this wave adds the B
@@ -548,6 +558,7 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
                     // every wave has left the stages that read the previous lot (their digits were in
                     // registers before the barrier that ended the last of them)
                     stage_limbs(c0);
+                    wait_vmem();
                     __syncthreads();
                 }
                 run(c0, min(c0 + kLimbStages, ck_hi), std::true_type{}, ph_c);
@@ -802,20 +813,27 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
                 // residues: sums of at most 32 lanes x WGN waves of values below 127, minus the exact
                 // checksum share, as a residue again so that the workspace word cannot wrap
                 long long dd = (long long)d - (long long)s_ck[r];
-                if (tile_n == 0) dd -= 128ll * (long long)(*p.total);
+                if (tile_n == 0) dd -= 128ll * (long long)total_sb;
                 d = (uint32_t)floor_mod127(dd);
             } else {
                 d -= (uint32_t)s_ck[r];
-                if (tile_n == 0) d -= 128u * (uint32_t)(*p.total);  // sum_k 128*S_B[k], once per row
+                if (tile_n == 0) d -= 128u * (uint32_t)total_sb;  // sum_k 128*S_B[k], once per row
             }
-            const unsigned long long old = __hip_atomic_fetch_add(ws_rows + row0 + r, ((unsigned long long)d << 32) | 1ull,
-                                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((uint32_t)old == (uint32_t)tiles_n - 1u) {
-                const uint32_t diff = (uint32_t)(old >> 32) + d;
-                bad = mod127 ? (diff % 127u != 0) : (diff != 0);
-                __hip_atomic_store(ws_rows + row0 + r, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (tiles_n == 1) {
+                // one tile column holds the whole row: the comparison ends here, nothing crosses workgroups
+                bad = mod127 ? (d % 127u != 0) : (d != 0);
                 p.row_flags[row0 + r] = bad ? 1 : 0;
                 fin = true;
+            } else {
+                const unsigned long long old = __hip_atomic_fetch_add(ws_rows + row0 + r, ((unsigned long long)d << 32) | 1ull,
+                                                                      __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((uint32_t)old == (uint32_t)tiles_n - 1u) {
+                    const uint32_t diff = (uint32_t)(old >> 32) + d;
+                    bad = mod127 ? (diff % 127u != 0) : (diff != 0);
+                    __hip_atomic_store(ws_rows + row0 + r, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    p.row_flags[row0 + r] = bad ? 1 : 0;
+                    fin = true;
+                }
             }
         }
         // errCount: every row is completed by exactly one thread of the grid.  A wavefront that completed
@@ -823,14 +841,21 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
         // half, corrupted ones in the high half); the report that brings the count to M has the total,
         // writes errCount and clears the word.  Workgroups that completed nothing are done here, and no
         // barrier stands between the two atomics.
+        // With p.err_accumulate the count is a counter that is added to: only wavefronts that found corrupted
+        // rows touch it (one atomic without a return value), and nobody waits for anything.
         const unsigned long long fin_mask = __ballot(fin), bad_mask = __ballot(fin && bad);
-        if (fin_mask != 0ull && lane == __builtin_ctzll(fin_mask)) {
+        if (p.err_count == nullptr) {
+            // no count was asked for
+        } else if (p.err_accumulate) {
+            if (bad_mask != 0ull && lane == __builtin_ctzll(bad_mask))
+                __hip_atomic_fetch_add(p.err_count, (int32_t)__builtin_popcountll(bad_mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else if (fin_mask != 0ull && lane == __builtin_ctzll(fin_mask)) {
             unsigned long long* const w_done = reinterpret_cast<unsigned long long*>(p.ws + kWsDoneWord);
             const uint32_t n_fin = (uint32_t)__builtin_popcountll(fin_mask), n_bad = (uint32_t)__builtin_popcountll(bad_mask);
             const unsigned long long old = __hip_atomic_fetch_add(w_done, ((unsigned long long)n_bad << 32) | n_fin,
                                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if ((uint32_t)old + n_fin == (uint32_t)p.M) {
-                if (p.err_count) *p.err_count = (int32_t)((uint32_t)(old >> 32) + n_bad);
+                *p.err_count = (int32_t)((uint32_t)(old >> 32) + n_bad);
                 __hip_atomic_store(w_done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }

@@ -411,7 +411,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_kernel(const GemmPara
             }
             if (cnt) atomicAdd(&s_ctl[1], cnt);
             __syncthreads();
-            if (tid == 0 && p.err_count) *p.err_count = s_ctl[1];
+            if (tid == 0 && p.err_count) {
+                if (!p.err_accumulate) *p.err_count = s_ctl[1];
+                else if (s_ctl[1]) atomicAdd(p.err_count, s_ctl[1]);
+            }
         }
     }
 }

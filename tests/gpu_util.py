@@ -32,7 +32,8 @@ class GpuRun:
         self.b.abft_packed_b_get_col_offsets(self.Bp, out)
         return out.cpu().numpy()
 
-    def gemm(self, A, variant="auto", check=True, injections=(), requant=None, want_c=True, ws=None, mod127=False):
+    def gemm(self, A, variant="auto", check=True, injections=(), requant=None, want_c=True, ws=None, mod127=False,
+             accumulate_from=None, want_count=True):
         """A: numpy uint8 [M,K] or a device tensor.  requant = (zA, zC, mult_np, bias_np|None).
         Returns dict with C, flags, err_count, Cq (numpy; None where not produced)."""
         b = self.b
@@ -40,7 +41,8 @@ class GpuRun:
         M = A_dev.shape[0]
         C = torch.full((M, self.N), -7, dtype=torch.int32, device="cuda") if want_c else None
         flags = torch.full((M,), -1, dtype=torch.int32, device="cuda")
-        cnt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        # accumulate_from = n: errCount is a counter that starts at n and is added to (ABFT_ERRCOUNT_ACCUMULATE)
+        cnt = torch.full((1,), -1 if accumulate_from is None else accumulate_from, dtype=torch.int32, device="cuda")
         if ws is None:
             ws = b.Workspace(M, self.Bp)
         rq = Cq = None
@@ -54,7 +56,9 @@ class GpuRun:
             Cq = torch.full((M, self.N), 7, dtype=torch.uint8, device="cuda")
         inj = b.make_injections(list(injections)) if len(injections) else None
         fl = VARIANTS[variant] | (b.ABFT_CHECK if check else b.ABFT_NOCHECK) | (b.ABFT_MOD127 if mod127 else 0)
-        b.abft_gemm_u8s8s32_checked(A_dev, self.Bp, C, flags, cnt, rq=rq, Cq=Cq, inj=inj, n_inj=len(injections),
+        if accumulate_from is not None:
+            fl |= b.ABFT_ERRCOUNT_ACCUMULATE
+        b.abft_gemm_u8s8s32_checked(A_dev, self.Bp, C, flags, cnt if want_count else None, rq=rq, Cq=Cq, inj=inj, n_inj=len(injections),
                                     flags=fl, workspace=ws.tensor)
         torch.cuda.synchronize()
         return {

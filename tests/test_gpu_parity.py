@@ -766,3 +766,29 @@ def test_mod127_on_the_tall_skinny_workload(binding, gpu_util, oracle):
         binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
         assert np.array_equal(out["C"], Cw) and np.array_equal(out["flags"], fw) and out["err_count"] == nw
     assert not out["ws"].any()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("M,N,K,variant", [(300, 520, 200, "tile64"), (300, 520, 200, "tile128"), (300, 520, 256, "tile256"),
+                                           (200, 300, 2304, "auto"), (16, 4096, 2048, "auto"), (40, 100, 144, "smallm"),
+                                           (129, 257, 65, "auto"), (100, 64, 272, "tile64"), (13, 16, 64, "smallm")])
+def test_errcount_as_a_counter_and_without_one(binding, gpu_util, oracle, M, N, K, variant):
+    """ABFT_ERRCOUNT_ACCUMULATE: the flagged rows are added to the caller's counter (Algorithm 1's errCount++),
+    a clean launch leaves it alone; err_count = NULL: flags only.  Every kernel family, including shapes with a
+    single tile column / column block (whose rows are judged inside one workgroup)."""
+    say(f"errCount modes: {M}x{N}x{K} variant={variant}")
+    A, B = operands(M, N, K, 3 * M + N + K)
+    run = gpu_util.GpuRun(binding, B)
+    ws = binding.Workspace(M, run.Bp)
+    inj = [(0, 0, 1 << 31), (M - 1, N - 1, 1), (M // 2, N // 3, 1 << 9), (M // 2, N // 2, 1 << 3)]
+    ref = oracle.checked_gemm(A, B, flips_c=inj)
+    clean = oracle.checked_gemm(A, B)
+    out = run.gemm(A, variant=variant, ws=ws, accumulate_from=5)
+    assert np.array_equal(out["C"], clean.C) and not out["flags"].any() and out["err_count"] == 5
+    out = run.gemm(A, variant=variant, ws=ws, injections=inj, accumulate_from=5)
+    assert np.array_equal(out["C"], ref.C) and np.array_equal(out["flags"], ref.flags)
+    assert out["err_count"] == 5 + ref.err_count == 8
+    out = run.gemm(A, variant=variant, ws=ws, injections=inj, want_count=False)
+    assert np.array_equal(out["C"], ref.C) and np.array_equal(out["flags"], ref.flags) and out["err_count"] == -1
+    out = run.gemm(A, variant=variant, ws=ws, injections=inj)        # the overwriting form on the same workspace
+    assert np.array_equal(out["flags"], ref.flags) and out["err_count"] == 3 and not out["ws"].any()
