@@ -495,21 +495,27 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
             for (int kbl = 0; kbl < 2; ++kbl)
 #pragma unroll
                 for (int c = 0; c < CB; ++c) mfma_digits(cacc[c], dig_a[kbl][c] ^ (int)0x80808080, limb[kbl]);
-            asm volatile("s_nop 7\n\ts_nop 7");
+            // (the digit accumulators are next touched a whole stage later, or after the wait states that
+            // follow this run of stages)
         };
         if constexpr (kAhead2) {
             for (int s = s_begin; s < s_end; ++s) {
                 const int nxt = cur + 1 == S ? 0 : cur + 1;
                 const int s_new = min(s + S, NS - 1);  // refills the slot of this stage once it is released
-                if (CHK) load_limbs(s);
+                // the digit operands of this stage (it is resident) are read ahead of the fragments of its
+                // first k-step and are there, reads completing in order, when the wait behind that k-step ends:
+                // nothing of the digit work waits for LDS on its own
+                if (CHK) {
+                    load_limbs(s);
+                    digit_reads(cur);
+                }
                 phase_small(0, 2, cur, 2, even_c{}, 0, 0, 0, 0);
                 wait_lds_but(frag_reads_c{});
                 __builtin_amdgcn_sched_barrier(0);
+                if (CHK) digit_mfmas();
                 phase_small(1, 3, cur, 3, odd_c{}, 0, 0, 0, 0);
-                if (CHK) digit_reads(cur);
                 wait_lds();  // every fragment of this stage is in registers
                 __builtin_amdgcn_sched_barrier(0);
-                if (CHK) digit_mfmas();
                 wait_vmem_but(pending_c{});
                 __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
@@ -521,6 +527,8 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
                 __builtin_amdgcn_sched_barrier(0);
                 cur = nxt;
             }
+            // the last digit MFMAs of the run: cover the longest write-to-read distance once, whatever follows
+            if (CHK) asm volatile("s_nop 7\n\ts_nop 7");
         } else {
             for (int s = s_begin; s < s_end; ++s) {
                 // stage whose loads go out now, the slot they go to, and the slot of the next stage
