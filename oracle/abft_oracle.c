@@ -364,3 +364,79 @@ void oracle_campaign_a_flips(const uint8_t* A, int64_t lda, const int8_t* B, int
         free(a);
     }
 }
+
+/* ---- Locating and correcting a single faulty element (Section IV, Eq. 2a and the two ----
+ * ---- correction formulas that follow the pair of checks)                              ----
+ * The full scheme encodes A as well: S_A[k] = sum_i A[i][k] (the appended row of A'), whose
+ * product with B is the extra row of C', C'[m][j] = (S_A B)[j].  Eq. 2a: every column of a
+ * correct C sums to that entry.  All sums modulo 2^32, like the row check. */
+
+/* S_A[k] = sum_i A[i][k] (Section IV, definition of the row appended to A). */
+void oracle_a_colsum(const uint8_t* A, int64_t lda, int M, int K, int32_t* S_A) {
+    for (int k = 0; k < K; ++k) {
+        uint32_t s = 0;
+        for (int i = 0; i < M; ++i) s += (uint32_t)A[(int64_t)i * lda + k];
+        S_A[k] = (int32_t)s;
+    }
+}
+
+/* C'[m][j] = sum_k S_A[k] * B[k][j]: the checksum row, computed on its own (not from C). */
+void oracle_col_checksum(const int32_t* S_A, const int8_t* B, int64_t ldb, int K, int N, int32_t* col_chk) {
+    for (int j = 0; j < N; ++j) {
+        uint32_t s = 0;
+        for (int k = 0; k < K; ++k) s += (uint32_t)S_A[k] * (uint32_t)(int32_t)B[(int64_t)k * ldb + j];
+        col_chk[j] = (int32_t)s;
+    }
+}
+
+/* Right-hand side of Eq. 2a: csum[j] = sum_i C[i][j]. */
+void oracle_col_sums(const int32_t* C, int64_t ldc, int M, int N, int32_t* csum) {
+    for (int j = 0; j < N; ++j) {
+        uint32_t s = 0;
+        for (int i = 0; i < M; ++i) s += (uint32_t)C[(int64_t)i * ldc + j];
+        csum[j] = (int32_t)s;
+    }
+}
+
+/* The decision and the repair (text after Eq. 2b): with exactly one row i violating Eq. 2b and
+ * exactly one column j violating Eq. 2a the element C[i][j] is the faulty one, and
+ *     correct C[i][j] = C'[m][j] - sum_{p != i} C[p][j]      (first formula)
+ *                     = C'[i][n] - sum_{p != j} C[i][p]      (second formula).
+ * C is repaired in place with the first formula; the second is evaluated too and the pair must agree,
+ * otherwise nothing is written (a pattern that is not one faulty element of C).
+ * row_flags: the verdicts of Eq. 2b as the checked product returned them; row_chk[i] = (A S_B)[i].
+ * out[0] = status: 0 nothing violated, 1 located and corrected, 2 violations that do not single out
+ * one element (C untouched); out[1], out[2] = row, column (status 1, else -1); out[3], out[4] = value
+ * found there and value written; out[5], out[6] = number of violated rows and columns. */
+void oracle_locate_correct(int32_t* C, int64_t ldc, int M, int N, const int32_t* row_flags, const int32_t* row_chk,
+                           const int32_t* col_chk, int32_t* col_flags, int32_t* out) {
+    int n_rows = 0, n_cols = 0, row = -1, col = -1;
+    for (int i = 0; i < M; ++i)
+        if (row_flags[i] != 0) { ++n_rows; row = i; }
+    for (int j = 0; j < N; ++j) {
+        uint32_t s = 0;
+        for (int i = 0; i < M; ++i) s += (uint32_t)C[(int64_t)i * ldc + j];
+        col_flags[j] = (int32_t)s != col_chk[j];
+        if (col_flags[j]) { ++n_cols; col = j; }
+    }
+    out[0] = (n_rows == 0 && n_cols == 0) ? 0 : 2;
+    out[1] = out[2] = -1;
+    out[3] = out[4] = 0;
+    out[5] = n_rows;
+    out[6] = n_cols;
+    if (n_rows != 1 || n_cols != 1) return;
+    uint32_t others_in_col = 0, others_in_row = 0;
+    for (int p = 0; p < M; ++p)
+        if (p != row) others_in_col += (uint32_t)C[(int64_t)p * ldc + col];
+    for (int p = 0; p < N; ++p)
+        if (p != col) others_in_row += (uint32_t)C[(int64_t)row * ldc + p];
+    const int32_t by_column = (int32_t)((uint32_t)col_chk[col] - others_in_col);
+    const int32_t by_row = (int32_t)((uint32_t)row_chk[row] - others_in_row);
+    if (by_column != by_row) return;
+    out[0] = 1;
+    out[1] = row;
+    out[2] = col;
+    out[3] = C[(int64_t)row * ldc + col];
+    out[4] = by_column;
+    C[(int64_t)row * ldc + col] = by_column;
+}

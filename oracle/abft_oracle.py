@@ -70,6 +70,10 @@ def lib() -> ctypes.CDLL:
                                                _int, _i32p, _i32p, _i32p, _i32p, _i32p]
         L.oracle_campaign_a_flips.argtypes = [_u8p, _i64, _i8p, _i64, _i32p, _int, _int, _int,
                                               _i32p, _i32p, _i32p, _i32p, _i32p]
+        L.oracle_a_colsum.argtypes = [_u8p, _i64, _int, _int, _i32p]
+        L.oracle_col_checksum.argtypes = [_i32p, _i8p, _i64, _int, _int, _i32p]
+        L.oracle_col_sums.argtypes = [_i32p, _i64, _int, _int, _i32p]
+        L.oracle_locate_correct.argtypes = [_i32p, _i64, _int, _int, _i32p, _i32p, _i32p, _i32p, _i32p]
         _lib = L
     return _lib
 
@@ -360,3 +364,64 @@ def campaign_a_flips(A, B, S_B, is_, ks, bits, want_rows=False):
                                   _p(is_, _i32p), _p(ks, _i32p), _p(bits, _i32p), _p(flag, _i32p),
                                   _p(rows, _i32p) if want_rows else None)
     return (flag, rows) if want_rows else flag
+
+
+# ---- locating and correcting one faulty element (Section IV, Eq. 2a) --------------------
+
+def a_colsum(A: np.ndarray) -> np.ndarray:
+    """S_A[k] = sum_i A[i][k], the row appended to A (Section IV)."""
+    A = _c(A, np.uint8)
+    M, K = A.shape
+    out = np.empty(K, np.int32)
+    lib().oracle_a_colsum(_p(A, _u8p), _ld(A), M, K, _p(out, _i32p))
+    return out
+
+
+def col_checksum(S_A: np.ndarray, B: np.ndarray) -> np.ndarray:
+    """The checksum row C'[m][:] = S_A B, computed on its own."""
+    S_A = _c(S_A, np.int32)
+    B = _c(B, np.int8)
+    K, N = B.shape
+    out = np.empty(N, np.int32)
+    lib().oracle_col_checksum(_p(S_A, _i32p), _p(B, _i8p), _ld(B), K, N, _p(out, _i32p))
+    return out
+
+
+def col_sums(C: np.ndarray) -> np.ndarray:
+    C = _c(C, np.int32)
+    M, N = C.shape
+    out = np.empty(N, np.int32)
+    lib().oracle_col_sums(_p(C, _i32p), _ld(C), M, N, _p(out, _i32p))
+    return out
+
+
+@dataclass
+class Located:
+    C: np.ndarray           # C after the call (repaired in place when status == 1)
+    status: int             # 0 nothing violated, 1 located and corrected, 2 not one element
+    row: int
+    col: int
+    old_value: int
+    new_value: int
+    rows_violated: int
+    cols_violated: int
+    col_flags: np.ndarray
+
+
+def locate_correct(A, B, C, row_flags, S_B=None) -> Located:
+    """Eq. 2a on the stored C with the checksum row recomputed from A and the B in memory, then the
+    decision and repair of Section IV.  A, B: the operands as they stand in memory; C, row_flags: what
+    the checked product returned; S_B: the checksum column stored with the weight (when B was hit after
+    it was encoded, pass the column of the clean B; default: computed from B)."""
+    A = _c(A, np.uint8)
+    B = _c(B, np.int8)
+    C = np.array(_c(C, np.int32), copy=True)
+    row_flags = _c(np.asarray(row_flags, np.int32), np.int32)
+    M, N = C.shape
+    col_chk = col_checksum(a_colsum(A), B)
+    row_chk = row_checksum(A, b_checksum(B) if S_B is None else _c(S_B, np.int32))
+    col_flags = np.empty(N, np.int32)
+    out = np.zeros(8, np.int32)
+    lib().oracle_locate_correct(_p(C, _i32p), _ld(C), M, N, _p(row_flags, _i32p), _p(row_chk, _i32p),
+                                _p(col_chk, _i32p), _p(col_flags, _i32p), _p(out, _i32p))
+    return Located(C, int(out[0]), int(out[1]), int(out[2]), int(out[3]), int(out[4]), int(out[5]), int(out[6]), col_flags)

@@ -374,3 +374,122 @@ def test_mod127_rowsum_entry_flip_closed_form(oracle):
         want = ((A[:, 5].astype(np.int64) * delta) % 127 != 0).astype(np.int32)
         assert np.array_equal(flags, want) and n == int(want.sum())
         assert flags[0] == 0 and flags[1] == 0 and flags[2] == 0
+
+
+# ---- locating and correcting one faulty element (Section IV, Eq. 2a) ------------------------
+
+def test_column_checksum_row_against_bigint_and_matmul(oracle):
+    """S_A and the checksum row S_A B: Python integers on tiny extreme inputs, float64 matmul (exact below
+    2^53) on a workload-sized case, and Eq. 2a itself: every column of a clean product sums to its entry."""
+    for (M, N, K) in [(1, 1, 1), (2, 3, 4), (5, 2, 3)]:
+        for a_val in (0, 255):
+            for b_val in (-128, 127):
+                A = np.full((M, K), a_val, np.uint8)
+                B = np.full((K, N), b_val, np.int8)
+                A[0, 0] = 7
+                B[0, N - 1] = -3
+                S_A = oracle.a_colsum(A)
+                want_S = [sum(int(A[i, k]) for i in range(M)) for k in range(K)]
+                assert S_A.tolist() == want_S
+                chk = oracle.col_checksum(S_A, B)
+                want = [sum(want_S[k] * int(B[k, j]) for k in range(K)) for j in range(N)]
+                assert [int(v) for v in chk] == [((w + 2**31) % 2**32) - 2**31 for w in want]
+    rng = np.random.default_rng(11)
+    A = rng.integers(0, 256, size=(256, 1024), dtype=np.uint8)
+    B = rng.integers(-128, 128, size=(1024, 300), dtype=np.int8)
+    S_A = oracle.a_colsum(A)
+    assert np.array_equal(S_A, A.astype(np.int64).sum(axis=0).astype(np.int32))
+    exact = (S_A.astype(np.float64) @ B.astype(np.float64)).astype(np.int64)
+    chk = oracle.col_checksum(S_A, B)
+    assert np.array_equal(chk, (exact & 0xFFFFFFFF).astype(np.uint32).view(np.int32))
+    C = oracle.gemm_u8s8s32(A, B)
+    assert np.array_equal(oracle.col_sums(C), chk)                       # Eq. 2a on a clean product
+    assert np.array_equal(oracle.col_sums(C), C.astype(np.int64).sum(axis=0).astype(np.uint64).astype(np.uint32).view(np.int32))
+
+
+def test_column_checksum_closed_form_with_wrap(oracle):
+    """Constant operands: S_A = M a, checksum row = K M a b, forced past 2^31."""
+    M, N, K, a, b = 3000, 3, 40, 255, 127
+    A = np.full((M, K), a, np.uint8)
+    B = np.full((K, N), b, np.int8)
+    assert K * M * a * b > 2**31
+    chk = oracle.col_checksum(oracle.a_colsum(A), B)
+    want = ((K * M * a * b + 2**31) % 2**32) - 2**31
+    assert chk.tolist() == [want] * N
+
+
+def test_single_c_fault_is_located_and_restored_for_every_bit(oracle):
+    rng = np.random.default_rng(12)
+    M, N, K = 23, 17, 40
+    A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+    B = rng.integers(-128, 128, size=(K, N), dtype=np.int8)
+    clean = oracle.checked_gemm(A, B)
+    got = oracle.locate_correct(A, B, clean.C, clean.flags)
+    assert got.status == 0 and got.rows_violated == 0 and got.cols_violated == 0 and np.array_equal(got.C, clean.C)
+    for bit in range(32):
+        r, c = int(rng.integers(M)), int(rng.integers(N))
+        bad = oracle.checked_gemm(A, B, flips_c=[(r, c, 1 << bit)])
+        assert bad.err_count == 1 and bad.flags[r] == 1
+        got = oracle.locate_correct(A, B, bad.C, bad.flags)
+        assert (got.status, got.row, got.col) == (1, r, c)
+        assert got.old_value == int(bad.C[r, c]) and got.new_value == int(clean.C[r, c])
+        assert np.array_equal(got.C, clean.C)
+        want_cols = np.zeros(N, np.int32)
+        want_cols[c] = 1
+        assert np.array_equal(got.col_flags, want_cols)
+    # an arbitrary replacement value (second fault model of Section IV-C) is repaired just the same
+    bad = oracle.checked_gemm(A, B, flips_c=[(5, 6, 0xDEADBEEF)])
+    got = oracle.locate_correct(A, B, bad.C, bad.flags)
+    assert got.status == 1 and np.array_equal(got.C, clean.C)
+
+
+def test_patterns_that_are_not_one_element_are_left_alone(oracle):
+    rng = np.random.default_rng(13)
+    M, N, K = 20, 30, 25
+    A = rng.integers(1, 256, size=(M, K), dtype=np.uint8)
+    B = rng.integers(-127, 128, size=(K, N), dtype=np.int8)
+    clean = oracle.checked_gemm(A, B)
+    # two faults: distinct rows and columns / same row / same column
+    for flips, rows, cols in (([(1, 2, 1 << 5), (7, 9, 1 << 20)], 2, 2), ([(4, 2, 1), (4, 9, 1 << 31)], 1, 2),
+                              ([(4, 3, 1 << 8), (11, 3, 1 << 9)], 2, 1)):
+        bad = oracle.checked_gemm(A, B, flips_c=flips)
+        got = oracle.locate_correct(A, B, bad.C, bad.flags)
+        assert got.status == 2 and (got.rows_violated, got.cols_violated) == (rows, cols)
+        assert np.array_equal(got.C, bad.C) and got.row == -1 and got.col == -1
+    # a fault in B after it was encoded corrupts a whole column of C consistently with the B in memory:
+    # rows violate Eq. 2b, no column violates Eq. 2a, nothing is "corrected"
+    bad = oracle.checked_gemm(A, B, flips_b=[(3, 8, 6)])
+    assert bad.err_count == M
+    B_bad = B.copy()
+    B_bad.view(np.uint8)[3, 8] ^= np.uint8(1 << 6)
+    got = oracle.locate_correct(A, B_bad, bad.C, bad.flags, S_B=clean.S_B)
+    assert got.status == 2 and got.rows_violated == M and got.cols_violated == 0 and np.array_equal(got.C, bad.C)
+    # ... even when only one row shows it (all other rows have a zero at that k)
+    A1 = A.copy()
+    A1[:, 3] = 0
+    A1[6, 3] = 9
+    bad = oracle.checked_gemm(A1, B, flips_b=[(3, 8, 6)])
+    assert bad.err_count == 1
+    got = oracle.locate_correct(A1, B_bad, bad.C, bad.flags, S_B=oracle.b_checksum(B))
+    assert got.status == 2 and (got.rows_violated, got.cols_violated) == (1, 0) and np.array_equal(got.C, bad.C)
+    # one column violated, no row flagged (a stale verdict): not an element either
+    C2 = clean.C.copy()
+    C2[2, 2] ^= 4
+    got = oracle.locate_correct(A, B, C2, clean.flags)
+    assert got.status == 2 and (got.rows_violated, got.cols_violated) == (0, 1) and np.array_equal(got.C, C2)
+
+
+def test_the_two_correction_formulas_agree_or_nothing_is_written(oracle):
+    """One row and one column violated, but by different elements' worth: the column formula and the row formula
+    give different values, and C is left as it is."""
+    rng = np.random.default_rng(14)
+    M, N, K = 9, 8, 16
+    A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+    B = rng.integers(-128, 128, size=(K, N), dtype=np.int8)
+    clean = oracle.checked_gemm(A, B)
+    C2 = clean.C.copy()
+    C2[3, 5] += 100
+    flags = np.zeros(M, np.int32)
+    flags[7] = 1                      # verdicts that name another row than the one the column points at
+    got = oracle.locate_correct(A, B, C2, flags)
+    assert got.status == 2 and (got.rows_violated, got.cols_violated) == (1, 1) and np.array_equal(got.C, C2)
