@@ -161,6 +161,27 @@ def recovery_sample(job, rows=(1, 64)):
             assert (before, after) == (n, 0), (before, after)
             best = dt if best is None else min(best, dt)
         out[f"{n}_rows_us"] = best
+    # the other recovery path: locate the one faulty element with the column check (Eq. 2a) and rewrite it
+    # (asynchronous; device time between two events on the launching stream, best of five)
+    if job.rq is None or job.C is not None:
+        t = int(first[0])
+        inj = b.make_injections([(int(r[t]), int(c[t]), 1 << int(bit[t]))])
+        loc_scratch = torch.empty(b.abft_locate_scratch_bytes(job.Bp[0]), dtype=torch.uint8, device="cuda")
+        report = torch.empty(8, dtype=torch.int32, device="cuda")
+        best = None
+        for _ in range(5):
+            job.cnt.zero_()
+            job.step(True, inj=inj, n_inj=1)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            b.abft_locate_correct(job.A, job.Bp[0], job.C, job.flags, job.cnt, rq=job.rq, Cq=job.Cq, report=report, scratch=loc_scratch)
+            e1.record()
+            torch.cuda.synchronize()
+            rep = report.cpu().numpy()
+            assert int(rep[0]) == b.ABFT_LOCATE_CORRECTED and (int(rep[1]), int(rep[2])) == (int(r[t]), int(c[t])), rep
+            dt = e0.elapsed_time(e1) * 1e3
+            best = dt if best is None else min(best, dt)
+        out["locate_correct_1_element_us"] = best
     return out
 
 
@@ -565,7 +586,8 @@ def main():
                                   f"{wrong} rows flagged other than the injected one"
     if not args.no_detection and not args.mod127:
         out["recovery"] = recovery_sample(job)
-        out["recovery_note"] = "host wall time of abft_recompute_flagged_rows (gather, re-checked GEMM, scatter; synchronises)"
+        out["recovery_note"] = ("N_rows_us: host wall time of abft_recompute_flagged_rows (gather, re-checked GEMM, scatter; synchronises); "
+                                "locate_correct_1_element_us: device time of abft_locate_correct (column check of Eq. 2a, repair of the located element)")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(job)
     if not args.only_headline:

@@ -230,6 +230,49 @@ int abft_recompute_flagged_rows(const uint8_t* A, int64_t lda, int M, const abft
                                 int max_rows_per_pass, void* scratch, size_t scratch_bytes, void* stream,
                                 int* rows_before, int* rows_after);
 
+/* Locating and correcting one faulty element of C_temp (Section IV: the column
+ * check of Eq. 2a next to the row check of Eq. 2b, and the two correction
+ * formulas that follow them).  The product itself stays with detection and an
+ * encoded B only, as the paper prescribes (Section IV-A-1); this call is the
+ * other half of the classic scheme, run on demand once a launch has flagged
+ * something: it forms S_A = e^T A from the A in memory, the checksum row
+ * C'[m][:] = S_A B from the packed weight, and the column sums of the stored
+ * C_temp (all wrap-around int32).  When exactly one row is flagged in row_flags
+ * (the verdicts of Eq. 2b as abft_gemm_u8s8s32_checked returned them) and exactly
+ * one column violates Eq. 2a, the element where they cross is recomputed as
+ *     C'[m][j] - sum_{p != i} C[p][j]
+ * and, as a cross-check, as (A S_B)[i] - sum_{p != j} C[i][p]; if the two agree the
+ * value is written to C (and requantized into Cq when rq != NULL), row_flags[i]
+ * is cleared and *err_count is decremented.  Any other pattern - several rows or
+ * columns, rows without a column (a fault in B after it was encoded corrupts a
+ * column of C consistently with the B in memory), formulas that disagree - leaves
+ * C, row_flags and err_count as they are.
+ *   A, lda, M, Bp, C, ldc, rq, Cq, ldcq   as for abft_gemm_u8s8s32_checked (C must
+ *              be present: the check reads the stored 32-bit values).
+ *   col_flags  int32 [N], overwritten with the verdicts of Eq. 2a; may be NULL.
+ *   report     DEVICE memory for one abft_locate_t, overwritten.
+ *   scratch    abft_locate_scratch_bytes(Bp) bytes of device memory, contents
+ *              irrelevant.
+ * Asynchronous like every other call; four small kernels, about one pass over A,
+ * the packed B and C. */
+#define ABFT_LOCATE_CLEAN 0            /* no row flagged, no column violated */
+#define ABFT_LOCATE_CORRECTED 1        /* one element located and rewritten */
+#define ABFT_LOCATE_NOT_ONE_ELEMENT 2  /* violations that do not single out one element; nothing written */
+typedef struct {
+    int32_t status;        /* ABFT_LOCATE_* */
+    int32_t row, col;      /* the element (status CORRECTED), else -1 */
+    int32_t old_value;     /* what was stored there */
+    int32_t new_value;     /* what was written */
+    int32_t rows_flagged;  /* rows set in row_flags on entry */
+    int32_t cols_violated; /* columns violating Eq. 2a */
+    int32_t reserved;
+} abft_locate_t;
+size_t abft_locate_scratch_bytes(const abft_packed_b* Bp);
+int abft_locate_correct(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp, int32_t* C, int64_t ldc,
+                        int32_t* row_flags, int32_t* err_count, const abft_requant_t* rq, uint8_t* Cq,
+                        int64_t ldcq, int32_t* col_flags, abft_locate_t* report, void* scratch,
+                        size_t scratch_bytes, void* stream);
+
 /* Measurement aid, not part of the method: a plain device-to-device copy of
  * `bytes` (a positive multiple of 16; both pointers 16-byte aligned, buffers
  * must not overlap).  It reads and writes exactly `bytes` once, which makes it

@@ -27,8 +27,9 @@ EXPORTS = (
     "abft_gemm_workspace_bytes", "abft_workspace_init", "abft_gemm_u8s8s32_checked", "abft_gemm_u8s8s32_checked_static",
     "abft_requantize_u8",
     "abft_verify_rows", "abft_row_checksum", "abft_recover_scratch_bytes", "abft_recompute_flagged_rows",
-    "abft_calib_copy", "abft_last_error",
+    "abft_locate_scratch_bytes", "abft_locate_correct", "abft_calib_copy", "abft_last_error",
 )
+ABFT_LOCATE_CLEAN, ABFT_LOCATE_CORRECTED, ABFT_LOCATE_NOT_ONE_ELEMENT = 0, 1, 2
 EXPORTS_EB = (
     "abft_eb_pack_rowsum", "abft_eb_table_dims", "abft_eb_table_get_rowsums", "abft_eb_table_flip_bit",
     "abft_eb_table_destroy", "abft_eb_u8_checked",
@@ -85,6 +86,9 @@ def _load() -> ctypes.CDLL:
     L.abft_recover_scratch_bytes.restype = sz
     L.abft_recompute_flagged_rows.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64,
                                               i32, vp, sz, vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.abft_locate_scratch_bytes.argtypes = [vp]
+    L.abft_locate_scratch_bytes.restype = sz
+    L.abft_locate_correct.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64, vp, vp, vp, sz, vp]
     L.abft_eb_pack_rowsum.argtypes = [vp, i64, vp, vp, i64, i32, u32, vp, ctypes.POINTER(vp)]
     L.abft_eb_table_dims.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.abft_eb_table_get_rowsums.argtypes = [vp, vp, vp]
@@ -292,6 +296,30 @@ def abft_recompute_flagged_rows(A, Bp: PackedB, C, row_flags, err_count=None, rq
         ctypes.byref(rq) if rq is not None else None, _ptr(Cq, torch.uint8, "Cq"), _ld(Cq, "Cq") if Cq is not None else 0,
         max_rows_per_pass, scratch.data_ptr(), scratch.numel(), _stream(stream), ctypes.byref(before), ctypes.byref(after)))
     return before.value, after.value
+
+
+def abft_locate_scratch_bytes(Bp: PackedB) -> int:
+    return int(lib.abft_locate_scratch_bytes(Bp.handle))
+
+
+def abft_locate_correct(A, Bp: PackedB, C, row_flags, err_count=None, rq=None, Cq=None, col_flags=None, report=None,
+                        scratch=None, stream=None):
+    """Eq. 2a column check + repair of a single located element, in place, asynchronously.  Returns the device
+    tensor holding the abft_locate_t report (8 int32: status, row, col, old, new, rows flagged, columns violated, -)."""
+    M = A.shape[0]
+    if scratch is None:
+        scratch = torch.empty(abft_locate_scratch_bytes(Bp), dtype=torch.uint8, device=A.device)
+    if report is None:
+        report = torch.empty(8, dtype=torch.int32, device=A.device)
+    if col_flags is not None and col_flags.numel() < Bp.N:
+        raise ValueError("col_flags shorter than N")
+    _check(lib.abft_locate_correct(
+        _ptr(A, torch.uint8, "A"), _ld(A, "A"), M, Bp.handle, _ptr(C, torch.int32, "C"), _ld(C, "C"),
+        _ptr(row_flags, torch.int32, "row_flags"), _ptr(err_count, torch.int32, "err_count"),
+        ctypes.byref(rq) if rq is not None else None, _ptr(Cq, torch.uint8, "Cq"), _ld(Cq, "Cq") if Cq is not None else 0,
+        _ptr(col_flags, torch.int32, "col_flags"), _ptr(report, torch.int32, "report"),
+        scratch.data_ptr(), scratch.numel() * scratch.element_size(), _stream(stream)))
+    return report
 
 
 def abft_calib_copy(src, dst, stream=None):

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libabftgemm.so")
 SOURCES = ["api.hip", "pack.hip", "gemm_tile.hip", "gemm_tile_a256.hip", "gemm_tile_a256w24.hip", "gemm_tile_a256w42.hip",
            "gemm_tile_a128.hip", "gemm_tile_a64.hip", "gemm_tile_a64r8.hip", "gemm_tile_a64k2.hip", "gemm_tile_g128.hip", "gemm_tile_g64.hip", "gemm_smallm.hip",
-           "rowops.hip", "eb.hip"]
+           "rowops.hip", "locate.hip", "eb.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",

@@ -428,6 +428,32 @@ int abft_recompute_flagged_rows(const uint8_t* A, int64_t lda, int M, const abft
     return ABFT_OK;
 }
 
+size_t abft_locate_scratch_bytes(const abft_packed_b* Bp) {
+    if (!Bp) return 0;
+    return ((size_t)Bp->KB * abft::kUnitK + 2 * (size_t)Bp->NT * abft::kTileN) * sizeof(int32_t);
+}
+
+int abft_locate_correct(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp, int32_t* C, int64_t ldc,
+                        int32_t* row_flags, int32_t* err_count, const abft_requant_t* rq, uint8_t* Cq, int64_t ldcq,
+                        int32_t* col_flags, abft_locate_t* report, void* scratch, size_t scratch_bytes, void* stream) {
+    const char* fn = "abft_locate_correct";
+    if (!A || !Bp || !C || !row_flags || !report || !scratch) return fail(ABFT_EINVAL, "%s: null pointer", fn);
+    if (M < 1 || lda < Bp->K || ldc < Bp->N) return fail(ABFT_EINVAL, "%s: bad shape (M=%d lda=%lld ldc=%lld)", fn, M, (long long)lda, (long long)ldc);
+    if (rq && (!Cq || ldcq < Bp->N || !rq->mult)) return fail(ABFT_EINVAL, "%s: bad requantized output", fn);
+    if (scratch_bytes < abft_locate_scratch_bytes(Bp))
+        return fail(ABFT_EINVAL, "%s: scratch of %zu bytes, %zu needed", fn, scratch_bytes, abft_locate_scratch_bytes(Bp));
+    if (((uintptr_t)scratch | (uintptr_t)report) & 3) return fail(ABFT_EINVAL, "%s: scratch and report must be 4-byte aligned", fn);
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev != Bp->device)
+        return fail(ABFT_EINVAL, "%s: the packed B lives on device %d, the current device is %d", fn, Bp->device, dev);
+    abft::RequantDev r{};
+    if (rq) r = abft::RequantDev{rq->zA, rq->zC, rq->mult, rq->per_channel, rq->bias};
+    HIP_TRY(abft::launch_locate_correct(A, lda, M, Bp, C, ldc, row_flags, err_count, rq ? &r : nullptr, Cq, ldcq, col_flags,
+                                        reinterpret_cast<int32_t*>(report), (int32_t*)scratch, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
 int abft_calib_copy(const void* src, void* dst, size_t bytes, void* stream) {
     const char* fn = "abft_calib_copy";
     if (!src || !dst) return fail(ABFT_EINVAL, "%s: null pointer", fn);
