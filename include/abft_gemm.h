@@ -51,8 +51,8 @@ extern "C" {
 #define ABFT_MOD127 2u            /* Algorithm 1 to the letter: the checksum column is
                                      rowSum = (B e) mod 127, one 8-bit column (Section
                                      IV-A-2), and a row is flagged when its sum and its
-                                     checksum entry differ modulo 127.  Tiled kernels,
-                                     16-byte aligned A, K <= 65536. */
+                                     checksum entry differ modulo 127.  16-byte aligned
+                                     A with K a multiple of 16, K <= 65536. */
 #define ABFT_ERRCOUNT_ACCUMULATE 4u /* errCount as Algorithm 1 writes it, a counter that is
                                      incremented: the number of flagged rows is ADDED to
                                      *err_count (which the caller set, normally to zero, and

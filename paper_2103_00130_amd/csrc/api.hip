@@ -247,10 +247,8 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
     // The streaming kernel reads the weight once and wins wherever that dominates: up to 32 rows always,
     // up to 64 rows when the weight is large (measured: 64x4096x2048 9.5 us against 10.1 us tiled, but
     // 64x1024x1024 7.0 against 6.5 and 64x256x512 6.3 against 5.3).
-    const bool streaming = !mod127 && (M <= 32 || (M <= 64 && (int64_t)Bp->N * Bp->K >= (int64_t)1 << 22));
+    const bool streaming = M <= 32 || (M <= 64 && (int64_t)Bp->N * Bp->K >= (int64_t)1 << 22);
     if (!chosen) variant = streaming ? (int)abft::kSmallM : pick_tile();
-    if (mod127 && variant == abft::kSmallM)
-        return fail(ABFT_EUNSUPPORTED, "%s: modulus 127 is implemented by the tiled kernels only", fn);
     hipError_t e;
     if (variant == abft::kSmallM) {
         if (M > 64) return fail(ABFT_EUNSUPPORTED, "%s: the streaming variant takes M <= 64, got %d", fn, M);

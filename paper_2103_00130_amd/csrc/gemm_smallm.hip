@@ -36,6 +36,13 @@ __device__ inline uint32_t row_sum16(uint32_t s) {
     return s;
 }
 
+// v mod 127 in [0,126] for |v| < 2^59 (2^28 is 1 modulo 127, so the two parts of v = hi * 2^28 + lo may be added)
+__device__ inline int32_t floor_mod127(long long v) {
+    const int32_t x = (int32_t)(v >> 28) + (int32_t)(v & 0x0FFFFFFF);
+    const int32_t r = x % 127;
+    return r < 0 ? r + 127 : r;
+}
+
 // RB = 16-row blocks of A (M <= 16*RB)
 template <int RB, bool kCheck, int kOut>
 __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, const int n_blocks) {
@@ -187,18 +194,23 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
                 }
             }
         if (kCheck) {
+            const bool mod127 = p.mod127 != 0;
             const int slot = cb & (kSmallMSlots - 1);
             const uint32_t total128 = 128u * (uint32_t)total_sb;  // sum_k 128*S_B[k], once per row (first column block)
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const uint32_t rs = row_sum16((uint32_t)acc[rb][e]);
+                    // (Algorithm 1 as printed, p.mod127: the entries are exact 32-bit values, K <= 65536, and are
+                    // summed as residues; the one live digit column holds rowSum, so its product is exact too)
+                    const uint32_t rs = row_sum16(mod127 ? (uint32_t)floor_mod127((long long)acc[rb][e]) : (uint32_t)acc[rb][e]);
                     uint32_t ck = lcol < kLimbs ? ((uint32_t)cacc[rb][e] << (8 * lcol)) : 0u;
                     ck += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)ck, 0xB1, 0xF, 0xF, true);
                     ck += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)ck, 0x4E, 0xF, 0xF, true);
                     const int row = rb * 16 + 4 * lkg + e;
-                    if (lcol == 0) s_d[row] = rs - ck - total128;
+                    if (lcol == 0)
+                        s_d[row] = mod127 ? (uint32_t)floor_mod127((long long)rs - (long long)(int32_t)ck - 128ll * (long long)total_sb)
+                                          : rs - ck - total128;
                 }
             // One row per lane.  The row's difference climbs workspace words, each a 64-bit
             // (value << 32 | arrivals) taken with one returned atomic.  With more than 32 column
@@ -229,14 +241,15 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
                 }
                 if (n_blocks == 1) {
                     // a single column block holds the whole row: nothing crosses workgroups
-                    bad = t != 0u;
+                    bad = mod127 ? (t % 127u != 0u) : (t != 0u);
                     p.row_flags[lane] = (int32_t)bad;
                     fin = true;
                 } else if (go) {
                     const unsigned long long old = __hip_atomic_fetch_add(w_row, ((unsigned long long)t << 32) | 1ull,
                                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if ((uint32_t)old == n_row - 1u) {
-                        bad = ((uint32_t)(old >> 32) + t) != 0u;
+                        const uint32_t diff = (uint32_t)(old >> 32) + t;
+                        bad = mod127 ? (diff % 127u != 0u) : (diff != 0u);
                         __hip_atomic_store(w_row, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         p.row_flags[lane] = (int32_t)bad;
                         fin = true;

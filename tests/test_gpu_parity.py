@@ -442,13 +442,11 @@ def test_mod127_full_size_and_refusals(binding, gpu_util, oracle):
     Cw, fw, nw = oracle.checked_gemm_mod127(ops.A, ops.B, flips_c=inj)
     out = run.gemm(ops.A, mod127=True, injections=inj)
     assert np.array_equal(out["C"], Cw) and np.array_equal(out["flags"], fw) and out["err_count"] == nw == 2
-    # the streaming kernel and unaligned operands do not implement the modulus
+    # unaligned operands do not implement the modulus
     A, B = operands(16, 64, 64, 1)
     small = gpu_util.GpuRun(binding, B)
-    out = small.gemm(A, mod127=True)                      # M <= 64 goes to a tiled kernel by itself
+    out = small.gemm(A, mod127=True)
     assert out["err_count"] == 0 and np.array_equal(out["C"], oracle.gemm_u8s8s32(A, B))
-    with pytest.raises(binding.AbftError):
-        small.gemm(A, variant="smallm", mod127=True)
     buf = torch.zeros(16 * 64 + 1, dtype=torch.uint8, device="cuda")
     with pytest.raises(binding.AbftError):
         small.gemm(buf[1:].view(16, 64), mod127=True)
@@ -792,3 +790,47 @@ def test_errcount_as_a_counter_and_without_one(binding, gpu_util, oracle, M, N, 
     assert np.array_equal(out["C"], ref.C) and np.array_equal(out["flags"], ref.flags) and out["err_count"] == -1
     out = run.gemm(A, variant=variant, ws=ws, injections=inj)        # the overwriting form on the same workspace
     assert np.array_equal(out["flags"], ref.flags) and out["err_count"] == 3 and not out["ws"].any()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("M,N,K", [(1, 800, 3200), (16, 48, 64), (17, 100, 144), (33, 70, 272), (64, 1000, 1040), (13, 16, 64)])
+def test_mod127_on_the_streaming_kernel(binding, gpu_util, oracle, M, N, K):
+    """Algorithm 1 as printed through the streaming kernel (Section VI-A-1 names m = 1 among its shapes):
+    clean, every bit of a C element, value changes that are multiples of 127 (missed by both sides), B faults
+    including operand values 127 and 254 at the faulty k, a fault in the 8-bit checksum entry."""
+    say(f"mod 127, streaming kernel: {M}x{N}x{K}")
+    A, B = operands(M, N, K, M + 3 * N + K, relu_like=(M % 2 == 0))
+    k0 = K // 2
+    A[0, k0] = 127
+    if M > 2:
+        A[1, k0], A[2, k0] = 254, 0
+    run = gpu_util.GpuRun(binding, B)
+    ws = binding.Workspace(M, run.Bp)
+    C0, f0, n0 = oracle.checked_gemm_mod127(A, B)
+    out = run.gemm(A, variant="smallm", mod127=True, ws=ws)
+    assert n0 == 0 and np.array_equal(out["C"], C0) and out["err_count"] == 0 and not out["flags"].any() and not out["ws"].any()
+    rng = np.random.default_rng(M * N)
+    for bit in range(32):
+        inj = [(int(rng.integers(M)), int(rng.integers(N)), 1 << bit)]
+        Cw, fw, nw = oracle.checked_gemm_mod127(A, B, flips_c=inj)
+        out = run.gemm(A, variant="smallm", mod127=True, injections=inj, ws=ws)
+        assert np.array_equal(out["C"], Cw) and np.array_equal(out["flags"], fw) and out["err_count"] == nw == 1
+    r, c = M - 1, N - 1
+    for delta in (127, 254 * 4096):
+        mask = int(np.uint32(C0[r, c]) ^ np.uint32(np.int64(C0[r, c]) + delta))
+        Cw, fw, nw = oracle.checked_gemm_mod127(A, B, flips_c=[(r, c, mask)])
+        out = run.gemm(A, variant="smallm", mod127=True, injections=[(r, c, mask)], ws=ws)
+        assert nw == 0 and out["err_count"] == 0 and np.array_equal(out["C"], Cw)
+    for (k, j, bit) in [(k0, 0, 0), (k0, N - 1, 7), (0, N // 2, 3), (K - 1, N - 1, 6)]:
+        Cw, fw, nw = oracle.checked_gemm_mod127(A, B, flips_b=[(k, j, bit)])
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        out = run.gemm(A, variant="smallm", mod127=True, ws=ws)
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        assert np.array_equal(out["C"], Cw) and np.array_equal(out["flags"], fw) and out["err_count"] == nw
+    Cw, fw, nw = oracle.checked_gemm_mod127(A, B, flips_rowsum=[(k0, 5)])
+    binding.abft_packed_b_flip_checksum_bit_mod127(run.Bp, k0, 5)
+    out = run.gemm(A, variant="smallm", mod127=True, ws=ws)
+    binding.abft_packed_b_flip_checksum_bit_mod127(run.Bp, k0, 5)
+    assert np.array_equal(out["flags"], fw) and out["err_count"] == nw
+    out = run.gemm(A, variant="smallm", ws=ws)           # the exact check on the same workspace afterwards
+    assert out["err_count"] == 0 and not out["ws"].any()
