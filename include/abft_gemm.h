@@ -230,6 +230,21 @@ int abft_recompute_flagged_rows(const uint8_t* A, int64_t lda, int M, const abft
                                 int max_rows_per_pass, void* scratch, size_t scratch_bytes, void* stream,
                                 int* rows_before, int* rows_after);
 
+/* The same recovery without a round trip to the host: the number of flagged
+ * rows stays on the device and bounds the gather and scatter kernels there, so
+ * the call only enqueues work (six small launches around one checked GEMM of
+ * max_rows rows) and returns.  At most max_rows flagged rows are recomputed in
+ * the one pass (any others keep their flag; soft errors are rare, one row is the
+ * expected case, and max_rows <= 64 keeps the recomputation on the streaming
+ * kernel: one pass over the weight).
+ *   status   DEVICE int32 [2], may be NULL: [0] flagged rows found, [1] rows still
+ *            flagged afterwards (also written to *err_count when that is given).
+ *   scratch  abft_recover_scratch_bytes(M, max_rows, Bp) bytes. */
+int abft_recompute_flagged_rows_async(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp,
+                                      int32_t* C, int64_t ldc, int32_t* row_flags, int32_t* err_count,
+                                      const abft_requant_t* rq, uint8_t* Cq, int64_t ldcq, int max_rows,
+                                      void* scratch, size_t scratch_bytes, int32_t* status, void* stream);
+
 /* Locating and correcting one faulty element of C_temp (Section IV: the column
  * check of Eq. 2a next to the row check of Eq. 2b, and the two correction
  * formulas that follow them).  The product itself stays with detection and an

@@ -27,6 +27,7 @@ EXPORTS = (
     "abft_gemm_workspace_bytes", "abft_workspace_init", "abft_gemm_u8s8s32_checked", "abft_gemm_u8s8s32_checked_static",
     "abft_requantize_u8",
     "abft_verify_rows", "abft_row_checksum", "abft_recover_scratch_bytes", "abft_recompute_flagged_rows",
+    "abft_recompute_flagged_rows_async",
     "abft_locate_scratch_bytes", "abft_locate_correct", "abft_calib_copy", "abft_last_error",
 )
 ABFT_LOCATE_CLEAN, ABFT_LOCATE_CORRECTED, ABFT_LOCATE_NOT_ONE_ELEMENT = 0, 1, 2
@@ -86,6 +87,8 @@ def _load() -> ctypes.CDLL:
     L.abft_recover_scratch_bytes.restype = sz
     L.abft_recompute_flagged_rows.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64,
                                               i32, vp, sz, vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.abft_recompute_flagged_rows_async.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64,
+                                                    i32, vp, sz, vp, vp]
     L.abft_locate_scratch_bytes.argtypes = [vp]
     L.abft_locate_scratch_bytes.restype = sz
     L.abft_locate_correct.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64, vp, vp, vp, sz, vp]
@@ -296,6 +299,24 @@ def abft_recompute_flagged_rows(A, Bp: PackedB, C, row_flags, err_count=None, rq
         ctypes.byref(rq) if rq is not None else None, _ptr(Cq, torch.uint8, "Cq"), _ld(Cq, "Cq") if Cq is not None else 0,
         max_rows_per_pass, scratch.data_ptr(), scratch.numel(), _stream(stream), ctypes.byref(before), ctypes.byref(after)))
     return before.value, after.value
+
+
+def abft_recompute_flagged_rows_async(A, Bp: PackedB, C, row_flags, err_count=None, rq=None, Cq=None, max_rows=64,
+                                      scratch=None, status=None, stream=None):
+    """Recomputes up to max_rows flagged rows in place without synchronising; returns the device tensor
+    `status` (rows found flagged, rows still flagged)."""
+    M = A.shape[0]
+    if scratch is None:
+        scratch = torch.empty(abft_recover_scratch_bytes(M, max_rows, Bp), dtype=torch.uint8, device=A.device)
+    if status is None:
+        status = torch.empty(2, dtype=torch.int32, device=A.device)
+    _check(lib.abft_recompute_flagged_rows_async(
+        _ptr(A, torch.uint8, "A"), _ld(A, "A"), M, Bp.handle,
+        _ptr(C, torch.int32, "C"), _ld(C, "C") if C is not None else 0,
+        _ptr(row_flags, torch.int32, "row_flags"), _ptr(err_count, torch.int32, "err_count"),
+        ctypes.byref(rq) if rq is not None else None, _ptr(Cq, torch.uint8, "Cq"), _ld(Cq, "Cq") if Cq is not None else 0,
+        max_rows, scratch.data_ptr(), scratch.numel(), _ptr(status, torch.int32, "status"), _stream(stream)))
+    return status
 
 
 def abft_locate_scratch_bytes(Bp: PackedB) -> int:

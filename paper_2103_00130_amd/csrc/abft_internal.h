@@ -170,6 +170,13 @@ hipError_t launch_gather_rows(const uint8_t* A, int64_t lda, const int32_t* idx,
 hipError_t launch_scatter_rows(const int32_t* C2, const uint8_t* Cq2, const int32_t* flags2, const int32_t* idx, int n,
                                int N, int32_t* C, int64_t ldc, uint8_t* Cq, int64_t ldcq, int32_t* flags, hipStream_t s);
 hipError_t launch_add_int(int32_t* dst, const int32_t* src, hipStream_t s);
+hipError_t launch_gather_rows_bounded(const uint8_t* A, int64_t lda, const int32_t* idx, const int32_t* count, int limit, int K,
+                                      uint8_t* A2, int64_t lda2, hipStream_t s);
+hipError_t launch_scatter_rows_bounded(const int32_t* C2, const uint8_t* Cq2, const int32_t* flags2, const int32_t* idx,
+                                       const int32_t* count, int limit, int N, int32_t* C, int64_t ldc, uint8_t* Cq, int64_t ldcq,
+                                       int32_t* flags, hipStream_t s);
+hipError_t launch_recount(const int32_t* count, const int32_t* cnt2, int limit, int32_t* err_count, int32_t* status,
+                          hipStream_t s);
 hipError_t launch_locate_correct(const uint8_t* A, int64_t lda, int M, const abft_packed_b* h, int32_t* C, int64_t ldc,
                                  int32_t* row_flags, int32_t* err_count, const RequantDev* rq, uint8_t* Cq, int64_t ldcq,
                                  int32_t* col_flags, int32_t* report, int32_t* scratch, hipStream_t s);

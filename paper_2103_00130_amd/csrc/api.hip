@@ -426,6 +426,38 @@ int abft_recompute_flagged_rows(const uint8_t* A, int64_t lda, int M, const abft
     return ABFT_OK;
 }
 
+int abft_recompute_flagged_rows_async(const uint8_t* A, int64_t lda, int M, const abft_packed_b* Bp, int32_t* C, int64_t ldc,
+                                      int32_t* row_flags, int32_t* err_count, const abft_requant_t* rq, uint8_t* Cq,
+                                      int64_t ldcq, int max_rows, void* scratch, size_t scratch_bytes, int32_t* status,
+                                      void* stream) {
+    const char* fn = "abft_recompute_flagged_rows_async";
+    if (!A || !Bp || !row_flags || !scratch) return fail(ABFT_EINVAL, "%s: null pointer", fn);
+    if (M < 1 || max_rows < 1 || lda < Bp->K) return fail(ABFT_EINVAL, "%s: bad shape", fn);
+    if (!C && !rq) return fail(ABFT_EINVAL, "%s: C is NULL and no requantization was asked for", fn);
+    if ((C && ldc < Bp->N) || (rq && (!Cq || ldcq < Bp->N))) return fail(ABFT_EINVAL, "%s: bad output", fn);
+    const RecoverLayout L = recover_layout(M, max_rows, Bp);
+    if (scratch_bytes < L.total) return fail(ABFT_EINVAL, "%s: scratch of %zu bytes, %zu needed", fn, scratch_bytes, L.total);
+    hipStream_t s = (hipStream_t)stream;
+    uint8_t* const base = (uint8_t*)scratch;
+    int32_t* const idx = (int32_t*)(base + L.idx);
+    int32_t* const count = (int32_t*)(base + L.count);
+    int32_t* const cnt2 = (int32_t*)(base + L.cnt2);
+    int32_t* const flags2 = (int32_t*)(base + L.flags2);
+    uint8_t* const A2 = base + L.a2;
+    int32_t* const C2 = (int32_t*)(base + L.c2);
+    uint8_t* const Q2 = base + L.q2;
+    HIP_TRY(abft::launch_list_flagged(row_flags, M, idx, count, s));
+    HIP_TRY(abft::launch_gather_rows_bounded(A, lda, idx, count, max_rows, Bp->K, A2, L.lda2, s));
+    HIP_TRY(abft::launch_fill_zero((int32_t*)(base + L.ws), L.ws_bytes / 4, s));
+    const int rc = abft_gemm_u8s8s32_checked(A2, L.lda2, max_rows, Bp, C ? C2 : nullptr, Bp->N, flags2, cnt2, rq, rq ? Q2 : nullptr,
+                                             Bp->N, nullptr, 0, ABFT_CHECK, base + L.ws, L.ws_bytes, stream);
+    if (rc != ABFT_OK) return rc;
+    HIP_TRY(abft::launch_scatter_rows_bounded(C ? C2 : nullptr, rq ? Q2 : nullptr, flags2, idx, count, max_rows, Bp->N, C, ldc,
+                                              rq ? Cq : nullptr, ldcq, row_flags, s));
+    HIP_TRY(abft::launch_recount(count, cnt2, max_rows, err_count, status, s));
+    return ABFT_OK;
+}
+
 size_t abft_locate_scratch_bytes(const abft_packed_b* Bp) {
     if (!Bp) return 0;
     return ((size_t)Bp->KB * abft::kUnitK + 2 * (size_t)Bp->NT * abft::kTileN) * sizeof(int32_t);

@@ -17,37 +17,44 @@
 namespace abft {
 namespace {
 
-// S_A[k] += sum of A[i][k] over this block's rows.  Thread t of block (bx, by) owns the 16 columns
-// k0 = (bx * 256 + t) * 16 .. +15 and walks the rows by*ROWS .. ; A rows are read 16 bytes per lane when
-// the caller's A allows it (base and lda multiples of 16), byte by byte otherwise.
-constexpr int kColsumRows = 64;
+// S_A[k] += sum of A[i][k] over this block's rows.  A block owns 256 columns and kColsumRows rows: thread
+// (kc, rl) walks the rows rl, rl + 16, ... of the block with the 16 columns of chunk kc (one 16-byte load when
+// the caller's A allows it - base and lda multiples of 16 - byte by byte otherwise), the sixteen row lanes
+// meet in LDS, and one atomic per column and block adds the block's sum.
+constexpr int kColsumRows = 256;
 __global__ __launch_bounds__(256) void a_colsum_kernel(const uint8_t* __restrict__ A, int64_t lda, int M, int K, int vec_ok,
                                                        int32_t* __restrict__ S_A) {
-    const int k0 = (blockIdx.x * 256 + threadIdx.x) * 16;
-    if (k0 >= K) return;
+    __shared__ uint32_t part[16][257];
+    const int kc = threadIdx.x & 15, rl = threadIdx.x >> 4;
+    const int k0 = blockIdx.x * 256 + kc * 16;
     uint32_t s[16];
 #pragma unroll
     for (int b = 0; b < 16; ++b) s[b] = 0;
-    // (row chunks in strides of the grid's second dimension, which the hardware caps at 65535)
+    // (row blocks in strides of the grid's second dimension, which the hardware caps at 65535)
     for (int64_t r0 = (int64_t)blockIdx.y * kColsumRows; r0 < M; r0 += (int64_t)gridDim.y * kColsumRows) {
-    const int r1 = (int)min(r0 + kColsumRows, (int64_t)M);
-    if (vec_ok && k0 + 16 <= K) {
-        for (int r = (int)r0; r < r1; ++r) {
-            const uint4 v = *reinterpret_cast<const uint4*>(A + (int64_t)r * lda + k0);
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        const int r1 = (int)min(r0 + kColsumRows, (int64_t)M);
+        if (vec_ok && k0 + 16 <= K) {
+            for (int r = (int)r0 + rl; r < r1; r += 16) {
+                const uint4 v = *reinterpret_cast<const uint4*>(A + (int64_t)r * lda + k0);
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int b = 0; b < 16; ++b) s[b] += (w[b >> 2] >> (8 * (b & 3))) & 0xFFu;
+                for (int b = 0; b < 16; ++b) s[b] += (w[b >> 2] >> (8 * (b & 3))) & 0xFFu;
+            }
+        } else {
+            for (int r = (int)r0 + rl; r < r1; r += 16)
+#pragma unroll
+                for (int b = 0; b < 16; ++b)
+                    if (k0 + b < K) s[b] += A[(int64_t)r * lda + k0 + b];
         }
-    } else {
-        for (int r = (int)r0; r < r1; ++r)
-#pragma unroll
-            for (int b = 0; b < 16; ++b)
-                if (k0 + b < K) s[b] += A[(int64_t)r * lda + k0 + b];
-    }
     }
 #pragma unroll
-    for (int b = 0; b < 16; ++b)
-        if (k0 + b < K && s[b] != 0) atomicAdd(&S_A[k0 + b], (int32_t)s[b]);
+    for (int b = 0; b < 16; ++b) part[rl][kc * 16 + b] = s[b];
+    __syncthreads();
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    uint32_t t = 0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) t += part[q][threadIdx.x];
+    if (k < K && t != 0) atomicAdd(&S_A[k], (int32_t)t);
 }
 
 // col_chk[j] += sum over this block's k-blocks of S_A[k] * B[k][j], straight from the packed weight.
@@ -63,9 +70,14 @@ __global__ __launch_bounds__(256) void col_checksum_kernel(const int8_t* __restr
     for (int kb = blockIdx.y * 2 + h; kb < KB; kb += gridDim.y * 2) {
         const int4 v = *reinterpret_cast<const int4*>(packed + packed_unit_offset(ntile, kb, unit, KB) + (kg * kUnitN + c) * 16);
         const int32_t w[4] = {v.x, v.y, v.z, v.w};
-        const int32_t* sa = S_A + kb * kUnitK + kg * 16;
+        const int4* sa4 = reinterpret_cast<const int4*>(S_A + kb * kUnitK + kg * 16);
 #pragma unroll
-        for (int b = 0; b < 16; ++b) s += (uint32_t)sa[b] * (uint32_t)(int32_t)(int8_t)(w[b >> 2] >> (8 * (b & 3)));
+        for (int q = 0; q < 4; ++q) {
+            const int4 a = sa4[q];
+            const int32_t sa[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+            for (int b = 0; b < 4; ++b) s += (uint32_t)sa[b] * (uint32_t)(int32_t)(int8_t)(w[q] >> (8 * b));
+        }
     }
     part[threadIdx.x >> 5][c] = s;
     __syncthreads();
@@ -181,7 +193,7 @@ hipError_t launch_locate_correct(const uint8_t* A, int64_t lda, int M, const abf
     hipError_t e = launch_fill_zero(scratch, (size_t)Kpad + 2 * (size_t)Npad, s);
     if (e != hipSuccess) return e;
     const int vec_ok = (((uintptr_t)A | (uintptr_t)lda) & 15) == 0;
-    a_colsum_kernel<<<dim3((unsigned)((K + 4095) / 4096), (unsigned)min((M + kColsumRows - 1) / kColsumRows, 65535)), dim3(256), 0, s>>>(
+    a_colsum_kernel<<<dim3((unsigned)((K + 255) / 256), (unsigned)min((M + kColsumRows - 1) / kColsumRows, 65535)), dim3(256), 0, s>>>(
         A, lda, M, K, vec_ok, S_A);
     c_colsum_kernel<<<dim3((unsigned)((N + 255) / 256), (unsigned)min((M + kColsumCRows - 1) / kColsumCRows, 65535)), dim3(256), 0, s>>>(
         C, ldc, M, N, csum);

@@ -91,6 +91,42 @@ __global__ void scatter_rows_kernel(const int32_t* __restrict__ C2, const uint8_
 
 __global__ void add_int_kernel(int32_t* dst, const int32_t* src) { *dst += *src; }
 
+// The same helpers with the number of listed rows read on the device (nothing goes back to the host):
+// block b of a grid of `limit` blocks handles listed row b if there is one, and otherwise clears its row of
+// the gathered operand (so that the product over all `limit` rows is defined and its spare rows pass).
+__global__ void gather_rows_bounded_kernel(const uint8_t* __restrict__ A, int64_t lda, const int32_t* __restrict__ idx,
+                                           const int32_t* __restrict__ count, int K, uint8_t* __restrict__ A2, int64_t lda2) {
+    const bool live = (int)blockIdx.x < *count;
+    const uint8_t* src = A + (int64_t)(live ? idx[blockIdx.x] : 0) * lda;
+    uint8_t* dst = A2 + (int64_t)blockIdx.x * lda2;
+    for (int k = threadIdx.x; k < (int)lda2; k += blockDim.x) dst[k] = (live && k < K) ? src[k] : (uint8_t)0;
+}
+
+__global__ void scatter_rows_bounded_kernel(const int32_t* __restrict__ C2, const uint8_t* __restrict__ Cq2,
+                                            const int32_t* __restrict__ flags2, const int32_t* __restrict__ idx,
+                                            const int32_t* __restrict__ count, int N, int32_t* __restrict__ C, int64_t ldc,
+                                            uint8_t* __restrict__ Cq, int64_t ldcq, int32_t* __restrict__ flags) {
+    if ((int)blockIdx.x >= *count) return;
+    const int r = idx[blockIdx.x];
+    for (int j = threadIdx.x; j < N; j += blockDim.x) {
+        if (C) C[(int64_t)r * ldc + j] = C2[(int64_t)blockIdx.x * N + j];
+        if (Cq) Cq[(int64_t)r * ldcq + j] = Cq2[(int64_t)blockIdx.x * N + j];
+    }
+    if (threadIdx.x == 0) flags[r] = flags2[blockIdx.x];
+}
+
+// status[0] = rows found flagged, status[1] = rows still flagged: those recomputed and flagged again
+// (cnt2 counts them: spare rows are all-zero and pass) plus those beyond the limit, which were not touched
+__global__ void recount_kernel(const int32_t* __restrict__ count, const int32_t* __restrict__ cnt2, int limit,
+                               int32_t* __restrict__ err_count, int32_t* __restrict__ status) {
+    const int found = *count, left = (found > limit ? found - limit : 0) + *cnt2;
+    if (err_count) *err_count = left;
+    if (status) {
+        status[0] = found;
+        status[1] = left;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_list_flagged(const int32_t* flags, int M, int32_t* idx, int32_t* count, hipStream_t s) {
@@ -114,6 +150,25 @@ hipError_t launch_scatter_rows(const int32_t* C2, const uint8_t* Cq2, const int3
 
 hipError_t launch_add_int(int32_t* dst, const int32_t* src, hipStream_t s) {
     add_int_kernel<<<dim3(1), dim3(1), 0, s>>>(dst, src);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows_bounded(const uint8_t* A, int64_t lda, const int32_t* idx, const int32_t* count, int limit, int K,
+                                      uint8_t* A2, int64_t lda2, hipStream_t s) {
+    gather_rows_bounded_kernel<<<dim3((unsigned)limit), dim3(256), 0, s>>>(A, lda, idx, count, K, A2, lda2);
+    return hipGetLastError();
+}
+
+hipError_t launch_scatter_rows_bounded(const int32_t* C2, const uint8_t* Cq2, const int32_t* flags2, const int32_t* idx,
+                                       const int32_t* count, int limit, int N, int32_t* C, int64_t ldc, uint8_t* Cq, int64_t ldcq,
+                                       int32_t* flags, hipStream_t s) {
+    scatter_rows_bounded_kernel<<<dim3((unsigned)limit), dim3(256), 0, s>>>(C2, Cq2, flags2, idx, count, N, C, ldc, Cq, ldcq, flags);
+    return hipGetLastError();
+}
+
+hipError_t launch_recount(const int32_t* count, const int32_t* cnt2, int limit, int32_t* err_count, int32_t* status,
+                          hipStream_t s) {
+    recount_kernel<<<dim3(1), dim3(1), 0, s>>>(count, cnt2, limit, err_count, status);
     return hipGetLastError();
 }
 

@@ -834,3 +834,65 @@ def test_mod127_on_the_streaming_kernel(binding, gpu_util, oracle, M, N, K):
     assert np.array_equal(out["flags"], fw) and out["err_count"] == nw
     out = run.gemm(A, variant="smallm", ws=ws)           # the exact check on the same workspace afterwards
     assert out["err_count"] == 0 and not out["ws"].any()
+
+
+@pytest.mark.gpu
+def test_recompute_flagged_rows_without_a_host_round_trip(binding, gpu_util, oracle):
+    """abft_recompute_flagged_rows_async: the count of flagged rows stays on the device.  Transient faults are
+    recovered bit for bit; more flagged rows than the pass holds leave the rest flagged; a fault that sits in
+    the weight stays flagged."""
+    import torch
+    b = binding
+    M, N, K = 300, 520, 384
+    say(f"recovery without synchronisation {M}x{N}x{K}")
+    A, B = operands(M, N, K, 47)
+    clean = oracle.checked_gemm(A, B)
+    run = gpu_util.GpuRun(b, B)
+    A_dev = gpu_util.dev(A)
+    mult_np = wlmod.draw_mult(np.random.default_rng(4), N, "channel")
+    mult = gpu_util.dev(mult_np)
+    rq = b.make_requant(128, 128, mult)
+    want_q = oracle.requantize(clean.C, clean.colsum, 128, 128, mult_np, precision="f32")
+    C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    Cq = torch.empty((M, N), dtype=torch.uint8, device="cuda")
+    flags = torch.empty(M, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+    ws = b.Workspace(M, run.Bp)
+    inj = [(0, 0, 1 << 31), (17, 300, 1 << 3), (128, 519, 0x00FF0000), (255, 256, 1), (299, 1, 1 << 20)]
+    for max_rows in (64, 5, 16):
+        b.abft_gemm_u8s8s32_checked(A_dev, run.Bp, C, flags, cnt, rq=rq, Cq=Cq, inj=b.make_injections(inj), n_inj=len(inj),
+                                    workspace=ws.tensor)
+        status = b.abft_recompute_flagged_rows_async(A_dev, run.Bp, C, flags, cnt, rq=rq, Cq=Cq, max_rows=max_rows)
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [5, 0] and int(cnt.item()) == 0 and not flags.any().item()
+        assert np.array_equal(C.cpu().numpy(), clean.C) and np.array_equal(Cq.cpu().numpy(), want_q)
+    # nothing flagged: nothing changes
+    status = b.abft_recompute_flagged_rows_async(A_dev, run.Bp, C, flags, cnt, rq=rq, Cq=Cq)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0] and np.array_equal(C.cpu().numpy(), clean.C)
+    # a pass of three rows against five flagged ones: three are recovered, two keep their flag
+    b.abft_gemm_u8s8s32_checked(A_dev, run.Bp, C, flags, cnt, rq=rq, Cq=Cq, inj=b.make_injections(inj), n_inj=len(inj),
+                                workspace=ws.tensor)
+    status = b.abft_recompute_flagged_rows_async(A_dev, run.Bp, C, flags, cnt, rq=rq, Cq=Cq, max_rows=3)
+    torch.cuda.synchronize()
+    f = flags.cpu().numpy()
+    assert status.cpu().tolist() == [5, 2] and int(cnt.item()) == 2 and int(f.sum()) == 2
+    Cn = C.cpu().numpy()
+    for r in (0, 17, 128, 255, 299):
+        assert np.array_equal(Cn[r], clean.C[r]) == (f[r] == 0)
+    status = b.abft_recompute_flagged_rows_async(A_dev, run.Bp, C, flags, cnt, rq=rq, Cq=Cq, max_rows=3)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [2, 0] and np.array_equal(C.cpu().numpy(), clean.C) and np.array_equal(Cq.cpu().numpy(), want_q)
+    # a fault in the weight persists through the recomputation
+    A1 = A.copy()
+    A1[:, 100] = 0
+    A1[[5, 9], 100] = 3
+    A1_dev = gpu_util.dev(A1)
+    bad = oracle.checked_gemm(A1, B, flips_b=[(100, 200, 6)])
+    b.abft_packed_b_flip_bit(run.Bp, 100, 200, 6)
+    b.abft_gemm_u8s8s32_checked(A1_dev, run.Bp, C, flags, cnt, workspace=ws.tensor)
+    status = b.abft_recompute_flagged_rows_async(A1_dev, run.Bp, C, flags, cnt)
+    torch.cuda.synchronize()
+    assert bad.err_count == 2 and status.cpu().tolist() == [2, 2] and int(cnt.item()) == 2
+    assert np.array_equal(flags.cpu().numpy(), bad.flags) and np.array_equal(C.cpu().numpy(), bad.C)
+    b.abft_packed_b_flip_bit(run.Bp, 100, 200, 6)
