@@ -283,6 +283,84 @@ def smallm_sweep(b, torch, steps, warmup, count_flag=0, M=16,
     return out
 
 
+def clock_trace(b, torch, args):
+    """Shader clock evidence for the matrix-core roofline (needs the diagnostic library:
+    `python -m paper_2103_00130_amd.build --clock-trace`, then ABFT_LIBRARY=<.../libabftgemm_clocktrace.so>).
+    Three measurements, each from cycle counter / 100 MHz wall counter pairs taken on the device:
+    the idle clock, a register-only MFMA load (no operand traffic), and the phases of the tiled GEMM itself."""
+    import statistics
+    out = {}
+    probe = torch.zeros(4, dtype=torch.int64, device="cuda")
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    b.abft_clock_probe(probe, 2000)
+    torch.cuda.synchronize()
+    o = probe.cpu().tolist()
+    out["idle_clock_ghz"] = (o[3] - o[1]) / ((o[2] - o[0]) / 100.0) / 1e3
+    peak = torch.zeros(4 * 256, dtype=torch.int64, device="cuda")
+    iters = 40000
+    for _ in range(3):
+        b.abft_mfma_peak_probe(peak, iters)
+    torch.cuda.synchronize()
+    pk = peak.cpu().view(256, 4).tolist()
+    us = statistics.median((r1 - r0) / 100.0 for c0, r0, c1, r1 in pk)
+    out["register_only_mfma"] = {
+        "clock_ghz": statistics.median((c1 - c0) / ((r1 - r0) / 100.0) / 1e3 for c0, r0, c1, r1 in pk),
+        "cycles_per_mfma": statistics.median((c1 - c0) / (4.0 * iters) for c0, r0, c1, r1 in pk),
+        "pops": 256 * 4 * iters * 4 * 65536.0 / us / 1e9, "us": us,
+        "note": "256 workgroups x 4 wavefronts x %d rounds of 4 independent 32x32x32 int8 MFMAs, operands in registers" % iters}
+    job = Job(b, torch, args.workload, accumulate=not args.overwrite_count)
+    wl = job.wl
+    n_wg = ((wl.M + 63) // 64) * ((wl.N + 63) // 64)
+    trace = torch.zeros(6 * n_wg, dtype=torch.int64, device="cuda")
+    for check in (True, False):
+        b.abft_clock_trace(None)
+        for _ in range(args.warmup):
+            job.step(check)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(200):
+                job.step(check)
+        trace.zero_()
+        torch.cuda.synchronize()
+        b.abft_clock_trace(trace)
+        # the trace pointer travels in the kernel arguments, which the graph captured without it: the traced
+        # launches are plain launches at the end of a warm run of graph replays
+        g.replay()
+        g.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(side):
+            b.abft_clock_probe(probe, 5000, stream=side)
+        e0.record()
+        for _ in range(50):
+            job.step(check)
+        e1.record()
+        g.replay()
+        torch.cuda.synchronize()
+        b.abft_clock_trace(None)
+        o = probe.cpu().tolist()
+        rows = [r for r in trace.cpu().view(n_wg, 6).tolist() if r[1] != 0 and r[5] != 0]
+        stages = (wl.K + 127) // 128
+        loop_cyc = [r[2] - r[0] for r in rows]
+        loop_us = [(r[3] - r[1]) / 100.0 for r in rows]
+        epi_cyc = [r[4] - r[2] for r in rows]
+        epi_us = [(r[5] - r[3]) / 100.0 for r in rows]
+        out["checked" if check else "unchecked"] = {
+            "workgroups_traced": len(rows), "us_per_launch_traced": e0.elapsed_time(e1) * 1e3 / 50,
+            "k_loop_us": statistics.median(loop_us), "k_loop_cycles_per_stage": statistics.median(loop_cyc) / stages,
+            "k_loop_clock_ghz": statistics.median(c / u / 1e3 for c, u in zip(loop_cyc, loop_us) if u > 0),
+            "epilogue_us": statistics.median(epi_us),
+            "epilogue_clock_ghz": statistics.median(c / u / 1e3 for c, u in zip(epi_cyc, epi_us) if u > 0),
+            "concurrent_probe_clock_ghz": (o[3] - o[1]) / max((o[2] - o[0]) / 100.0, 1e-9) / 1e3,
+            "k_loop_pops": 2.0 * wl.M * wl.N * wl.K / statistics.median(loop_us) / 1e9,
+            "mfma_cycles_per_stage_at_full_rate": 2048 if max(wl.M, wl.N) >= 2048 else None}
+    out["workload"] = wl.name
+    out["note"] = ("clock = shader cycles / wall time between two samples on the device; the peak of 5.0 POP/s is quoted at 2.4 GHz, "
+                   "so the matrix-core ceiling at a sustained clock f is 5.0 * f / 2.4")
+    return out
+
+
 CALIB_COPY_BYTES = 256 << 20
 GEMM_KERNEL_TAGS = ("gemm_tile_async_kernel", "gemm_tile_kernel", "gemm_smallm_kernel")
 
@@ -505,6 +583,8 @@ def main():
                     "comparison modulo 127) instead of the exact int32 checksum; tiled kernels only")
     ap.add_argument("--overwrite-count", action="store_true", help="errCount overwritten by every launch (the library's default) "
                     "instead of a counter that the launches add to (ABFT_ERRCOUNT_ACCUMULATE, what this benchmark times by default)")
+    ap.add_argument("--clock-trace", action="store_true", help="print only the shader-clock evidence (idle, register-only MFMA load, "
+                    "phases of the tiled GEMM); needs ABFT_LIBRARY to point at the library built with `build --clock-trace`")
     ap.add_argument("--pmc-child", action="store_true", help=argparse.SUPPRESS)
     ap.add_argument("--pmc-child-eb", type=str, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--no-eb", action="store_true", help="skip the EmbeddingBag entries (reported under 'eb')")
@@ -519,6 +599,12 @@ def main():
         return
     if args.pmc_child_eb:
         pmc_child_eb(args.pmc_child_eb)
+        return
+    if args.clock_trace:
+        import torch
+        from paper_2103_00130_amd import binding as b
+        torch.cuda.set_device(0)
+        print(json.dumps({"clock_trace": clock_trace(b, torch, args)}))
         return
     if args.eb_only:
         import torch

@@ -295,6 +295,34 @@ int abft_locate_correct(const uint8_t* A, int64_t lda, int M, const abft_packed_
  * by when the GEMM kernels' traffic is reported. */
 int abft_calib_copy(const void* src, void* dst, size_t bytes, void* stream);
 
+/* Measurement aid, not part of the method: one lane samples the shader-clock
+ * cycle counter and the constant 100 MHz wall counter, waits `microseconds`
+ * (1..100000) of wall time, and samples both again.  out (DEVICE, 4 x uint64):
+ * wall ticks and shader cycles at the start, wall ticks and shader cycles at
+ * the end; (cycles end - start) / (ticks end - start) x 100 MHz is the shader
+ * clock in that interval.  Enqueued on a stream of its own next to a run of
+ * GEMM launches it shows the clock the chip sustains under that load, which is
+ * what the matrix-core roofline has to be read against. */
+int abft_clock_probe(uint64_t* out, int microseconds, void* stream);
+
+/* Measurement aid: a register-only matrix-core load.  256 workgroups of four
+ * wavefronts run `iters` rounds of four independent 32x32x32 int8 MFMAs on
+ * operands that stay in registers; out (DEVICE, 4 x uint64 per workgroup, 256
+ * workgroups): shader cycles and 100 MHz wall ticks before and after the loop.
+ * 256 x 4 x iters x 4 x 65536 operations over the wall time is what the matrix
+ * cores deliver, and cycles over wall time the clock they hold, when neither
+ * LDS nor memory draws power: the reference the GEMM's in-loop figures are read
+ * against. */
+int abft_mfma_peak_probe(uint64_t* out, int iters, void* stream);
+
+/* Diagnostic builds only (the library compiled with ABFT_CLOCK_TRACE, see
+ * build.py --clock-trace; ABFT_EUNSUPPORTED otherwise): from now on every
+ * direct-to-LDS tiled launch writes, per workgroup, 6 x uint64 to buf (DEVICE,
+ * sized for the largest grid the caller launches; NULL switches it off):
+ * shader cycles and 100 MHz wall ticks before the K loop, after it, and at the
+ * end of the kernel.  Process-wide; the product library carries no such code. */
+int abft_clock_trace(uint64_t* buf);
+
 /* Message for the last non-OK return on this host thread. */
 const char* abft_last_error(void);
 

@@ -13,7 +13,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libabftgemm.so")
+# ABFT_LIBRARY: path of another build of the same library (the diagnostic build with in-kernel clock traces)
+LIB_PATH = os.environ.get("ABFT_LIBRARY") or os.path.join(_HERE, "libabftgemm.so")
 
 ABFT_OK, ABFT_EINVAL, ABFT_EUNSUPPORTED, ABFT_EHIP = 0, -1, -2, -3
 ABFT_CHECK, ABFT_NOCHECK, ABFT_MOD127, ABFT_ERRCOUNT_ACCUMULATE = 0, 1, 2, 4
@@ -28,7 +29,7 @@ EXPORTS = (
     "abft_requantize_u8",
     "abft_verify_rows", "abft_row_checksum", "abft_recover_scratch_bytes", "abft_recompute_flagged_rows",
     "abft_recompute_flagged_rows_async",
-    "abft_locate_scratch_bytes", "abft_locate_correct", "abft_calib_copy", "abft_last_error",
+    "abft_locate_scratch_bytes", "abft_locate_correct", "abft_calib_copy", "abft_clock_probe", "abft_mfma_peak_probe", "abft_clock_trace", "abft_last_error",
 )
 ABFT_LOCATE_CLEAN, ABFT_LOCATE_CORRECTED, ABFT_LOCATE_NOT_ONE_ELEMENT = 0, 1, 2
 EXPORTS_EB = (
@@ -83,6 +84,9 @@ def _load() -> ctypes.CDLL:
     L.abft_verify_rows.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
     L.abft_row_checksum.argtypes = [vp, i64, i32, vp, vp, vp]
     L.abft_calib_copy.argtypes = [vp, vp, sz, vp]
+    L.abft_clock_probe.argtypes = [vp, i32, vp]
+    L.abft_mfma_peak_probe.argtypes = [vp, i32, vp]
+    L.abft_clock_trace.argtypes = [vp]
     L.abft_recover_scratch_bytes.argtypes = [i32, i32, vp]
     L.abft_recover_scratch_bytes.restype = sz
     L.abft_recompute_flagged_rows.argtypes = [vp, i64, i32, vp, vp, i64, vp, vp, ctypes.POINTER(abft_requant_t), vp, i64,
@@ -349,6 +353,25 @@ def abft_calib_copy(src, dst, stream=None):
     if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
         raise ValueError("abft_calib_copy: contiguous device tensors expected")
     _check(lib.abft_calib_copy(src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size(), _stream(stream)))
+
+
+def abft_clock_probe(out: torch.Tensor, microseconds: int, stream=None):
+    """out: int64 device tensor of 4 (wall ticks at 100 MHz and shader cycles, start and end)."""
+    if out.dtype != torch.int64 or out.numel() < 4 or not out.is_cuda:
+        raise ValueError("abft_clock_probe: out must be an int64 device tensor of at least 4 entries")
+    _check(lib.abft_clock_probe(out.data_ptr(), int(microseconds), _stream(stream)))
+
+
+def abft_mfma_peak_probe(out: torch.Tensor, iters: int, stream=None):
+    """out: int64 device tensor of 4 * 256 (shader cycles, wall ticks before; the same after; per workgroup)."""
+    if out.dtype != torch.int64 or out.numel() < 4 * 256 or not out.is_cuda:
+        raise ValueError("abft_mfma_peak_probe: out must be an int64 device tensor of at least 1024 entries")
+    _check(lib.abft_mfma_peak_probe(out.data_ptr(), int(iters), _stream(stream)))
+
+
+def abft_clock_trace(buf: torch.Tensor | None):
+    """Diagnostic library only: buf int64 device tensor, 6 entries per workgroup of the largest grid; None = off."""
+    _check(lib.abft_clock_trace(None if buf is None else buf.data_ptr()))
 
 
 class Workspace:

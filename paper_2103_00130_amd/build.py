@@ -21,8 +21,16 @@ FLAGS = [
 ]
 
 
-def build_library(force: bool = True, verbose: bool = False) -> str:
-    build_dir = os.path.join(HERE, "_build")
+def build_library(force: bool = True, verbose: bool = False, clock_trace: bool = False) -> str:
+    """clock_trace: build libabftgemm_clocktrace.so instead, the same sources with ABFT_CLOCK_TRACE defined (tiled
+    kernels record cycle and wall counters per workgroup; load it through ABFT_LIBRARY, see bench.py --clock-trace)."""
+    if clock_trace:
+        return _build(force, verbose, os.path.join(HERE, "_build_clocktrace"), os.path.join(HERE, "libabftgemm_clocktrace.so"),
+                      ["-DABFT_CLOCK_TRACE"])
+    return _build(force, verbose, os.path.join(HERE, "_build"), LIB, [])
+
+
+def _build(force, verbose, build_dir, lib, extra) -> str:
     os.makedirs(build_dir, exist_ok=True)
     deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", h) for h in ("abft_gemm.h", "abft_eb.h")]
     newest = max(os.path.getmtime(d) for d in deps)
@@ -32,7 +40,7 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
         obj = os.path.join(build_dir, src.replace(".hip", ".o"))
         objs.append(obj)
         if force or not os.path.exists(obj) or os.path.getmtime(obj) < newest:
-            cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+            cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
             if verbose:
                 print(" ".join(cmd), flush=True)
             procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -47,9 +55,9 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
             print(f"---- {src} ----\n{out}")
     if failed:
         raise RuntimeError("hipcc failed")
-    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
-    return LIB
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], check=True)
+    return lib
 
 
 if __name__ == "__main__":
-    print(build_library(force="--force" in sys.argv, verbose=True))
+    print(build_library(force="--force" in sys.argv, verbose=True, clock_trace="--clock-trace" in sys.argv))

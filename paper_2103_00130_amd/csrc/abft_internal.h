@@ -101,6 +101,7 @@ struct GemmParams {
     RequantDev rq;
     const void* inj;           // abft_inject_t[n_inj]
     int n_inj;
+    unsigned long long* clock_trace;  // diagnostic builds (ABFT_CLOCK_TRACE): 6 words per workgroup, else NULL
     int32_t* ws;               // workspace: counting words in the first kWsHeaderInts ints, then the per-row words
 };
 
@@ -181,6 +182,8 @@ hipError_t launch_locate_correct(const uint8_t* A, int64_t lda, int M, const abf
                                  int32_t* row_flags, int32_t* err_count, const RequantDev* rq, uint8_t* Cq, int64_t ldcq,
                                  int32_t* col_flags, int32_t* report, int32_t* scratch, hipStream_t s);
 hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+hipError_t launch_clock_probe(unsigned long long* out, unsigned long long ticks, hipStream_t s);
+hipError_t launch_mfma_peak_probe(unsigned long long* out, int iters, hipStream_t s);
 hipError_t launch_row_checksum(const uint8_t* A, int64_t lda, int M, int K, const int32_t* S_B,
                                int32_t* row_chk, hipStream_t s);
 

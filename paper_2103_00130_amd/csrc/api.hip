@@ -12,6 +12,9 @@
 namespace {
 
 thread_local char g_err[512] = "";
+#ifdef ABFT_CLOCK_TRACE
+std::atomic<unsigned long long*> g_clock_trace{nullptr};  // set by abft_clock_trace, handed to every tiled launch
+#endif
 
 int fail(int code, const char* fmt, ...) {
     va_list ap;
@@ -224,6 +227,9 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
     p.n_inj = n_inj;
     p.ws = (int32_t*)workspace;
     p.err_accumulate = (flags & ABFT_ERRCOUNT_ACCUMULATE) != 0;
+#ifdef ABFT_CLOCK_TRACE
+    p.clock_trace = g_clock_trace.load(std::memory_order_acquire);
+#endif
     const bool mod127 = check && (flags & ABFT_MOD127) != 0;
     if (mod127) {
         // exact (unwrapped) 32-bit entries are what the congruence modulo 127 needs
@@ -491,6 +497,34 @@ int abft_calib_copy(const void* src, void* dst, size_t bytes, void* stream) {
         return fail(ABFT_EINVAL, "%s: bytes=%zu and both pointers must be multiples of 16", fn, bytes);
     HIP_TRY(abft::launch_calib_copy(src, dst, bytes, (hipStream_t)stream));
     return ABFT_OK;
+}
+
+int abft_clock_probe(uint64_t* out, int microseconds, void* stream) {
+    const char* fn = "abft_clock_probe";
+    if (!out || ((uintptr_t)out & 7)) return fail(ABFT_EINVAL, "%s: out must be an 8-byte aligned device pointer", fn);
+    if (microseconds < 1 || microseconds > 100000) return fail(ABFT_EINVAL, "%s: %d us outside [1, 100000]", fn, microseconds);
+    HIP_TRY(abft::launch_clock_probe(reinterpret_cast<unsigned long long*>(out), 100ull * (unsigned long long)microseconds,
+                                     (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+int abft_mfma_peak_probe(uint64_t* out, int iters, void* stream) {
+    const char* fn = "abft_mfma_peak_probe";
+    if (!out || ((uintptr_t)out & 7)) return fail(ABFT_EINVAL, "%s: out must be an 8-byte aligned device pointer", fn);
+    if (iters < 1 || iters > (1 << 22)) return fail(ABFT_EINVAL, "%s: iters=%d outside [1, 2^22]", fn, iters);
+    HIP_TRY(abft::launch_mfma_peak_probe(reinterpret_cast<unsigned long long*>(out), iters, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+int abft_clock_trace(uint64_t* buf) {
+#ifdef ABFT_CLOCK_TRACE
+    g_clock_trace.store(reinterpret_cast<unsigned long long*>(buf), std::memory_order_release);
+    return ABFT_OK;
+#else
+    (void)buf;
+    return fail(ABFT_EUNSUPPORTED, "abft_clock_trace: this library was built without ABFT_CLOCK_TRACE "
+                                   "(python -m paper_2103_00130_amd.build --clock-trace builds the diagnostic library)");
+#endif
 }
 
 }  // extern "C"

@@ -450,6 +450,12 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
     }
 
     asm volatile("" : "+s"(total_sb));  // (the value is in its register from here on)
+#ifdef ABFT_CLOCK_TRACE
+    // Diagnostic build only: the first thread of every workgroup samples the shader-clock cycle counter and the
+    // constant 100 MHz wall counter before the K loop, after it and at the end of the kernel (6 words per
+    // workgroup): cycles over wall time is the clock the chip sustained in each phase.
+    unsigned long long trace_c0 = clock64(), trace_r0 = wall_clock64();
+#endif
     int cur = 0;
     // A run of stages [s_begin, s_end) with or without the checksum-digit MFMAs (separate loops
     // keep every loop body one straight block).  PH says on which k-steps this wave adds the B
@@ -582,6 +588,15 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
     // (the last stage re-issued loads into a dead buffer; the epilogue keeps its scratch outside
     // the stage buffers, so nobody waits for them before the very end of the kernel)
 
+#ifdef ABFT_CLOCK_TRACE
+    if (p.clock_trace && threadIdx.x == 0) {
+        unsigned long long* const o = p.clock_trace + (size_t)blockIdx.x * 6;
+        o[0] = trace_c0;
+        o[1] = trace_r0;
+        o[2] = clock64();
+        o[3] = wall_clock64();
+    }
+#endif
     // ------------------------- K split: the groups' results come together -------------------------
     if constexpr (WGK > 1) {
         static_assert(TM * TN <= 4, "the K split is for small wave tiles");
@@ -870,6 +885,13 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
     }
     // direct-to-LDS loads that are still in flight must not outlive the workgroup's LDS
     wait_vmem();
+#ifdef ABFT_CLOCK_TRACE
+    if (p.clock_trace && threadIdx.x == 0) {
+        unsigned long long* const o = p.clock_trace + (size_t)blockIdx.x * 6;
+        o[4] = clock64();
+        o[5] = wall_clock64();
+    }
+#endif
 }
 
 template <int BM, int BN, int WGM, int WGN, int kStages, int WGK = 1>

@@ -63,6 +63,55 @@ __global__ void calib_copy_kernel(const uint4* __restrict__ src, uint4* __restri
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// One lane reads the shader-clock cycle counter and the constant-rate (100 MHz) wall counter, idles until the
+// wall counter has advanced by `ticks`, and reads both again: cycles over wall time is the shader clock the
+// chip ran at in between.  Launched on a second stream it measures the clock under whatever else is running.
+// The wall counter advances on its own, so the wait always ends.
+__global__ void clock_probe_kernel(unsigned long long* __restrict__ out, unsigned long long ticks) {
+    if (threadIdx.x != 0) return;
+    const unsigned long long r0 = wall_clock64(), c0 = clock64();
+    while (wall_clock64() - r0 < ticks) __builtin_amdgcn_s_sleep(16);
+    const unsigned long long r1 = wall_clock64(), c1 = clock64();
+    out[0] = r0;
+    out[1] = c0;
+    out[2] = r1;
+    out[3] = c1;
+}
+
+// Register-only matrix-core load: every wavefront runs `iters` rounds of four independent 32x32x32 int8 MFMAs on
+// operands that never leave its registers (no LDS, no memory).  The first thread of every workgroup records the
+// shader-clock cycle counter and the 100 MHz wall counter around the loop: what the matrix cores deliver, and
+// at which clock, when nothing but they draws power.  Four wavefronts per workgroup, one per SIMD.
+typedef int probe_v4i __attribute__((ext_vector_type(4)));
+typedef int probe_v16i __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void mfma_peak_probe_kernel(unsigned long long* __restrict__ out, int iters) {
+    probe_v16i acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0;
+    const int t = (int)threadIdx.x;
+    const probe_v4i a = {t, t + 1, t + 2, t + 3}, b = {t * 3, t * 5, t * 7, t * 9};
+    const unsigned long long c0 = clock64(), r0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+    }
+    int keep = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) keep ^= acc[i][e];
+    const unsigned long long c1 = clock64(), r1 = wall_clock64();
+    if (threadIdx.x == 0 || keep == 0x7fffffff) {   // (the second condition only keeps the result alive)
+        unsigned long long* const o = out + (size_t)blockIdx.x * 4;
+        o[0] = c0;
+        o[1] = r0;
+        o[2] = c1;
+        o[3] = r1;
+    }
+}
+
 // Recovery helpers: list the flagged rows, gather them, put recomputed rows back.
 __global__ void list_flagged_kernel(const int32_t* __restrict__ flags, int M, int32_t* __restrict__ idx,
                                     int32_t* __restrict__ count) {
@@ -176,6 +225,16 @@ hipError_t launch_calib_copy(const void* src, void* dst, size_t bytes, hipStream
     const size_t n16 = bytes / 16;
     const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 16);
     calib_copy_kernel<<<dim3(grid), dim3(256), 0, s>>>((const uint4*)src, (uint4*)dst, n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_clock_probe(unsigned long long* out, unsigned long long ticks, hipStream_t s) {
+    clock_probe_kernel<<<dim3(1), dim3(64), 0, s>>>(out, ticks);
+    return hipGetLastError();
+}
+
+hipError_t launch_mfma_peak_probe(unsigned long long* out, int iters, hipStream_t s) {
+    mfma_peak_probe_kernel<<<dim3(256), dim3(256), 0, s>>>(out, iters);
     return hipGetLastError();
 }
 
