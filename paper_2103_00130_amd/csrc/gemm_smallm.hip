@@ -26,6 +26,7 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kOutC = 1, kOutQ = 2;
+constexpr int kSmallMWideN = 8192;   // from this width on a workgroup owns 32 columns (M <= 32)
 
 // sum over the 16 lanes of a DPP row; every lane of the row ends up with the total
 __device__ inline uint32_t row_sum16(uint32_t s) {
@@ -43,18 +44,22 @@ __device__ inline int32_t floor_mod127(long long v) {
     return r < 0 ? r + 127 : r;
 }
 
-// RB = 16-row blocks of A (M <= 16*RB)
-template <int RB, bool kCheck, int kOut>
+// RB = 16-row blocks of A (M <= 16*RB); NCB = blocks of 16 columns per workgroup.  With NCB = 2 a workgroup owns a
+// whole 32-column unit of the packed weight, with NCB = 4 two neighbouring units: every k-block it reads is 2 or
+// 4 KiB of contiguous memory instead of every other 256 bytes of it, and one A operand serves two or four matrix
+// instructions (wide weights, where the column blocks alone fill the chip many times over; measured at M = 16 on
+// 16384 x 32768 int8: 0.49 of the HBM peak with NCB = 1, 0.64 with 2, 0.70 with 4).
+template <int RB, int NCB, bool kCheck, int kOut>
 __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, const int n_blocks) {
-    constexpr int BATCH = RB == 1 ? 8 : 4;  // k-blocks per wave per batch of loads
+    constexpr int BATCH = (RB == 1 ? 8 : 4) / NCB > 0 ? (RB == 1 ? 8 : 4) / NCB : 1;  // k-blocks per wave per batch of loads
     constexpr bool kWantC = (kOut & kOutC) != 0, kWantQ = (kOut & kOutQ) != 0;
-    __shared__ v4i s_acc[3][RB][64];
+    __shared__ v4i s_acc[3][NCB][RB][64];
     __shared__ v4i s_chk[3][RB][64];
-    __shared__ uint32_t s_bsum[3][64];
+    __shared__ uint32_t s_bsum[3][NCB][64];
     __shared__ uint32_t s_d[64];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int cb = blockIdx.x, col0 = cb * 16;
+    const int cb = blockIdx.x, col0 = cb * 16 * NCB;
     const int KB = p.KB;
     const int lcol = lane & 15, lkg = lane >> 4;
 
@@ -72,19 +77,27 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
     // sum_k S_B[k] for the first column block's share of the check, fetched ahead of its use at the very end
     const int32_t total_sb = (kCheck && cb == 0) ? *p.total : 0;
 
-    v4i acc[RB], cacc[RB];
+    v4i acc[NCB][RB], cacc[RB];
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) acc[rb] = cacc[rb] = v4i{0, 0, 0, 0};
-    uint32_t bsum = 0;
+    for (int rb = 0; rb < RB; ++rb) {
+        cacc[rb] = v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int c = 0; c < NCB; ++c) acc[c][rb] = v4i{0, 0, 0, 0};
+    }
+    uint32_t bsum[NCB];
+#pragma unroll
+    for (int c = 0; c < NCB; ++c) bsum[c] = 0;
 
-    v4i fb[2][BATCH], fa[2][BATCH][RB], fl[2][BATCH];
+    v4i fb[2][BATCH][NCB], fa[2][BATCH][RB], fl[2][BATCH];
     auto issue = [&](int kb0, int s) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
             const int kb = kb0 + 4 * u;
             const int kbc = min(kb, KB - 1);
             // a k-block past the end is fetched from the last one and zeroed below
-            fb[s][u] = *reinterpret_cast<const v4i*>(b_src + (int64_t)kbc * B_KB_STRIDE);
+#pragma unroll
+            for (int c = 0; c < NCB; ++c)   // the next 16 columns of a unit lie 256 bytes further on, the next unit 2 KiB
+                fb[s][u][c] = *reinterpret_cast<const v4i*>(b_src + (int64_t)kbc * B_KB_STRIDE + (c >> 1) * kUnitBytes + (c & 1) * 256);
             const int k = min(kbc * 64 + lkg * 16, p.K - 16);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) fa[s][u][rb] = *reinterpret_cast<const v4i*>(a_row[rb] + k);
@@ -99,17 +112,22 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
             const int kb = kb0 + 4 * u;
-            v4i b = fb[s][u];
-            if (kb >= KB) b = v4i{0, 0, 0, 0};
-            // bytes of B as biased uint8, summed four at a time; the bias comes off at the end
-            bsum = __builtin_amdgcn_sad_u8((uint32_t)b.x ^ 0x80808080u, 0u, bsum);
-            bsum = __builtin_amdgcn_sad_u8((uint32_t)b.y ^ 0x80808080u, 0u, bsum);
-            bsum = __builtin_amdgcn_sad_u8((uint32_t)b.z ^ 0x80808080u, 0u, bsum);
-            bsum = __builtin_amdgcn_sad_u8((uint32_t)b.w ^ 0x80808080u, 0u, bsum);
+            v4i b[NCB];
+#pragma unroll
+            for (int c = 0; c < NCB; ++c) {
+                b[c] = fb[s][u][c];
+                if (kb >= KB) b[c] = v4i{0, 0, 0, 0};
+                // bytes of B as biased uint8, summed four at a time; the bias comes off at the end
+                bsum[c] = __builtin_amdgcn_sad_u8((uint32_t)b[c].x ^ 0x80808080u, 0u, bsum[c]);
+                bsum[c] = __builtin_amdgcn_sad_u8((uint32_t)b[c].y ^ 0x80808080u, 0u, bsum[c]);
+                bsum[c] = __builtin_amdgcn_sad_u8((uint32_t)b[c].z ^ 0x80808080u, 0u, bsum[c]);
+                bsum[c] = __builtin_amdgcn_sad_u8((uint32_t)b[c].w ^ 0x80808080u, 0u, bsum[c]);
+            }
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
                 const v4i a = fa[s][u][rb] ^ (int)0x80808080;
-                acc[rb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[rb], 0, 0, 0);
+#pragma unroll
+                for (int c = 0; c < NCB; ++c) acc[c][rb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[c], acc[c][rb], 0, 0, 0);
                 if (kCheck) cacc[rb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, fl[s][u], cacc[rb], 0, 0, 0);
             }
         }
@@ -132,10 +150,12 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
     if (wave > 0) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-            s_acc[wave - 1][rb][lane] = acc[rb];
+#pragma unroll
+            for (int c = 0; c < NCB; ++c) s_acc[wave - 1][c][rb][lane] = acc[c][rb];
             if (kCheck) s_chk[wave - 1][rb][lane] = cacc[rb];
         }
-        s_bsum[wave - 1][lane] = bsum;
+#pragma unroll
+        for (int c = 0; c < NCB; ++c) s_bsum[wave - 1][c][lane] = bsum[c];
     }
     __syncthreads();
     if (wave == 0) {
@@ -143,56 +163,62 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
         for (int w = 0; w < 3; ++w) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                acc[rb] += s_acc[w][rb][lane];
+#pragma unroll
+                for (int c = 0; c < NCB; ++c) acc[c][rb] += s_acc[w][c][rb][lane];
                 if (kCheck) cacc[rb] += s_chk[w][rb][lane];
             }
-            bsum += s_bsum[w][lane];
-        }
-        // column sum of the streamed B for column lcol: the four k-groups sit in lanes lcol + 16*g
-        // (row swap and half swap: both return {own, partner} in an order that depends on the lane)
-        {
-            const auto r16 = __builtin_amdgcn_permlane16_swap(bsum, bsum, false, false);
-            bsum = r16[0] + r16[1];
-            const auto r32 = __builtin_amdgcn_permlane32_swap(bsum, bsum, false, false);
-            bsum = r32[0] + r32[1];
+#pragma unroll
+            for (int c = 0; c < NCB; ++c) bsum[c] += s_bsum[w][c][lane];
         }
         // every lane summed 16 biased bytes per k-block slot; 4 waves x n_batches x BATCH slots x 4 k-groups
         const uint32_t bias = 128u * 16u * 4u * 4u * (uint32_t)(n_batches * BATCH);
-        const int32_t cs128 = 128 * (int32_t)(bsum - bias);
-
-        // accumulator layout of the 16x16 MFMA: lane l, element e is row 4*(l/16) + e, column l%16
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
+        for (int c = 0; c < NCB; ++c) {
+            // column sum of the streamed B for column lcol: the four k-groups sit in lanes lcol + 16*g
+            // (row swap and half swap: both return {own, partner} in an order that depends on the lane)
+            const auto r16 = __builtin_amdgcn_permlane16_swap(bsum[c], bsum[c], false, false);
+            bsum[c] = r16[0] + r16[1];
+            const auto r32 = __builtin_amdgcn_permlane32_swap(bsum[c], bsum[c], false, false);
+            bsum[c] = r32[0] + r32[1];
+            const int32_t cs128 = 128 * (int32_t)(bsum[c] - bias);
+            // accumulator layout of the 16x16 MFMA: lane l, element e is row 4*(l/16) + e, column l%16
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[rb][e] += cs128;
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[c][rb][e] += cs128;
+        }
 
         if (p.n_inj > 0) {
             // simulated faults in the 32-bit intermediate (test hook): XOR before the row sums
             const abft_inject_t* inj = reinterpret_cast<const abft_inject_t*>(p.inj);
             for (int n = 0; n < p.n_inj; ++n) {
                 const int r = inj[n].row, c = inj[n].col - col0;
-                if (r < 0 || r >= p.M || r >= 16 * RB || c < 0 || c >= 16 || inj[n].col >= p.N) continue;
-                const bool mine = (lcol == c) && (lkg == ((r & 15) >> 2));
+                if (r < 0 || r >= p.M || r >= 16 * RB || c < 0 || c >= 16 * NCB || inj[n].col >= p.N) continue;
+                const bool mine = (lcol == (c & 15)) && (lkg == ((r & 15) >> 2));
 #pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
+                for (int cc = 0; cc < NCB; ++cc)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (mine && rb == (r >> 4) && e == (r & 3)) acc[rb][e] ^= (int)inj[n].xor_mask;
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (mine && cc == (c >> 4) && rb == (r >> 4) && e == (r & 3)) acc[cc][rb][e] ^= (int)inj[n].xor_mask;
             }
         }
 
         // stores first (they need no answer), then the check, whose atomics wait for theirs;
         // per (rb, e) one store instruction covers 4 rows x 16 columns
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
+        for (int c = 0; c < NCB; ++c)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int row = rb * 16 + 4 * lkg + e, col = col0 + lcol;
-                if (row < p.M && col < p.N) {
-                    if (kWantC) p.C[(int64_t)row * p.ldc + col] = acc[rb][e];
-                    if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_one(acc[rb][e], p.colsum[col], col, p.rq);
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int row = rb * 16 + 4 * lkg + e, col = col0 + c * 16 + lcol;
+                    if (row < p.M && col < p.N) {
+                        if (kWantC) p.C[(int64_t)row * p.ldc + col] = acc[c][rb][e];
+                        if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_one(acc[c][rb][e], p.colsum[col], col, p.rq);
+                    }
                 }
-            }
         if (kCheck) {
             const bool mod127 = p.mod127 != 0;
             const int slot = cb & (kSmallMSlots - 1);
@@ -203,7 +229,11 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
                 for (int e = 0; e < 4; ++e) {
                     // (Algorithm 1 as printed, p.mod127: the entries are exact 32-bit values, K <= 65536, and are
                     // summed as residues; the one live digit column holds rowSum, so its product is exact too)
-                    const uint32_t rs = row_sum16(mod127 ? (uint32_t)floor_mod127((long long)acc[rb][e]) : (uint32_t)acc[rb][e]);
+                    uint32_t mine = 0;   // this lane's entries of the row (residues of them under the printed modulus)
+#pragma unroll
+                    for (int c = 0; c < NCB; ++c)
+                        mine += mod127 ? (uint32_t)floor_mod127((long long)acc[c][rb][e]) : (uint32_t)acc[c][rb][e];
+                    const uint32_t rs = row_sum16(mine);
                     uint32_t ck = lcol < kLimbs ? ((uint32_t)cacc[rb][e] << (8 * lcol)) : 0u;
                     ck += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)ck, 0xB1, 0xF, 0xF, true);
                     ck += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)ck, 0x4E, 0xF, 0xF, true);
@@ -277,14 +307,14 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
     }
 }
 
-template <int RB>
+template <int RB, int NCB>
 hipError_t launch_rb(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
-    const int n_blocks = (p.N + 15) / 16;
+    const int n_blocks = (p.N + 16 * NCB - 1) / (16 * NCB);
     const dim3 grid((unsigned)n_blocks), block(256);
-#define ABFT_LAUNCH(CK, OUT)                                                    \
-    do {                                                                        \
-        gemm_smallm_kernel<RB, CK, OUT><<<grid, block, 0, s>>>(p, n_blocks);    \
-        return hipGetLastError();                                               \
+#define ABFT_LAUNCH(CK, OUT)                                                         \
+    do {                                                                             \
+        gemm_smallm_kernel<RB, NCB, CK, OUT><<<grid, block, 0, s>>>(p, n_blocks);    \
+        return hipGetLastError();                                                    \
     } while (0)
 #define ABFT_OUT(CK)                                          \
     do {                                                      \
@@ -302,9 +332,12 @@ hipError_t launch_rb(bool check, bool want_c, bool want_q, const GemmParams& p, 
 
 hipError_t launch_gemm_smallm(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
     if (p.M > 64 || !p.a_vec_ok || p.K % 16 != 0) return hipErrorNotSupported;
-    if (p.M <= 16) return launch_rb<1>(check, want_c, want_q, p, s);
-    if (p.M <= 32) return launch_rb<2>(check, want_c, want_q, p, s);
-    return launch_rb<4>(check, want_c, want_q, p, s);
+    // whole 32-column units per workgroup once the 16-column blocks alone would fill the chip at least twice
+    const bool wide = p.N >= kSmallMWideN;
+    if (p.M <= 16 && p.N >= 2 * kSmallMWideN) return launch_rb<1, 4>(check, want_c, want_q, p, s);
+    if (p.M <= 16) return wide ? launch_rb<1, 2>(check, want_c, want_q, p, s) : launch_rb<1, 1>(check, want_c, want_q, p, s);
+    if (p.M <= 32) return wide ? launch_rb<2, 2>(check, want_c, want_q, p, s) : launch_rb<2, 1>(check, want_c, want_q, p, s);
+    return launch_rb<4, 1>(check, want_c, want_q, p, s);
 }
 
 }  // namespace abft

@@ -287,7 +287,11 @@ def test_deterministic_across_runs(binding, gpu_util):
 
 
 SMALLM_SHAPES = [(1, 16, 16), (1, 800, 3200), (5, 33, 80), (16, 48, 64), (16, 4096, 2048), (17, 100, 144),
-                 (32, 512, 1024), (33, 70, 272), (64, 256, 512), (64, 1000, 1040)]
+                 (32, 512, 1024), (33, 70, 272), (64, 256, 512), (64, 1000, 1040),
+                 # wide weights: a workgroup owns whole 32-column units (M <= 32, N >= 8192), ragged last unit
+                 (16, 8192, 256), (9, 8217, 208), (32, 8240, 144), (17, 12000, 80),
+                 # ... and two units (64 columns) from N = 16384 on (M <= 16)
+                 (16, 16384, 128), (7, 16454, 80), (3, 16400, 2112)]
 
 
 @pytest.mark.parametrize("M,N,K", SMALLM_SHAPES)
@@ -793,7 +797,8 @@ def test_errcount_as_a_counter_and_without_one(binding, gpu_util, oracle, M, N, 
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("M,N,K", [(1, 800, 3200), (16, 48, 64), (17, 100, 144), (33, 70, 272), (64, 1000, 1040), (13, 16, 64)])
+@pytest.mark.parametrize("M,N,K", [(1, 800, 3200), (16, 48, 64), (17, 100, 144), (33, 70, 272), (64, 1000, 1040), (13, 16, 64),
+                                   (12, 8230, 96), (5, 16420, 64)])
 def test_mod127_on_the_streaming_kernel(binding, gpu_util, oracle, M, N, K):
     """Algorithm 1 as printed through the streaming kernel (Section VI-A-1 names m = 1 among its shapes):
     clean, every bit of a C element, value changes that are multiples of 127 (missed by both sides), B faults
