@@ -26,7 +26,7 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kOutC = 1, kOutQ = 2;
-constexpr int kSmallMWideN = 8192;   // from this width on a workgroup owns 32 columns (M <= 32)
+constexpr int kSmallMWideN = 8192;   // from this width on a workgroup owns 32 columns (M <= 32): at least 256 workgroups remain (with fewer, 16 x 4096 x 2048 runs in 5.6 us instead of 4.7)
 
 // sum over the 16 lanes of a DPP row; every lane of the row ends up with the total
 __device__ inline uint32_t row_sum16(uint32_t s) {
