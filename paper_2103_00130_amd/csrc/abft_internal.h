@@ -69,14 +69,28 @@ struct RequantDev {
 // Requantization of one 32-bit value (Section III-B with the rank-1 correction of Eq. 1 for a
 // symmetric B): t = v - zA * colsum (+ bias) in wrap-around int32, one binary32 multiply, round
 // to nearest even, + zC, clamp to [0, 255].  The one place this arithmetic is written down.
-__device__ inline uint8_t requant_one(int32_t v, int32_t cs, int col, const RequantDev& rq) {
-    uint32_t t = (uint32_t)v - (uint32_t)rq.zA * (uint32_t)cs;
-    if (rq.bias) t += (uint32_t)rq.bias[col];
-    const float m = rq.mult[rq.per_channel ? col : 0];
-    const float p = __fmul_rn((float)(int32_t)t, m);
-    float y = __builtin_rintf(p) + (float)rq.zC;
+// What a column contributes, fetched once per column: colsum * zA - bias as one wrap-around term, and the
+// multiplier (a kernel that stores between two uses would otherwise have to fetch them again every time).
+struct RequantCol {
+    uint32_t sub;   // zA * colsum - bias (mod 2^32)
+    float mult;
+};
+__device__ inline RequantCol requant_col(int32_t cs, int col, const RequantDev& rq) {
+    RequantCol c;
+    c.sub = (uint32_t)rq.zA * (uint32_t)cs;
+    if (rq.bias) c.sub -= (uint32_t)rq.bias[col];
+    c.mult = rq.mult[rq.per_channel ? col : 0];
+    return c;
+}
+__device__ inline uint8_t requant_with(int32_t v, const RequantCol& c, int32_t zC) {
+    const uint32_t t = (uint32_t)v - c.sub;
+    const float p = __fmul_rn((float)(int32_t)t, c.mult);
+    float y = __builtin_rintf(p) + (float)zC;
     y = fminf(fmaxf(y, 0.0f), 255.0f);
     return (uint8_t)y;
+}
+__device__ inline uint8_t requant_one(int32_t v, int32_t cs, int col, const RequantDev& rq) {
+    return requant_with(v, requant_col(cs, col, rq), rq.zC);
 }
 #endif
 

@@ -208,17 +208,23 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
         // stores first (they need no answer), then the check, whose atomics wait for theirs;
         // per (rb, e) one store instruction covers 4 rows x 16 columns
 #pragma unroll
-        for (int c = 0; c < NCB; ++c)
+        for (int c = 0; c < NCB; ++c) {
+            const int col = col0 + c * 16 + lcol;
+            RequantCol rqc;   // this lane's column, fetched once
+            rqc.sub = 0;
+            rqc.mult = 0.0f;
+            if (kWantQ && col < p.N) rqc = requant_col(p.colsum[col], col, p.rq);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int row = rb * 16 + 4 * lkg + e, col = col0 + c * 16 + lcol;
+                    const int row = rb * 16 + 4 * lkg + e;
                     if (row < p.M && col < p.N) {
                         if (kWantC) p.C[(int64_t)row * p.ldc + col] = acc[c][rb][e];
-                        if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_one(acc[c][rb][e], p.colsum[col], col, p.rq);
+                        if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_with(acc[c][rb][e], rqc, p.rq.zC);
                     }
                 }
+        }
         if (kCheck) {
             const bool mod127 = p.mod127 != 0;
             const int slot = cb & (kSmallMSlots - 1);

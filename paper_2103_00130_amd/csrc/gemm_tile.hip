@@ -9,6 +9,7 @@ ABFT_DECL(a256w42);
 ABFT_DECL(a128);
 ABFT_DECL(a64);
 ABFT_DECL(a64r8);
+ABFT_DECL(a64r4);
 ABFT_DECL(a64k2);
 ABFT_DECL(g128);
 ABFT_DECL(g64);
@@ -43,6 +44,9 @@ hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, c
                 if (e != hipErrorNotSupported) return e;
             }
             if (tiles <= 256 && p.K >= 2048) return launch_gemm_tile_a64r8(check, want_c, want_q, p, s);
+            // short K on such a grid: a ring of four stages, all in flight before the first k-step, instead of the
+            // double buffer whose every stage waits out a trip to memory (256x512x1024: 6.7 -> see the measurements)
+            if (tiles <= 256 && p.K > 256) return launch_gemm_tile_a64r4(check, want_c, want_q, p, s);
             return launch_gemm_tile_a64(check, want_c, want_q, p, s);
         }
         case kTile256w24: return launch_gemm_tile_a256w24(check, want_c, want_q, p, s);

@@ -688,9 +688,19 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
     const int r_lane = wm * WTM + 4 * lhalf;   // first row of this lane inside the tile
     const int c_lane = wn * WTN + lcol;
     const bool full = (row0 + BM <= p.M) && (col0 + BN <= p.N);
-    int32_t zcs[TN];
+    // what this lane's columns contribute to the requantization, fetched once ahead of the stores (columns past N
+    // of the padded tile read the padded column sums and the first column's parameters; nothing of them is stored)
+    RequantCol rqc[TN];
 #pragma unroll
-    for (int t = 0; t < TN; ++t) zcs[t] = kWantQ ? p.colsum[col0 + c_lane + t * 32] : 0;
+    for (int t = 0; t < TN; ++t) {
+        rqc[t].sub = 0;
+        rqc[t].mult = 0.0f;
+        if (kWantQ) {
+            const int col = col0 + c_lane + t * 32;
+            rqc[t] = requant_col(p.colsum[col], col < p.N ? col : 0, p.rq);
+        }
+    }
+    const int32_t rq_zC = kWantQ ? p.rq.zC : 0;
     int32_t* cptr = kWantC ? p.C + (int64_t)(row0 + r_lane) * p.ldc + col0 + c_lane : nullptr;
     uint8_t* qptr = kWantQ ? p.Cq + (int64_t)(row0 + r_lane) * p.ldcq + col0 + c_lane : nullptr;
     const int rows_left = p.M - row0 - r_lane;  // rows of this lane's column that exist
@@ -719,7 +729,7 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
                         const int32_t val = raw + cs[t];
                         if (FULL || (roff < rows_left && col0 + c_lane + t * 32 < p.N)) {
                             if (kWantC) cptr[t * 32] = val;
-                            if (kWantQ) qptr[t * 32] = requant_one(val, zcs[t], col0 + c_lane + t * 32, p.rq);
+                            if (kWantQ) qptr[t * 32] = requant_with(val, rqc[t], rq_zC);
                         }
                     }
                     if (kCheck) {
@@ -779,7 +789,8 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
                 if (inj[m].row == row && inj[m].col == col) mask ^= inj[m].xor_mask;
             const int bi = r >> 5, rr = r & 31, bj = c >> 5;
             const int e_hit = (rr >> 3) * 4 + (rr & 3), half_hit = (rr >> 2) & 1;
-            int32_t raw = 0, cs_hit = 0, zcs_hit = 0;
+            int32_t raw = 0, cs_hit = 0;
+            RequantCol rqc_hit = rqc[0];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -789,11 +800,11 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
                         if (i == bi && t == bj && e == e_hit) raw = acc[i][t][e];
 #pragma unroll
             for (int t = 0; t < TN; ++t)
-                if (t == bj) { cs_hit = cs[t]; zcs_hit = zcs[t]; }
+                if (t == bj) { cs_hit = cs[t]; rqc_hit = rqc[t]; }
             if (lcol == (c & 31) && lhalf == half_hit) {
                 const int32_t val = raw + cs_hit, bad = (int32_t)((uint32_t)val ^ mask);
                 if (kWantC) p.C[(int64_t)row * p.ldc + col] = bad;
-                if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_one(bad, zcs_hit, col, p.rq);
+                if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_with(bad, rqc_hit, rq_zC);
                 // (the row sum was formed from the clean value; it is moved by the difference, taken in
                 // wrap-around arithmetic: a flip of bit 31 changes the value by 2^31)
                 if (kCheck)

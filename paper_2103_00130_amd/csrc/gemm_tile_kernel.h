@@ -354,9 +354,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_kernel(const GemmPara
 
     // store C_temp and/or its requantized form; padded rows and columns are dropped.  The
     // zero-point term of Eq. 1 uses the column sums stored with the weight.
-    int32_t zcs[TN];
+    RequantCol rqc[TN];   // this lane's columns, fetched once ahead of the stores
 #pragma unroll
-    for (int j = 0; j < TN; ++j) zcs[j] = kWantQ ? p.colsum[col0 + wn * WTN + j * 32 + lcol] : 0;
+    for (int j = 0; j < TN; ++j) {
+        rqc[j].sub = 0;
+        rqc[j].mult = 0.0f;
+        if (kWantQ) {
+            const int col = col0 + wn * WTN + j * 32 + lcol;
+            rqc[j] = requant_col(p.colsum[col], col < p.N ? col : 0, p.rq);
+        }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -368,7 +375,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_tile_kernel(const GemmPara
                     const int col = col0 + wn * WTN + j * 32 + lcol;
                     if (col < p.N) {
                         if (kWantC) p.C[(int64_t)row * p.ldc + col] = acc[i][j][e];
-                        if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_one(acc[i][j][e], zcs[j], col, p.rq);
+                        if (kWantQ) p.Cq[(int64_t)row * p.ldcq + col] = requant_with(acc[i][j][e], rqc[j], p.rq.zC);
                     }
                 }
             }
