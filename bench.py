@@ -556,10 +556,12 @@ def pmc_child_eb(spec):
     from paper_2103_00130_amd import binding as b
     from paper_2103_00130_amd import eb_workloads as ew
     torch.cuda.set_device(0)
-    d, n_bags = (int(x) for x in spec.split(":"))
+    parts = spec.split(":")
+    d, n_bags = int(parts[0]), int(parts[1])
+    aligned = len(parts) > 2 and parts[2] == "aligned"      # D:N_BAGS[:aligned]  (records on 128-byte lines)
     src = torch.zeros(CALIB_COPY_BYTES // 4, dtype=torch.int32, device="cuda")
     dst = torch.empty_like(src)
-    job = EbJob(b, torch, ew.EbWorkload("pmc", 4_000_000, d, n_bags, 100, False, "uniform"), max_sets=5)
+    job = EbJob(b, torch, ew.EbWorkload("pmc", 4_000_000, d, n_bags, 100, False, "uniform"), max_sets=5, aligned=aligned)
     torch.cuda.synchronize()
     b.abft_calib_copy(src, dst)
     for s_ in range(5):
@@ -616,9 +618,10 @@ def main():
         print(json.dumps({"eb": [measure_eb(b, torch, ewl, cpu=False)]}))
         return
     traffic, traffic_note = (None, "skipped") if args.no_traffic else measure_traffic(args)
-    eb_traffic = None
+    eb_traffic = eb_traffic_aligned = None
     if not args.no_traffic and not args.no_eb:
         eb_traffic, _ = measure_traffic(args, ["--pmc-child-eb", "64:16384"], EB_KERNEL_TAGS)
+        eb_traffic_aligned, _ = measure_traffic(args, ["--pmc-child-eb", "64:16384:aligned"], EB_KERNEL_TAGS)
 
     import torch
     from paper_2103_00130_amd import binding as b     # fails loudly if the HIP library is missing
@@ -731,10 +734,11 @@ def main():
             eb_runs += [(ew.TABLE1[128], False, 4), (ew.LARGE_BATCH[128], False, 4)]
         for ewl, aligned, bits in eb_runs:
             r = measure_eb(b, torch, ewl, cpu=not args.no_cpu_baseline and not aligned, aligned=aligned, bits=bits)
-            if eb_traffic is not None and ewl.name == ew.LARGE_BATCH[64].name and not aligned and bits == 8:
-                r["roofline"]["traffic"] = eb_traffic["read"] + eb_traffic["write"]
-                r["roofline"]["traffic_read"] = eb_traffic["read"]
-                r["roofline"]["traffic_write"] = eb_traffic["write"]
+            tr = eb_traffic_aligned if aligned else eb_traffic
+            if tr is not None and ewl.name == ew.LARGE_BATCH[64].name and bits == 8:
+                r["roofline"]["traffic"] = tr["read"] + tr["write"]
+                r["roofline"]["traffic_read"] = tr["read"]
+                r["roofline"]["traffic_write"] = tr["write"]
             out["eb"].append(r)
     print(json.dumps(out))
 
