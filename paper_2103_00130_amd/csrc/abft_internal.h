@@ -102,6 +102,9 @@ struct GemmParams {
     int a_vec_ok;              // A and lda are multiples of 16 bytes
     int mod127;                // compare modulo 127 (Algorithm 1 as printed) instead of 2^32
     int err_accumulate;        // flagged rows are added to *err_count instead of overwriting it
+    int share_q, share_r;      // the checksum product's K range (stages or k-blocks) is dealt out to the tile columns /
+                               // column blocks of the grid: block c takes share_q units, the first share_r blocks one more
+                               // (set by the launcher: a division by a run-time count costs a kernel hundreds of cycles)
     const int8_t* packed;
     const int8_t* limbs;
     const int32_t* colsum;
@@ -127,6 +130,9 @@ constexpr int kTicketFlatMax = 128;  // grids up to this size count their arriva
 // the streaming kernel spreads its per-row sums over kSmallMSlots slots of kSmallMRows rows
 constexpr int kSmallMSlots = 32;
 constexpr int kSmallMRows = 64;
+
+// first unit of block c's share (see share_q, share_r)
+__host__ __device__ inline int share_begin(int c, int q, int r) { return c * q + (c < r ? c : r); }
 
 #ifdef __HIPCC__
 // Arrival count of the workgroups of a grid in two levels, so that no workspace word takes more

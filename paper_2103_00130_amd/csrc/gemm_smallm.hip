@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) a_row[rb] = p.A + (int64_t)min(rb * 16 + lcol, p.M - 1) * p.lda;
     // this column block's share of the checksum product's K range
-    const int lo = (int)(((int64_t)cb * KB) / n_blocks), hi = (int)(((int64_t)(cb + 1) * KB) / n_blocks);
+    const int lo = share_begin(cb, p.share_q, p.share_r), hi = share_begin(cb + 1, p.share_q, p.share_r);
 
     // sum_k S_B[k] for the first column block's share of the check, fetched ahead of its use at the very end
     const int32_t total_sb = (kCheck && cb == 0) ? *p.total : 0;
@@ -314,8 +314,11 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
 }
 
 template <int RB, int NCB>
-hipError_t launch_rb(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
+hipError_t launch_rb(bool check, bool want_c, bool want_q, const GemmParams& p_in, hipStream_t s) {
+    GemmParams p = p_in;
     const int n_blocks = (p.N + 16 * NCB - 1) / (16 * NCB);
+    p.share_q = p.KB / n_blocks;   // k-blocks of the checksum product per column block
+    p.share_r = p.KB % n_blocks;
     const dim3 grid((unsigned)n_blocks), block(256);
 #define ABFT_LAUNCH(CK, OUT)                                                         \
     do {                                                                             \

@@ -271,8 +271,8 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
     // digit MFMAs.
     constexpr int kLimbStages = 32 / WGK;
     // (stage numbers of this group: the share is cut against the group's run of stages)
-    const int ck_lo = kCheck ? min(max((int)(((int64_t)tile_n * NS_all) / tiles_n) - s_base, 0), NS) : 0;
-    const int ck_hi = kCheck ? min(max((int)(((int64_t)(tile_n + 1) * NS_all) / tiles_n) - s_base, 0), NS) : 0;
+    const int ck_lo = kCheck ? min(max(share_begin(tile_n, p.share_q, p.share_r) - s_base, 0), NS) : 0;
+    const int ck_hi = kCheck ? min(max(share_begin(tile_n + 1, p.share_q, p.share_r) - s_base, 0), NS) : 0;
     uint8_t* const s_limb = smem + S * (A_STAGE + B_STAGE) + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t);
     // sum_k S_B[k], which the first tile column needs at the very end (the u8 -> s8 shift of A moves every
     // checksum product by 128 times it): fetched now, so that the epilogue does not wait for memory
@@ -906,8 +906,11 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
 }
 
 template <int BM, int BN, int WGM, int WGN, int kStages, int WGK = 1>
-hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p, hipStream_t s) {
+hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p_in, hipStream_t s) {
+    GemmParams p = p_in;
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    p.share_q = p.KB2 / tiles_n;   // stages of the checksum product per tile column
+    p.share_r = p.KB2 % tiles_n;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(WGM * WGN * WGK * 64);
     const size_t lds = WGK * ((group_lds_bytes<BM, BN, WGN, kStages, WGK>() + 1023) / 1024 * 1024);
     if (WGK > 1) {
