@@ -270,9 +270,10 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
     // vector-memory traffic, the direct-to-LDS loads of the next stage included, in front of the
     // digit MFMAs.
     constexpr int kLimbStages = 32 / WGK;
-    // (stage numbers of this group: the share is cut against the group's run of stages)
-    const int ck_lo = kCheck ? min(max(share_begin(tile_n, p.share_q, p.share_r) - s_base, 0), NS) : 0;
-    const int ck_hi = kCheck ? min(max(share_begin(tile_n + 1, p.share_q, p.share_r) - s_base, 0), NS) : 0;
+    // (stage numbers of this group: every group's run of stages is dealt out to the tile columns in the same way, so
+    // that the groups of a K-split workgroup carry the same number of checked stages between their common barriers)
+    const int ck_lo = kCheck ? share_begin(tile_n, p.share_q, p.share_r) : 0;
+    const int ck_hi = kCheck ? share_begin(tile_n + 1, p.share_q, p.share_r) : 0;
     uint8_t* const s_limb = smem + S * (A_STAGE + B_STAGE) + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t);
     // sum_k S_B[k], which the first tile column needs at the very end (the u8 -> s8 shift of A moves every
     // checksum product by 128 times it): fetched now, so that the epilogue does not wait for memory
@@ -909,15 +910,15 @@ template <int BM, int BN, int WGM, int WGN, int kStages, int WGK = 1>
 hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p_in, hipStream_t s) {
     GemmParams p = p_in;
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    p.share_q = p.KB2 / tiles_n;   // stages of the checksum product per tile column
-    p.share_r = p.KB2 % tiles_n;
+    p.share_q = (p.KB2 / WGK) / tiles_n;   // stages of the checksum product per tile column (and K group)
+    p.share_r = (p.KB2 / WGK) % tiles_n;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(WGM * WGN * WGK * 64);
     const size_t lds = WGK * ((group_lds_bytes<BM, BN, WGN, kStages, WGK>() + 1023) / 1024 * 1024);
     if (WGK > 1) {
         // every group must pass the same barriers: equal runs of stages, and a share of the checksum
         // product that its staged digits hold without a refill (32 / WGK stages)
         const int ns = p.KB2;
-        if (ns % WGK != 0 || ns / WGK < 2 || (ns + tiles_n - 1) / tiles_n + 1 > 32 / WGK) return hipErrorNotSupported;
+        if (ns % WGK != 0 || ns / WGK < 2 || (ns / WGK + tiles_n - 1) / tiles_n > 32 / WGK) return hipErrorNotSupported;
     }
     // Row sums in block form or per row.  Small wave tiles: always the block form, which halves the
     // vector work of an epilogue that is short anyway.  The 128x128 wave tile: per row when the grid
