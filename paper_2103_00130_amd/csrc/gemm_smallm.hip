@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void gemm_smallm_kernel(const GemmParams p, co
             // a k-block past the end is fetched from the last one and zeroed below
 #pragma unroll
             for (int c = 0; c < NCB; ++c)   // the next 16 columns of a unit lie 256 bytes further on, the next unit 2 KiB
-                fb[s][u][c] = *reinterpret_cast<const v4i*>(b_src + (int64_t)kbc * B_KB_STRIDE + (c >> 1) * kUnitBytes + (c & 1) * 256);
+                fb[s][u][c] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(b_src + (int64_t)kbc * B_KB_STRIDE + (c >> 1) * kUnitBytes + (c & 1) * 256));
             const int k = min(kbc * 64 + lkg * 16, p.K - 16);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) fa[s][u][rb] = *reinterpret_cast<const v4i*>(a_row[rb] + k);

@@ -729,7 +729,10 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
                         if (kCheck && MOD) rs64 += raw;
                         const int32_t val = raw + cs[t];
                         if (FULL || (roff < rows_left && col0 + c_lane + t * 32 < p.N)) {
-                            if (kWantC) cptr[t * 32] = val;
+                            if (kWantC) {
+                                if (kAhead2) cptr[t * 32] = val;
+                                else __builtin_nontemporal_store(val, &cptr[t * 32]);
+                            }
                             if (kWantQ) qptr[t * 32] = requant_with(val, rqc[t], rq_zC);
                         }
                     }
