@@ -184,8 +184,8 @@ __global__ __launch_bounds__(256) void eb_batch_kernel(const EbParams p) {
             if (in && !r.ok[u]) flag |= ABFT_EB_BAD_INDEX;
             if (kWeighted) r.wv[u] = ix.wv[u];
             const uint8_t* rec = base + (r.ok[u] ? ix.idx[u] : 0) * p.stride;
-            r.q[u] = *reinterpret_cast<const v4u*>(rec);
-            r.tl[u] = *reinterpret_cast<const v4u*>(rec + (CB - piece * 16));
+            r.q[u] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(rec));
+            r.tl[u] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(rec + (CB - piece * 16)));
         }
     };
     auto pool = [&](const RowSet& r) __attribute__((always_inline)) {
@@ -333,7 +333,7 @@ __global__ __launch_bounds__(256) void eb_group_kernel(const EbParams p) {
         for (int l = 0; l < NL; ++l) {
             const int g = l * 256 + tid, r = g / P, pc = g - r * P;
             const bool ok = (uint64_t)idx[l] < (uint64_t)p.rows;
-            v[l] = *reinterpret_cast<const v4u*>(p.tab + (ok ? idx[l] : 0) * p.stride + pc * 16);
+            v[l] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p.tab + (ok ? idx[l] : 0) * p.stride + pc * 16));
             // the last word of a record's tail is unused in memory; staged, it marks a row that is not pooled
             if (pc == G) v[l][3] = ok ? 0u : 1u;
         }
