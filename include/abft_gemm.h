@@ -143,7 +143,11 @@ typedef struct {
 
 /* Scratch the checked GEMM needs for a problem with M rows against Bp: one
  * 64-bit word per row (partial row sum - checksum, and how many column blocks
- * have contributed) and a few counting words (rows finished, rows corrupted).
+ * have contributed) and a few counting words (rows finished, rows corrupted);
+ * with Bp given, also room for the partial tiles of a K split across
+ * workgroups on the shapes where the library uses one (few tiles, K of about
+ * 5000 and more; Bp == NULL, or a smaller workspace of at least the size this
+ * call returns for Bp == NULL, runs every shape unsplit).
  * The memory must be zero before its first use (abft_workspace_init) and every
  * call leaves it zero again, so one workspace serves any number of calls that
  * are ordered on one stream.  Calls that may overlap need one workspace each. */

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libabftgemm.so")
 SOURCES = ["api.hip", "pack.hip", "gemm_tile.hip", "gemm_tile_a256.hip", "gemm_tile_a256w24.hip", "gemm_tile_a256w42.hip",
-           "gemm_tile_a128.hip", "gemm_tile_a64.hip", "gemm_tile_a64r8.hip", "gemm_tile_a64r4.hip", "gemm_tile_a64k2.hip", "gemm_tile_g128.hip", "gemm_tile_g64.hip", "gemm_smallm.hip",
+           "gemm_tile_a128.hip", "gemm_tile_a64.hip", "gemm_tile_a64r8.hip", "gemm_tile_a64r4.hip", "gemm_tile_a64s.hip", "gemm_tile_a64k2.hip", "gemm_tile_g128.hip", "gemm_tile_g64.hip", "gemm_smallm.hip",
            "rowops.hip", "locate.hip", "eb.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

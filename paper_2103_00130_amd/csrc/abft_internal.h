@@ -118,6 +118,10 @@ struct GemmParams {
     RequantDev rq;
     const void* inj;           // abft_inject_t[n_inj]
     int n_inj;
+    int ksplit;                // K slices across workgroups (split-K kernels; 1 elsewhere)
+    int32_t* ws_tickets;       // split-K: one arrival counter per tile
+    int32_t* ws_part;          // split-K: partial tiles, [tile][slice][value][thread]
+    size_t ws_ints;            // ints the caller's workspace holds
     unsigned long long* clock_trace;  // diagnostic builds (ABFT_CLOCK_TRACE): 6 words per workgroup, else NULL
     int32_t* ws;               // workspace: counting words in the first kWsHeaderInts ints, then the per-row words
 };
@@ -130,6 +134,44 @@ constexpr int kTicketFlatMax = 128;  // grids up to this size count their arriva
 // the streaming kernel spreads its per-row sums over kSmallMSlots slots of kSmallMRows rows
 constexpr int kSmallMSlots = 32;
 constexpr int kSmallMRows = 64;
+
+// ints of workspace the row words and counting words of a problem with M rows take
+inline size_t ws_base_ints(int M) {
+    const size_t rows = 2 * ((((size_t)M + 63) / 64) * 64);  // one 64-bit word per row
+    // streaming kernel: one 64-bit word per (slot, row) and one per row
+    const size_t streaming = 2 * ((size_t)kSmallMSlots * kSmallMRows + kSmallMRows);
+    return (size_t)kWsHeaderInts + (rows > streaming ? rows : streaming);
+}
+
+// Split-K across workgroups (64x64 tiles, grids that would leave most compute units idle): how many K slices,
+// and where the tile tickets and the partial tiles lie in the workspace behind the row words.  One place for
+// the rule, so that abft_gemm_workspace_bytes and the launcher agree.
+constexpr int kSplitKPartInts = 256 * 17;   // per workgroup: 256 threads x (16 accumulator values + 1 column sum)
+struct SplitKPlan {
+    int z;                                  // slices (1 = no split)
+    size_t tickets_off, part_off, total_ints;
+};
+inline SplitKPlan splitk_plan(int M, int N, int stages) {
+    SplitKPlan pl;
+    const long tiles = (long)((M + 63) / 64) * ((N + 63) / 64);
+    pl.z = 1;
+    // The slices of a tile meet through memory (the L2s are not coherent with each other): store the partial tile,
+    // wait for the acknowledgement, take the ticket, fetch the others' partials - three dependent device-scope round
+    // trips, measured at 3.5-4 us.  A stage of the unsplit 64x64 loop takes about 0.25 us, so the split pays from
+    // about forty stages on (measured: 256x512x4096 8.1 us split against 8.5 unsplit, 256x1024x8192 10.5 against
+    // 14.0, 128x128x16384 9.8 against 33.9; 256x512x2048 7.6 against 5.9), and slices of fewer than four stages
+    // are all overhead.
+    if (stages >= 40)
+        for (int z = 16; z >= 2; z >>= 1)
+            if (tiles * z <= 256 && stages % z == 0 && stages / z >= 4) {
+                pl.z = z;
+                break;
+            }
+    pl.tickets_off = ws_base_ints(M);
+    pl.part_off = pl.tickets_off + (size_t)((tiles + 63) / 64 * 64);
+    pl.total_ints = pl.z > 1 ? pl.part_off + (size_t)tiles * pl.z * kSplitKPartInts : pl.tickets_off;
+    return pl;
+}
 
 // first unit of block c's share (see share_q, share_r)
 __host__ __device__ inline int share_begin(int c, int q, int r) { return c * q + (c < r ? c : r); }

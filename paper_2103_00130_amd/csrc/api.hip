@@ -46,12 +46,7 @@ void free_handle(abft_packed_b* h) {
     delete h;
 }
 
-size_t ws_ints(int M) {
-    const size_t rows = 2 * ((((size_t)M + 63) / 64) * 64);  // one 64-bit word per row
-    // streaming kernel: one 64-bit word per (slot, row) and one per row
-    const size_t streaming = 2 * ((size_t)abft::kSmallMSlots * abft::kSmallMRows + abft::kSmallMRows);
-    return (size_t)abft::kWsHeaderInts + (rows > streaming ? rows : streaming);
-}
+size_t ws_ints(int M) { return abft::ws_base_ints(M); }
 
 }  // namespace
 
@@ -155,8 +150,9 @@ int abft_packed_b_flip_checksum_bit_mod127(abft_packed_b* Bp, int k, int bit, vo
 void abft_packed_b_destroy(abft_packed_b* Bp) { free_handle(Bp); }
 
 size_t abft_gemm_workspace_bytes(int M, const abft_packed_b* Bp) {
-    (void)Bp;
     if (M < 1) return 0;
+    // with the weight known: room for the partial tiles of a K split across workgroups, where one would be used
+    if (Bp) return abft::splitk_plan(M, Bp->N, Bp->KB / 2).total_ints * sizeof(int32_t);
     return ws_ints(M) * sizeof(int32_t);
 }
 
@@ -191,9 +187,11 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
     if (n_inj < 0 || (n_inj > 0 && !inj)) return fail(ABFT_EINVAL, "%s: bad injection list", fn);
     if (check) {
         if (!row_flags) return fail(ABFT_EINVAL, "%s: row_flags is NULL", fn);
-        if (!workspace || workspace_bytes < abft_gemm_workspace_bytes(M, Bp))
+        // (the row words are what a checked launch needs; the room for a K split across workgroups that
+        // abft_gemm_workspace_bytes adds is optional: without it the launch runs unsplit)
+        if (!workspace || workspace_bytes < ws_ints(M) * sizeof(int32_t))
             return fail(ABFT_EINVAL, "%s: workspace of %zu bytes, %zu needed", fn, workspace_bytes,
-                        abft_gemm_workspace_bytes(M, Bp));
+                        ws_ints(M) * sizeof(int32_t));
     }
 
     abft::GemmParams p;
@@ -226,6 +224,8 @@ int abft_gemm_u8s8s32_checked(const uint8_t* A, int64_t lda, int M, const abft_p
     p.inj = inj;
     p.n_inj = n_inj;
     p.ws = (int32_t*)workspace;
+    p.ws_ints = workspace ? workspace_bytes / sizeof(int32_t) : 0;
+    p.ksplit = 1;
     p.err_accumulate = (flags & ABFT_ERRCOUNT_ACCUMULATE) != 0;
 #ifdef ABFT_CLOCK_TRACE
     p.clock_trace = g_clock_trace.load(std::memory_order_acquire);

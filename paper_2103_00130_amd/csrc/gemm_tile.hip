@@ -10,6 +10,7 @@ ABFT_DECL(a128);
 ABFT_DECL(a64);
 ABFT_DECL(a64r8);
 ABFT_DECL(a64r4);
+ABFT_DECL(a64s);
 ABFT_DECL(a64k2);
 ABFT_DECL(g128);
 ABFT_DECL(g64);
@@ -39,6 +40,12 @@ hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, c
             // staged digits; then one group with a ring of eight stages takes a long K (it takes most of
             // a unit's LDS, and filling it costs more than it saves below about sixteen stages).
             const int64_t tiles = (int64_t)((p.M + 63) / 64) * ((p.N + 63) / 64);
+            // few tiles and a long K: K is split across workgroups as well, so that the compute units that would sit
+            // idle take slices of it (the launcher refuses when the caller's workspace has no room for the partial tiles)
+            if (splitk_plan(p.M, p.N, p.KB2).z > 1) {
+                const hipError_t e = launch_gemm_tile_a64s(check, want_c, want_q, p, s);
+                if (e != hipErrorNotSupported) return e;
+            }
             if (tiles <= 256 && p.K >= 1536) {
                 const hipError_t e = launch_gemm_tile_a64k2(check, want_c, want_q, p, s);
                 if (e != hipErrorNotSupported) return e;

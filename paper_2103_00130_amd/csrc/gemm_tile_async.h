@@ -106,7 +106,13 @@ constexpr size_t group_lds_bytes() {
 // and one wavefront issues at most one instruction every four cycles).  The groups pass the same
 // barriers (same number of stages each, the launcher sees to it); at the end groups 1.. hand their
 // accumulators to group 0 through LDS and leave, and group 0 runs the epilogue.
-template <int BM, int BN, int WGM, int WGN, int kStages, bool kCheck, int kOut, bool kBlockSums, int WGK>
+// kSplitK: K split across workgroups as well.  p.ksplit workgroups per tile take consecutive runs of stages; each
+// stores its partial tile (accumulators and column sums) in the workspace and takes a ticket on the tile's counter,
+// and the one that arrives last adds the others' partials to its own and runs the epilogue.  The checksum product
+// of every run of stages is dealt out to the tile columns as before, so every workgroup contributes its share
+// of it to the row words directly (the comparison of Eq. 2b is linear in the K slices) and only the last one
+// contributes row sums.  For grids of 64x64 tiles that would leave most compute units idle.
+template <int BM, int BN, int WGM, int WGN, int kStages, bool kCheck, int kOut, bool kBlockSums, int WGK, bool kSplitK = false>
 __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(const GemmParams p, const int tiles_m,
                                                                              const int tiles_n) {
     constexpr int NW = WGM * WGN, NT = NW * 64;    // wavefronts and threads of one group
@@ -137,8 +143,8 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
     int tile_m, tile_n;
     {
         const int n_tiles = tiles_m * tiles_n;
-        int t = blockIdx.x;
-        if (n_tiles % 8 == 0) t = (blockIdx.x & 7) * (n_tiles >> 3) + (blockIdx.x >> 3);
+        int t = kSplitK ? (int)blockIdx.x % n_tiles : (int)blockIdx.x;   // (split-K: slice z = blockIdx.x / n_tiles)
+        if (!kSplitK && n_tiles % 8 == 0) t = (blockIdx.x & 7) * (n_tiles >> 3) + (blockIdx.x >> 3);
         const int strip_h = tiles_m >= 4 ? 4 : tiles_m;
         const int per_strip = strip_h * tiles_n;
         const int strip = t / per_strip, r = t - strip * per_strip;
@@ -147,9 +153,11 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
         tile_m = strip * strip_h + r - tile_n * h;
     }
     const int row0 = tile_m * BM, col0 = tile_n * BN;
-    const int NS_all = p.KB2;          // stages of 128 k-values
-    const int NS = NS_all / WGK;       // ... of this group (the launcher splits only what divides)
-    const int s_base = grp * NS;       // its first stage
+    const int Z = kSplitK ? p.ksplit : 1;                                       // K slices across workgroups
+    const int z = kSplitK ? (int)blockIdx.x / (tiles_m * tiles_n) : 0;
+    const int NS_all = p.KB2;            // stages of 128 k-values
+    const int NS = NS_all / (WGK * Z);   // ... of this group (the launcher splits only what divides)
+    const int s_base = (z * WGK + grp) * NS;  // its first stage
 
     // ---- direct global->LDS loads ---------------------------------------------------
     // One instruction moves 16 bytes per lane to LDS address m0 + lane*16.  They are issued
@@ -177,7 +185,7 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
             const int c16 = ((lane & 7) ^ ((r >> 1) & 7)) * 16;
             const uint32_t rowoff = (uint32_t)min(row0 + r, p.M - 1) * (uint32_t)p.lda;
             a_voff[i] = rowoff + (uint32_t)c16;
-            a_voff_last[i] = rowoff + (uint32_t)(grp == WGK - 1 ? min(c16, c16_max) : c16);  // only the last group meets K's end
+            a_voff_last[i] = rowoff + (uint32_t)((grp == WGK - 1 && z == Z - 1) ? min(c16, c16_max) : c16);  // only the last group meets K's end
             a_lds[i] = lds_base + (wave * A_LD + i) * 1024;
         }
     }
@@ -277,7 +285,7 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
     uint8_t* const s_limb = smem + S * (A_STAGE + B_STAGE) + (4 * BN + WGN * BM + BM + 4) * sizeof(int32_t);
     // sum_k S_B[k], which the first tile column needs at the very end (the u8 -> s8 shift of A moves every
     // checksum product by 128 times it): fetched now, so that the epilogue does not wait for memory
-    int32_t total_sb = (kCheck && tile_n == 0) ? *p.total : 0;
+    int32_t total_sb = (kCheck && tile_n == 0 && z == 0) ? *p.total : 0;
     int limb_base = ck_lo;  // stage whose digits sit at the start of s_limb
     // (copied by the same direct global->LDS loads as the stages, 1 KiB per instruction: no trip through
     // registers, and no wait that the compiler would place - it does not see the direct loads and would
@@ -645,6 +653,53 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
         }
     }
 
+    // ------------------------- K split across workgroups: partial tiles meet in the last arrival -------------------------
+    bool last = true;   // this workgroup holds the complete tile (always, without a split)
+    if constexpr (kSplitK) {
+        static_assert(WGK == 1 && TM * TN == 1 && NT == 256, "split-K is built for the 64x64 tile of four 32x32 wavefronts");
+        __shared__ int s_ticket;
+        constexpr int kVals = 16 * TM * TN + TN;
+        static_assert(kVals * NT == kSplitKPartInts, "layout of a partial tile");
+        const int tile = tile_m * tiles_n + tile_n;
+        int32_t* const mine = p.ws_part + ((size_t)tile * Z + z) * kSplitKPartInts + tid;
+        {
+            // device-scope stores (they pass through the L2, which is not coherent with the other seven): once this
+            // wavefront's stores are acknowledged and the barrier is passed, the whole partial tile is in memory
+            int k = 0;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) __hip_atomic_store(mine + (k++) * NT, acc[0][0][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(mine + (k++) * NT, (int32_t)bsum[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        wait_vmem();   // (also the direct-to-LDS loads still in flight)
+        __syncthreads();
+        if (tid == 0) s_ticket = __hip_atomic_fetch_add(p.ws_tickets + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        last = s_ticket == Z - 1;
+        if (last) {
+            if (tid == 0) __hip_atomic_store(p.ws_tickets + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // the other slices' partial tiles, four at a time so that their loads are in flight together (a slice
+            // number past the last one, or this workgroup's own, re-reads a valid partial and adds nothing)
+            for (int z0 = 0; z0 < Z; z0 += 4) {
+                int32_t v[4][kVals];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int32_t* const theirs = p.ws_part + ((size_t)tile * Z + min(z0 + j, Z - 1)) * kSplitKPartInts + tid;
+#pragma unroll
+                    for (int k = 0; k < kVals; ++k) v[j][k] = __hip_atomic_load(theirs + k * NT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int32_t use = (z0 + j < Z && z0 + j != z) ? -1 : 0;   // all ones or zero
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[0][0][e] += v[j][e] & use;
+                    bsum[0] += (uint32_t)(v[j][16] & use);
+                }
+            }
+        } else if (!kCheck) {
+            return;   // (nothing in flight: awaited above)
+        }
+    }
+
     // ---------------------------------- epilogue ----------------------------------
     // accumulator layout of the 32x32 MFMA: lane l, element e of block (i, t) is
     // row 8*(e/4) + 4*(l/32) + e%4, column l%32 of that block.
@@ -654,6 +709,9 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
     int32_t* const s_bs = reinterpret_cast<int32_t*>(smem + S * (A_STAGE + B_STAGE));
     int32_t* const s_rs = s_bs + 4 * BN;
     int32_t* const s_ck = s_rs + WGN * BM;
+    const bool mod127 = kCheck && p.mod127 != 0;
+    // (split-K: only the workgroup that holds the complete tile stores it and forms its row sums)
+    if (last) {
     // column sums of the streamed B: lane halves hold the two k-groups, waves wm = 0 and 1 (or a
     // lone wave) hold alternate k-steps; every byte carried a bias of 128
     constexpr int SUM_WAVES = WGM == 1 ? 1 : 2;
@@ -762,7 +820,6 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
         }
     };
 
-    const bool mod127 = kCheck && p.mod127 != 0;
     auto store_form = [&](auto full_c, auto mod_c) __attribute__((always_inline)) {
         store_blocks(full_c, mod_c, std::integral_constant<bool, kBlockSums>{});
     };
@@ -818,6 +875,8 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
         }
     }
 
+    }  // if (last)
+
     if (kCheck) {
         // 16x16 accumulator: lane l, element e is row 4*(l/16) + e, column l%16; columns 0..3
         // hold the four digit products
@@ -845,19 +904,23 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
         const int r = tid;
         if (r < BM && row0 + r < p.M) {
             uint32_t d = 0;
+            if (last) {
 #pragma unroll
-            for (int w = 0; w < WGN; ++w) d += (uint32_t)s_rs[w * BM + r];
+                for (int w = 0; w < WGN; ++w) d += (uint32_t)s_rs[w * BM + r];
+            }
+            const bool first = tile_n == 0 && z == 0;   // the workgroup that accounts for the u8 -> s8 shift of the checksum product
+            const int arrivals = tiles_n * Z;           // contributions a row's word receives
             if (mod127) {
                 // residues: sums of at most 32 lanes x WGN waves of values below 127, minus the exact
                 // checksum share, as a residue again so that the workspace word cannot wrap
                 long long dd = (long long)d - (long long)s_ck[r];
-                if (tile_n == 0) dd -= 128ll * (long long)total_sb;
+                if (first) dd -= 128ll * (long long)total_sb;
                 d = (uint32_t)floor_mod127(dd);
             } else {
                 d -= (uint32_t)s_ck[r];
-                if (tile_n == 0) d -= 128u * (uint32_t)total_sb;  // sum_k 128*S_B[k], once per row
+                if (first) d -= 128u * (uint32_t)total_sb;  // sum_k 128*S_B[k], once per row
             }
-            if (tiles_n == 1) {
+            if (arrivals == 1) {
                 // one tile column holds the whole row: the comparison ends here, nothing crosses workgroups
                 bad = mod127 ? (d % 127u != 0) : (d != 0);
                 p.row_flags[row0 + r] = bad ? 1 : 0;
@@ -865,7 +928,7 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
             } else {
                 const unsigned long long old = __hip_atomic_fetch_add(ws_rows + row0 + r, ((unsigned long long)d << 32) | 1ull,
                                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if ((uint32_t)old == (uint32_t)tiles_n - 1u) {
+                if ((uint32_t)old == (uint32_t)arrivals - 1u) {
                     const uint32_t diff = (uint32_t)(old >> 32) + d;
                     bad = mod127 ? (diff % 127u != 0) : (diff != 0);
                     __hip_atomic_store(ws_rows + row0 + r, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -909,13 +972,23 @@ __global__ __launch_bounds__(WGM* WGN* WGK * 64) void gemm_tile_async_kernel(con
 #endif
 }
 
-template <int BM, int BN, int WGM, int WGN, int kStages, int WGK = 1>
+template <int BM, int BN, int WGM, int WGN, int kStages, int WGK = 1, bool kSplitK = false>
 hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p_in, hipStream_t s) {
     GemmParams p = p_in;
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    p.share_q = (p.KB2 / WGK) / tiles_n;   // stages of the checksum product per tile column (and K group)
-    p.share_r = (p.KB2 / WGK) % tiles_n;
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(WGM * WGN * WGK * 64);
+    int Z = 1;
+    if (kSplitK) {
+        // slices, tickets and partial tiles as splitk_plan lays them out; refused when the workspace does not hold them
+        const SplitKPlan pl = splitk_plan(p.M, p.N, p.KB2);
+        if (pl.z < 2 || p.ws == nullptr || p.ws_ints < pl.total_ints) return hipErrorNotSupported;
+        Z = pl.z;
+        p.ksplit = Z;
+        p.ws_tickets = p.ws + pl.tickets_off;
+        p.ws_part = p.ws + pl.part_off;
+    }
+    p.share_q = (p.KB2 / (WGK * Z)) / tiles_n;   // stages of the checksum product per tile column (and K group / slice)
+    p.share_r = (p.KB2 / (WGK * Z)) % tiles_n;
+    const dim3 grid((unsigned)(tiles_m * tiles_n * Z)), block(WGM * WGN * WGK * 64);
     const size_t lds = WGK * ((group_lds_bytes<BM, BN, WGN, kStages, WGK>() + 1023) / 1024 * 1024);
     if (WGK > 1) {
         // every group must pass the same barriers: equal runs of stages, and a share of the checksum
@@ -940,7 +1013,7 @@ hipError_t launch_cfg(bool check, bool want_c, bool want_q, const GemmParams& p_
     } while (0)
 #define ABFT_LAUNCH_FORM(CK, OUT, BS)                                                                     \
     do {                                                                                                  \
-        auto kern = gemm_tile_async_kernel<BM, BN, WGM, WGN, kStages, CK, OUT, ((BS) || !(CK)), WGK>;     \
+        auto kern = gemm_tile_async_kernel<BM, BN, WGM, WGN, kStages, CK, OUT, ((BS) || !(CK)), WGK, kSplitK>; \
         static std::atomic<uint64_t> lds_allowed{0};                                                      \
         const hipError_t e_attr = allow_dynamic_lds(reinterpret_cast<const void*>(kern), lds, lds_allowed);\
         if (e_attr != hipSuccess) return e_attr;                                                          \

@@ -22,6 +22,13 @@ class GpuRun:
         self.Bp = binding.abft_pack_b_checksum(self.B_dev, b_is_transposed=transposed)
         self.K, self.N = self.Bp.K, self.Bp.N
 
+    def _zero_ints(self, M, numel):
+        base = 64 + max(2 * ((M + 63) // 64 * 64), 2 * (32 * 64 + 64))
+        if numel <= base:
+            return numel
+        tiles = ((M + 63) // 64) * ((self.N + 63) // 64)
+        return base + (tiles + 63) // 64 * 64
+
     def checksum(self) -> np.ndarray:
         out = torch.empty(self.K, dtype=torch.int32, device="cuda")
         self.b.abft_packed_b_get_checksum(self.Bp, out)
@@ -66,5 +73,7 @@ class GpuRun:
             "flags": flags.cpu().numpy(),
             "err_count": int(cnt.item()),
             "Cq": None if Cq is None else Cq.cpu().numpy(),
-            "ws": ws.tensor.cpu().numpy(),
+            # the words every call must leave at zero: row and counting words, and (when the workspace also has room for
+            # the partial tiles of a K split across workgroups, whose contents are irrelevant) the tile tickets behind them
+            "ws": ws.tensor.cpu().numpy()[: self._zero_ints(M, ws.tensor.numel())],
         }

@@ -901,3 +901,76 @@ def test_recompute_flagged_rows_without_a_host_round_trip(binding, gpu_util, ora
     assert bad.err_count == 2 and status.cpu().tolist() == [2, 2] and int(cnt.item()) == 2
     assert np.array_equal(flags.cpu().numpy(), bad.flags) and np.array_equal(C.cpu().numpy(), bad.C)
     b.abft_packed_b_flip_bit(run.Bp, 100, 200, 6)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("M,N,K", [(256, 512, 8192), (200, 300, 5120), (65, 64, 6144), (130, 70, 5264), (100, 1000, 8192),
+                                   (128, 128, 16384)])
+def test_k_split_across_workgroups(binding, gpu_util, oracle, M, N, K):
+    """Few 64x64 tiles and a long K: the library splits K across workgroups, the slices of a tile meet through the
+    workspace, and every slice contributes its share of the checksum product on its own.  Bit-exact against the
+    oracle: clean, C faults in several tiles, B faults early and late in K (different slices), A faults, the
+    requantization epilogue, the printed modulus, errCount as a counter - and the same shapes unsplit, which is
+    what a workspace without room for the partial tiles gets."""
+    import torch
+    say(f"split-K across workgroups: {M}x{N}x{K}")
+    A, B = operands(M, N, K, M + 2 * N + K, relu_like=(K % 256 == 0))
+    run = gpu_util.GpuRun(binding, B)
+    ws = binding.Workspace(M, run.Bp)
+    base_bytes = (64 + max(2 * ((M + 63) // 64 * 64), 2 * (32 * 64 + 64))) * 4
+    assert ws.tensor.numel() * 4 > base_bytes, "this shape is meant to be split"
+    small = torch.zeros(base_bytes // 4, dtype=torch.int32, device="cuda")
+
+    class SmallWs:
+        tensor = small
+    ref = oracle.checked_gemm(A, B)
+    for w in (ws, SmallWs):
+        out = run.gemm(A, ws=w)
+        assert np.array_equal(out["C"], ref.C) and not out["flags"].any() and out["err_count"] == 0
+        assert not out["ws"][: base_bytes // 4].any(), "row words and counting words must be left zero"
+        if w is ws:
+            tiles = ((M + 63) // 64) * ((N + 63) // 64)
+            assert not out["ws"][base_bytes // 4: base_bytes // 4 + tiles].any(), "tile tickets must be left zero"
+        out = run.gemm(A, ws=w, check=False)
+        assert np.array_equal(out["C"], ref.C)
+    rng = np.random.default_rng(K + M)
+    inj = [(0, 0, 1 << 31), (M - 1, N - 1, 1), (M // 2, N // 2, 1 << 17), (M // 2, N // 3, 1 << 5), (1, N - 1, 0xFFFF0000)]
+    refi = oracle.checked_gemm(A, B, flips_c=inj)
+    out = run.gemm(A, ws=ws, injections=inj)
+    assert np.array_equal(out["C"], refi.C) and np.array_equal(out["flags"], refi.flags) and out["err_count"] == refi.err_count
+    out = run.gemm(A, ws=ws, injections=inj, accumulate_from=2)
+    assert np.array_equal(out["flags"], refi.flags) and out["err_count"] == 2 + refi.err_count
+    for (k, j, bit) in [(0, 0, 7), (K - 1, N - 1, 0), (K // 2 + 3, N // 2, 6), (K // 4, 5, 3)]:
+        refb = oracle.checked_gemm(A, B, flips_b=[(k, j, bit)])
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        out = run.gemm(A, ws=ws)
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        assert np.array_equal(out["C"], refb.C) and np.array_equal(out["flags"], refb.flags) and out["err_count"] == refb.err_count
+    i, k, bit = int(rng.integers(M)), int(rng.integers(K)), int(rng.integers(8))
+    refa = oracle.checked_gemm(A, B, flips_a=[(i, k, bit)])
+    A2 = A.copy()
+    A2[i, k] ^= np.uint8(1 << bit)
+    out = run.gemm(A2, ws=ws)
+    assert np.array_equal(out["C"], refa.C) and out["err_count"] == 0
+    # a fault in the checksum column late in K: the slice that holds that stage's share shows it
+    S2 = ref.S_B.copy()
+    S2.view(np.uint32)[K - 2] ^= np.uint32(1 << 9)
+    want, n = oracle.compare(ref.rsum, oracle.row_checksum(A, S2))
+    binding.abft_packed_b_flip_checksum_bit(run.Bp, K - 2, 9)
+    out = run.gemm(A, ws=ws)
+    binding.abft_packed_b_flip_checksum_bit(run.Bp, K - 2, 9)
+    assert np.array_equal(out["flags"], want) and out["err_count"] == n
+    # requantization epilogue, with and without C
+    mult = wlmod.draw_mult(rng, N, "channel")
+    bias = rng.integers(-3000, 3000, size=N).astype(np.int32)
+    q32 = oracle.requantize(ref.C, ref.colsum, 128, 128, mult, bias, precision="f32")
+    for want_c in (True, False):
+        out = run.gemm(A, ws=ws, requant=(128, 128, mult, bias), want_c=want_c)
+        assert np.array_equal(out["Cq"], q32) and out["err_count"] == 0
+    # Algorithm 1 with its printed modulus
+    if K % 16 == 0 and K <= 65536:
+        Cw, fw, nw = oracle.checked_gemm_mod127(A, B, flips_c=inj[:3])
+        out = run.gemm(A, ws=ws, mod127=True, injections=inj[:3])
+        assert np.array_equal(out["C"], Cw) and np.array_equal(out["flags"], fw) and out["err_count"] == nw
+    out = run.gemm(A, ws=ws)
+    assert out["err_count"] == 0 and not out["ws"][: base_bytes // 4].any()

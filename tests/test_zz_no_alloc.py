@@ -32,7 +32,7 @@ def run_both(b, gpu_util, A, B, injections=(), requant=None, mod127=False):
     b.abft_gemm_u8s8s32_checked_static(A_dev, run.Bp, C, flags, cnt, rq=rq, Cq=Cq,
                                        inj=inj, n_inj=len(injections), flags=b.ABFT_MOD127 if mod127 else b.ABFT_CHECK)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_allocated() <= before      # (nothing was allocated through torch; earlier temporaries may have been released)
     got = {"C": C.cpu().numpy(), "flags": flags.cpu().numpy(), "err_count": int(cnt.item()),
            "Cq": None if Cq is None else Cq.cpu().numpy()}
     assert np.array_equal(got["C"], want["C"]), "C differs between the two entry points"
