@@ -361,6 +361,49 @@ def clock_trace(b, torch, args):
     return out
 
 
+def splitk_points(b, torch, steps, count_flag, shapes=((256, 1024, 8192), (128, 128, 16384), (256, 512, 4096))):
+    """Few 64x64 tiles and a long K: the library splits K across workgroups when the workspace has room for the
+    partial tiles; the same launch on a workspace of the row words alone runs unsplit.  Seeded draws on the device."""
+    out = []
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(210300131)
+    for M, N, K in shapes:
+        A = torch.randint(0, 256, (M, K), dtype=torch.uint8, device="cuda", generator=gen)
+        B = torch.randint(-127, 128, (K, N), dtype=torch.int8, device="cuda", generator=gen)
+        Bp = b.abft_pack_b_checksum(B)
+        C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+        flags = torch.empty(M, dtype=torch.int32, device="cuda")
+        cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+        full = b.Workspace(M, Bp).tensor
+        rows_only = torch.zeros(b.lib.abft_gemm_workspace_bytes(M, None) // 4, dtype=torch.int32, device="cuda")
+        n = max(50, min(steps, 400))
+
+        def timed(ws, check):
+            def run():
+                b.abft_gemm_u8s8s32_checked(A, Bp, C, flags, cnt, flags=(b.ABFT_CHECK if check else b.ABFT_NOCHECK) | count_flag,
+                                            workspace=ws)
+            for _ in range(20):
+                run()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for _ in range(n):
+                    run()
+            g.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / n
+        out.append({"M": M, "N": N, "K": K, "split": full.numel() > rows_only.numel(),
+                    "us_checked": timed(full, True), "us_unchecked": timed(full, False),
+                    "us_checked_unsplit": timed(rows_only, True), "us_unchecked_unsplit": timed(rows_only, False)})
+        Bp.destroy()
+    return out
+
+
 CALIB_COPY_BYTES = 256 << 20
 GEMM_KERNEL_TAGS = ("gemm_tile_async_kernel", "gemm_tile_kernel", "gemm_smallm_kernel")
 
@@ -712,6 +755,9 @@ def main():
             out["configs"].append(r)
         torch.cuda.empty_cache()
         out["smallm_sweep"] = smallm_sweep(b, torch, args.steps, args.warmup, 0 if args.overwrite_count else b.ABFT_ERRCOUNT_ACCUMULATE)
+        out["splitk"] = splitk_points(b, torch, args.steps, 0 if args.overwrite_count else b.ABFT_ERRCOUNT_ACCUMULATE)
+        out["splitk_note"] = ("few 64x64 tiles, long K: K split across workgroups (chosen from about forty 128-k stages on) against the same "
+                              "launch unsplit (a workspace without room for the partial tiles); the third shape sits below the threshold")
         out["smallm_sweep_note"] = ("streaming kernel, M = 16, weights of growing size rotated through >= 768 MiB of packed "
                                     "copies (nothing served from cache): algorithmic bytes / time against 8 TB/s")
     if not args.no_eb:
