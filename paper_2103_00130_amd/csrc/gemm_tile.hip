@@ -52,7 +52,7 @@ hipError_t launch_gemm_tile(int variant, bool check, bool want_c, bool want_q, c
             }
             if (tiles <= 256 && p.K >= 2048) return launch_gemm_tile_a64r8(check, want_c, want_q, p, s);
             // short K on such a grid: a ring of four stages, all in flight before the first k-step, instead of the
-            // double buffer whose every stage waits out a trip to memory (256x512x1024: 6.7 -> see the measurements)
+            // double buffer whose every stage waits out a trip to memory (a few tenths of a microsecond at 256x512x1024)
             if (tiles <= 256 && p.K > 256) return launch_gemm_tile_a64r4(check, want_c, want_q, p, s);
             return launch_gemm_tile_a64(check, want_c, want_q, p, s);
         }
