@@ -611,6 +611,54 @@ def test_k_split_between_wavefront_groups(binding, gpu_util, oracle, M, N, K):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("M,N,K", [(200, 130, 2064), (64, 64, 2048), (130, 200, 3008), (320, 1000, 4096), (1000, 1024, 2176), (70, 190, 4112)])
+def test_small_grid_long_k_every_feature(binding, gpu_util, oracle, M, N, K):
+    """At most 256 tiles of 64x64 and K of sixteen stages or more (the kernels with deep stage rings and K split
+    inside the workgroup): odd and even numbers of stages, a K that ends inside the last stage, shares of the checksum
+    product of one and two stages and empty ones, ragged M and N, injections in every quadrant of a tile, faults in the
+    weight early, late and in the middle of K and in the checksum column, both outputs with requantization, the
+    unchecked launch, the check modulo 127."""
+    say(f"small grid, long K, every feature {M}x{N}x{K}")
+    A, B = operands(M, N, K, 11 * M + N + K, full_range_b=False)
+    inj = [(M - 1, N - 1, 1 << 29), (0, 0, 1 << 3), (M // 2, N // 2, 0x00400000), (40, 10, 1 << 31), (5, 50, 1 << 12)]
+    ref = oracle.checked_gemm(A, B, flips_c=inj)
+    run = gpu_util.GpuRun(binding, B)
+    out = run.gemm(A, variant="tile64", injections=inj)
+    assert np.array_equal(out["C"], ref.C) and np.array_equal(out["flags"], ref.flags)
+    assert out["err_count"] == ref.err_count == len(set(r for r, _, _ in inj)) and not out["ws"].any()
+    auto = run.gemm(A)
+    clean = oracle.checked_gemm(A, B)
+    assert np.array_equal(auto["C"], clean.C) and auto["err_count"] == 0 and not auto["flags"].any()
+    unchecked = run.gemm(A, variant="tile64", check=False)
+    assert np.array_equal(unchecked["C"], clean.C)
+    rng = np.random.default_rng(K)
+    mult = wlmod.draw_mult(rng, N, "channel")
+    bias = rng.integers(-5000, 5000, size=N).astype(np.int32)
+    q = run.gemm(A, variant="tile64", requant=(128, 128, mult, bias))
+    assert np.array_equal(q["C"], clean.C)
+    assert np.array_equal(q["Cq"], oracle.requantize(clean.C, clean.colsum, 128, 128, mult, bias, precision="f32"))
+    assert q["err_count"] == 0
+    C127, flags127, count127 = oracle.checked_gemm_mod127(A, B, flips_c=inj)
+    out127 = run.gemm(A, variant="tile64", injections=inj, mod127=True)
+    assert np.array_equal(out127["C"], C127) and np.array_equal(out127["flags"], flags127) and out127["err_count"] == count127
+    for k, j, bit in ((5, N // 3, 6), (K - 3, N - 1, 2), (K // 2 + 33, 0, 7)):
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        refb = oracle.checked_gemm(A, B, flips_b=[(k, j, bit)])
+        outb = run.gemm(A, variant="tile64")
+        assert np.array_equal(outb["C"], refb.C) and np.array_equal(outb["flags"], refb.flags) and outb["err_count"] == refb.err_count
+        binding.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+    # a fault in the checksum column itself: every row whose A entry at that k is not zero is flagged, C is clean
+    k = K // 3
+    S2 = oracle.b_checksum(B)
+    S2.view(np.uint32)[k] ^= np.uint32(1 << 9)
+    want, n = oracle.compare(oracle.row_sums(clean.C), oracle.row_checksum(A, S2))
+    binding.abft_packed_b_flip_checksum_bit(run.Bp, k, 9)
+    outc = run.gemm(A, variant="tile64")
+    binding.abft_packed_b_flip_checksum_bit(run.Bp, k, 9)
+    assert np.array_equal(outc["C"], clean.C) and np.array_equal(outc["flags"], want) and outc["err_count"] == n and n > 0
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("M,N,K,variant", [(100, 64, 8320, "tile64"), (300, 256, 12288, "tile256"), (130, 128, 4224, "tile128")])
 def test_long_checksum_share(binding, gpu_util, oracle, M, N, K, variant):
     """One tile column and a long K: its share of the checksum product is longer than one lot of
