@@ -275,6 +275,62 @@ def test_paper_shaped_workloads_full_size(binding, gpu_util, oracle, cfg):
     want[wl.M - 1] = 1
     assert np.array_equal(out["flags"], want) and out["err_count"] == 1
     assert out["C"][wl.M - 1, wl.N - 1] == np.int32(np.uint32(ref.C[wl.M - 1, wl.N - 1]) ^ np.uint32(1 << 31))
+    # errCount as a counter that is added to, which is how the benchmark launches it
+    acc = run.gemm(ops.A, requant=rq, accumulate_from=5)
+    assert np.array_equal(acc["C"], ref.C) and not acc["flags"].any() and acc["err_count"] == 5
+    if rq is not None:
+        assert np.array_equal(acc["Cq"], q32)
+    acc = run.gemm(ops.A, requant=rq, injections=inj, accumulate_from=5)
+    assert np.array_equal(acc["flags"], want) and acc["err_count"] == 6
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 520, 1536), (16, 4096, 2048), (256, 512, 8192)])
+def test_graph_replays_match_oracle(binding, gpu_util, oracle, M, N, K):
+    """Three checked launches captured in a graph (tiled kernel with row words, streaming kernel, K split across
+    workgroups), replayed several times with eager work between the replays: every replay is compared with the
+    oracle, clean and with a fault planted in the weight between two replays (the graph itself is unchanged)."""
+    import torch
+    say(f"graph replays {M}x{N}x{K}")
+    b = binding
+    A, B = operands(M, N, K, 13 * M + N + K, full_range_b=False)
+    run = gpu_util.GpuRun(b, B)
+    A_dev = gpu_util.dev(A)
+    C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    flags = torch.empty(M, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = b.Workspace(M, run.Bp)
+    def launch():
+        b.abft_gemm_u8s8s32_checked(A_dev, run.Bp, C, flags, cnt, flags=b.ABFT_CHECK | b.ABFT_ERRCOUNT_ACCUMULATE, workspace=ws.tensor)
+    launch()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(3):
+            launch()
+    clean = oracle.checked_gemm(A, B)
+    k, j, bit = K // 2 + 1, N // 3, 5
+    hit = oracle.checked_gemm(A, B, flips_b=[(k, j, bit)])
+    assert hit.err_count > 0
+    for rep in range(4):
+        faulty = rep in (1, 3)
+        if faulty:
+            b.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        C.fill_(-3)
+        flags.fill_(-3)
+        cnt.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        want = hit if faulty else clean
+        assert np.array_equal(C.cpu().numpy(), want.C), f"replay {rep}"
+        assert np.array_equal(flags.cpu().numpy(), want.flags), f"replay {rep}"
+        assert int(cnt.item()) == 3 * want.err_count, f"replay {rep}"
+        if faulty:
+            b.abft_packed_b_flip_bit(run.Bp, k, j, bit)
+        # eager work between the replays: an unrelated checked launch through the same workspace
+        launch()
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy(), clean.C)
 
 
 def test_deterministic_across_runs(binding, gpu_util):
